@@ -1,0 +1,200 @@
+"""ctypes front end of the C oracle (``ngc_oracle.c``) plus the few host-integer
+parts of the method that need no C (keep counts, cache-size trajectory).
+
+TEST INFRASTRUCTURE ONLY -- see the header of ``ngc_oracle.c``.  All arrays are
+numpy; bf16 tensors travel as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from fractions import Fraction
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ngc_oracle.c")
+_SO = os.path.join(_HERE, "libngc_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Contraction is off so that the defined
+    logarithm is the stated operation sequence and nothing else."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        u32p, i32p, f32p, u16p = (C.POINTER(C.c_uint32), C.POINTER(C.c_int32),
+                                  C.POINTER(C.c_float), C.POINTER(C.c_uint16))
+        lib.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        lib.orc_philox4x32_10.restype = None
+        lib.orc_item_word.argtypes = [C.c_uint64] + [C.c_uint32] * 5
+        lib.orc_item_word.restype = C.c_uint32
+        lib.orc_log.argtypes = [C.c_double]
+        lib.orc_log.restype = C.c_double
+        lib.orc_gumbel_u32.argtypes = [C.c_uint32]
+        lib.orc_gumbel_u32.restype = C.c_double
+        lib.orc_perturbed_keys.argtypes = [f32p, C.c_int32, C.c_float, C.c_uint64,
+                                           C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, f32p]
+        lib.orc_perturbed_keys.restype = None
+        lib.orc_select.argtypes = [f32p, C.c_int32, C.c_int32, i32p, i32p]
+        lib.orc_select.restype = C.c_int
+        for name in ("orc_logprob_literal", "orc_logprob_suffix"):
+            fn = getattr(lib, name)
+            fn.argtypes = [f32p, C.c_int32, i32p, C.c_int32]
+            fn.restype = C.c_double
+        lib.orc_compact_rows.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32]
+        lib.orc_compact_rows.restype = C.c_int32
+        lib.orc_compact_i32.argtypes = [i32p, i32p, C.c_int32, C.c_int32, i32p, C.c_int32]
+        lib.orc_compact_i32.restype = C.c_int32
+        lib.orc_decode_attn.argtypes = [u16p, u16p, u16p, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_double, f32p]
+        lib.orc_decode_attn.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _arr(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+# ---------------------------------------------------------------- RNG -----
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = _arr(ctr, np.uint32)
+    k = _arr(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    _L().orc_philox4x32_10(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def item_word(seed: int, rnd: int, l: int, b: int, hsel: int, t: int) -> int:
+    return int(_L().orc_item_word(seed, rnd, l, b, hsel, t))
+
+
+def defined_log(x: float) -> float:
+    return float(_L().orc_log(float(x)))
+
+
+def gumbel_u32(r: int) -> float:
+    return float(_L().orc_gumbel_u32(int(r)))
+
+
+# ------------------------------------------------------------- sampling ---
+
+def perturbed_keys(logits, tau: float, seed: int, rnd: int, l: int, b: int, hsel: int) -> np.ndarray:
+    s = _arr(logits, np.float32)
+    keys = np.empty_like(s)
+    _L().orc_perturbed_keys(_p(s, C.c_float), s.size, tau, seed, rnd, l, b, hsel, _p(keys, C.c_float))
+    return keys
+
+
+def select(keys, K: int):
+    k = _arr(keys, np.float32)
+    kept = np.empty(K, np.int32)
+    sigma = np.empty(K, np.int32)
+    rc = _L().orc_select(_p(k, C.c_float), k.size, K, _p(kept, C.c_int32), _p(sigma, C.c_int32))
+    if rc != 0:
+        raise ValueError("orc_select: bad arguments or NaN key")
+    return kept, sigma
+
+
+def evict_select(logits, K: int, tau: float, seed: int, rnd: int, l: int, b: int, hsel: int):
+    """Sample which K items of one segment survive: (kept ascending, sigma in
+    sampled order)."""
+    return select(perturbed_keys(logits, tau, seed, rnd, l, b, hsel), K)
+
+
+# ------------------------------------------------------------- log-prob ---
+
+def logprob_literal(logits, sigma) -> float:
+    s = _arr(logits, np.float32)
+    sg = _arr(sigma, np.int32)
+    return float(_L().orc_logprob_literal(_p(s, C.c_float), s.size, _p(sg, C.c_int32), sg.size))
+
+
+def logprob_suffix(logits, sigma) -> float:
+    s = _arr(logits, np.float32)
+    sg = _arr(sigma, np.int32)
+    return float(_L().orc_logprob_suffix(_p(s, C.c_float), s.size, _p(sg, C.c_int32), sg.size))
+
+
+# ------------------------------------------------------------ compaction --
+
+def compact_rows(rows_u16, kept, block: int = 1) -> np.ndarray:
+    """rows_u16: [n, D] uint16.  Returns the packed surviving rows [n_new, D]."""
+    src = _arr(rows_u16, np.uint16)
+    n, D = src.shape
+    kp = _arr(kept, np.int32)
+    dst = np.zeros_like(src)
+    n_new = _L().orc_compact_rows(_p(src, C.c_uint16), _p(dst, C.c_uint16), n, D, block,
+                                  _p(kp, C.c_int32), kp.size)
+    return dst[:n_new].copy()
+
+
+def compact_i32(vals, kept, block: int = 1) -> np.ndarray:
+    src = _arr(vals, np.int32)
+    kp = _arr(kept, np.int32)
+    dst = np.zeros_like(src)
+    n_new = _L().orc_compact_i32(_p(src, C.c_int32), _p(dst, C.c_int32), src.size, block,
+                                 _p(kp, C.c_int32), kp.size)
+    return dst[:n_new].copy()
+
+
+# ------------------------------------------------------------- attention --
+
+def decode_attn(q_u16, k_u16, v_u16, scale: float) -> np.ndarray:
+    """q: [G, D], k, v: [n, D] (bf16 bit patterns).  Returns fp32 [G, D]."""
+    q = _arr(q_u16, np.uint16)
+    k = _arr(k_u16, np.uint16)
+    v = _arr(v_u16, np.uint16)
+    G, D = q.shape
+    n = k.shape[0]
+    assert k.shape == v.shape and (n == 0 or k.shape[1] == D)
+    out = np.zeros((G, D), np.float32)
+    _L().orc_decode_attn(_p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16), n, G, D,
+                         float(scale), _p(out, C.c_float))
+    return out
+
+
+# ------------------------------------------------- host-integer schedule --
+
+def keep_count(n: int, num: int, den: int) -> int:
+    """Items kept out of n at retention rate num/den (= 1 - eviction rate):
+    the ceiling, at least 1 and at most n (Sec. 4.1 leaves the rounding open)."""
+    if n <= 0:
+        return 0
+    k = -((-n * num) // den)
+    return max(1, min(n, k))
+
+
+def trajectory_fraction(c0: int, delta: int, num: int, den: int, rounds: int):
+    """Cache sizes immediately before each eviction round when every round
+    keeps the fraction num/den of the cache and delta tokens follow
+    (Appendix A.2: c_{t+1} = (1 - eps) c_t + delta)."""
+    sizes, c = [], c0
+    for _ in range(rounds):
+        sizes.append(c)
+        c = keep_count(c, num, den) + delta
+    return sizes
+
+
+def steady_state(delta: int, num: int, den: int) -> Fraction:
+    """Fixed point delta / eps of the recursion above (Appendix A.2)."""
+    eps = 1 - Fraction(num, den)
+    return Fraction(delta) / eps

@@ -1,0 +1,113 @@
+"""Pins for the oracle's subset log-probability (Eq. 2 of the paper)."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import gammaln, log_softmax, logsumexp
+
+import oracle as orc
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 7, 8])
+def test_ordered_probabilities_sum_to_one(n):
+    rng = np.random.default_rng(n)
+    s = (2.0 * rng.standard_normal(n)).astype(np.float32)
+    for K in range(0, n + 1):
+        if n == 8 and K not in (0, 1, 2, 3, 8):
+            continue            # 8!/(8-K)! grows fast; the ends and small K cover the n=8 case
+        total = 0.0
+        for seq in itertools.permutations(range(n), K):
+            total += math.exp(orc.logprob_literal(s, seq))
+        assert total == pytest.approx(1.0, abs=1e-10), (n, K)
+
+
+def test_single_pick_is_log_softmax():
+    rng = np.random.default_rng(10)
+    s = rng.standard_normal(50).astype(np.float32)
+    ls = log_softmax(s.astype(np.float64))
+    for t in (0, 7, 49):
+        assert orc.logprob_literal(s, [t]) == pytest.approx(ls[t], rel=1e-13)
+        assert orc.logprob_suffix(s, [t]) == pytest.approx(ls[t], rel=1e-13)
+
+
+def test_equal_logits_closed_form():
+    # every ordered K-sequence of n equally likely items has probability (n-K)!/n!
+    for n, K in ((5, 2), (40, 40), (1000, 333), (4096, 1366)):
+        s = np.full(n, 0.37, np.float32)
+        sigma = np.random.default_rng(n).permutation(n)[:K]
+        want = gammaln(n - K + 1) - gammaln(n + 1)
+        assert orc.logprob_suffix(s, sigma) == pytest.approx(want, rel=1e-12)
+        if n * K <= 2_000_000:
+            assert orc.logprob_literal(s, sigma) == pytest.approx(want, rel=1e-12)
+
+
+def test_two_step_example_by_hand():
+    # n = 3, picks (2, 0): p = e^{s2}/(e^{s0}+e^{s1}+e^{s2}) * e^{s0}/(e^{s0}+e^{s1})
+    s = np.array([0.5, -1.0, 2.0], np.float32)
+    e = np.exp(s.astype(np.float64))
+    want = math.log(e[2] / e.sum()) + math.log(e[0] / (e[0] + e[1]))
+    assert orc.logprob_literal(s, [2, 0]) == pytest.approx(want, rel=1e-13)
+    # the order matters (it is the probability of a sequence, not of a set)
+    other = math.log(e[0] / e.sum()) + math.log(e[2] / (e[1] + e[2]))
+    assert orc.logprob_literal(s, [0, 2]) == pytest.approx(other, rel=1e-13)
+    assert abs(want - other) > 1e-3
+
+
+def test_shift_invariance_and_literal_equals_suffix():
+    rng = np.random.default_rng(11)
+    for n, K in ((9, 9), (300, 120), (2048, 1024)):
+        s = rng.standard_normal(n).astype(np.float64)
+        sigma = rng.permutation(n)[:K]
+        a = orc.logprob_literal(s.astype(np.float32), sigma)
+        b = orc.logprob_suffix(s.astype(np.float32), sigma)
+        assert a == pytest.approx(b, rel=1e-12)
+        # shift by a power of two so that the fp32 logits shift exactly
+        s32 = (np.round(s * 1024) / 1024).astype(np.float32)
+        c = orc.logprob_suffix(s32, sigma)
+        d = orc.logprob_suffix(s32 + np.float32(8.0), sigma)
+        assert c == pytest.approx(d, rel=1e-12)
+
+
+def test_against_independent_numpy_evaluation():
+    # Eq. 2 re-evaluated with scipy's logsumexp over explicit remaining sets
+    rng = np.random.default_rng(12)
+    n, K = 200, 77
+    s = (3 * rng.standard_normal(n)).astype(np.float32)
+    sigma = rng.permutation(n)[:K]
+    alive = np.ones(n, bool)
+    want = 0.0
+    for j in sigma:
+        want += float(s[j]) - logsumexp(s[alive].astype(np.float64))
+        alive[j] = False
+    assert orc.logprob_literal(s, sigma) == pytest.approx(want, rel=1e-13)
+    assert orc.logprob_suffix(s, sigma) == pytest.approx(want, rel=1e-13)
+
+
+def test_heavy_tails_do_not_cancel():
+    # a few huge logits picked first: the removed mass is ~1 after two picks; the
+    # reverse running sum must still agree with the literal form
+    rng = np.random.default_rng(13)
+    n, K = 500, 200
+    s = rng.standard_normal(n).astype(np.float32)
+    s[[3, 100, 250]] = [38.0, 31.0, 25.0]
+    keys = s.copy()
+    order = np.argsort(-keys, kind="stable")[:K]
+    a = orc.logprob_literal(s, order)
+    b = orc.logprob_suffix(s, order)
+    assert a == pytest.approx(b, rel=1e-12)
+    assert np.isfinite(a)
+
+
+def test_full_permutation_of_everything():
+    # K = n: the unpicked mass is zero and the last factor is exactly 1
+    s = np.array([0.1, 0.2, -0.3, 1.0], np.float32)
+    e = np.exp(s.astype(np.float64))
+    seq = [3, 1, 0, 2]
+    want, rem = 0.0, e.sum()
+    for i in seq:
+        want += math.log(e[i] / rem)
+        rem -= e[i]
+    assert orc.logprob_literal(s, seq) == pytest.approx(want, rel=1e-12)
+    assert orc.logprob_suffix(s, seq) == pytest.approx(want, rel=1e-12)
+    assert orc.logprob_suffix(s, []) == 0.0
