@@ -1,0 +1,187 @@
+/*
+ * ngc.h -- C ABI of the MI355X (gfx950) eviction + decode-attention library
+ * for Neural Garbage Collection (NGC).
+ *
+ * The library implements the periodic eviction step of the method and the
+ * decode attention that follows it:
+ *
+ *   ngc_perturbed_keys   logits + Gumbel noise                     (Sec. 4.3)
+ *   ngc_evict            Gumbel-top-k sample of the entries to keep, their
+ *                        ordered-subset log-probability, and in-place removal
+ *                        of everything else                  (Sec. 4.1, 4.3, Eq. 2)
+ *   ngc_subset_logprob   Eq. 2 for caller-supplied sampled actions (Sec. 4.3-4.4)
+ *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
+ *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
+ *                        entries of every sequence               (Sec. 4.1, 4.2)
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless a comment says "host".  The
+ *     structs themselves (ngc_cache, ngc_evict_params) live in HOST memory and
+ *     are read during the call only.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls and never synchronises: each call only enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  Ragged lengths and keep counts are read on the device.
+ *   - Return value: NGC_OK or a negative NGC_E* code; nothing is enqueued when
+ *     an error is returned.  Conditions only the device can see (a keep count
+ *     above the segment size, a length above the capacity, ...) never trap:
+ *     they are clamped and counted in the status words at the start of the
+ *     workspace (see NGC_STATUS_*).
+ *   - A "segment" is one independent selection problem: one (layer, sequence,
+ *     KV head).  Segment id = (layer * B + sequence) * Hkv + head.
+ *   - An "item" is what is kept or evicted as a unit: `block` consecutive rows
+ *     of a segment (the block of Sec. 4.2; block = 1 is one cache position).
+ *     A segment of n rows has ceil(n / block) items, the last possibly short.
+ */
+#ifndef NGC_H
+#define NGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NGC_OK            0
+#define NGC_EINVAL       (-1)  /* null / misaligned pointer, bad shape or parameter        */
+#define NGC_ENOSPC       (-2)  /* workspace too small                                      */
+#define NGC_EHIP         (-3)  /* a HIP call failed (launch, attribute)                    */
+#define NGC_EUNSUPPORTED (-4)  /* valid request outside what the kernels cover (see below) */
+
+/* Status words: int32 counters at the start of the workspace, one per kind of
+ * device-detected anomaly.  The caller zeroes the workspace once; kernels only
+ * add to them.  NGC_STATUS_WORDS words are reserved. */
+#define NGC_STATUS_WORDS        64
+#define NGC_STATUS_KEEP_CLAMPED  0  /* keep[seg] > items (or < 0): clamped                  */
+#define NGC_STATUS_LEN_CLAMPED   1  /* len[seg] > cap (or < 0): clamped                     */
+#define NGC_STATUS_EMPTY_ATTN    2  /* decode attention over an empty segment: zeros        */
+#define NGC_STATUS_APPEND_FULL   3  /* append to a full segment: skipped                    */
+#define NGC_STATUS_BAD_SIGMA     4  /* ngc_subset_logprob: index out of range or repeated   */
+
+/* Non-owning view of a KV cache in device memory.
+ *   k, v : bf16, dense [L][B][Hkv][cap][D], 16-byte aligned.  Rows [0, len) of
+ *          a segment are the surviving entries in ascending order of their
+ *          original position; rows >= len are unspecified.
+ *   len  : int32 [L][B][Hkv], rows in use per segment (ragged).
+ *   pos  : optional int32 [L][B][Hkv][cap], original token index of each row
+ *          (moved together with the rows), or NULL.
+ *   D    : 64 or 128.  Hq must be a multiple of Hkv with Hq / Hkv <= 16.     */
+typedef struct ngc_cache {
+    void    *k;
+    void    *v;
+    int32_t *len;
+    int32_t *pos;
+    int32_t  L, B, Hkv, Hq, D, cap;
+} ngc_cache;
+
+/* Parameters of one eviction round.
+ *   block        rows per item (>= 1).
+ *   share_heads  0: every (layer, sequence, head) draws its own noise;
+ *                1: the head index is left out of the noise counter, so all
+ *                   KV heads of a (layer, sequence) draw the same noise (one
+ *                   decision per layer, Sec. 4.2, when their logits agree too).
+ *   noise_scale  tau: key = logit + tau * Gumbel.  1 = sampling (Sec. 4.3),
+ *                0 = greedy top-k as used at evaluation (Sec. 5.1).
+ *   round        eviction round counter; with `seed` it names the draw, the
+ *                same (seed, round) reproduces the same sample.
+ *   flags        NGC_EVICT_SELECT_ONLY: sample (and score) but move nothing
+ *                and leave `len` untouched.                                   */
+#define NGC_EVICT_SELECT_ONLY 1u
+typedef struct ngc_evict_params {
+    int32_t  block;
+    int32_t  share_heads;
+    float    noise_scale;
+    uint32_t round;
+    uint64_t seed;
+    uint32_t flags;
+    uint32_t reserved;
+} ngc_evict_params;
+
+/* Library version (major * 10000 + minor * 100 + patch). */
+int ngc_version(void);
+
+/* Static, NUL-terminated description of a return code (host memory). */
+const char *ngc_strerror(int code);
+
+/* Bytes of workspace that make every call below succeed for this cache
+ * geometry and up to `max_keep` kept items per segment.  Host computation. */
+size_t ngc_workspace_bytes(const ngc_cache *c, int32_t max_keep);
+
+/* Perturbed keys (Sec. 4.3): for every segment of `layer` (-1 = all layers)
+ * and every item t < ceil(len / block):
+ *     keys[seg][t] = fl32( (double)logits[seg][t] + (double)tau * g ),
+ *     g = -log(-log u),  u = (r + 1/2) 2^-32,
+ *     r = word (t mod 4) of Philox-4x32-10 with key = seed and counter
+ *         (t / 4, sequence, layer * 65536 + head selector, round);
+ * tau == 0 copies the logits.  logits, keys_out: fp32 [L][B][Hkv][cap], item t
+ * of a segment at offset t of its row; entries past the item count are left
+ * untouched.  ws needs NGC_STATUS_WORDS * 4 bytes (status only). */
+int ngc_perturbed_keys(const ngc_cache *c, int32_t layer, const float *logits,
+                       const ngc_evict_params *p, float *keys_out,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/* One eviction round (Sec. 4.1, 4.3) for every segment of `layer` (-1 = all).
+ *   logits    fp32 [L][B][Hkv][cap]; item t of a segment at offset t of its
+ *             row.  NaN is treated as -inf.
+ *   keep      int32 [L][B][Hkv]: items to keep per segment (K).  Values above
+ *             the item count are clamped (a no-op round), below 0 to 0.
+ *   max_keep  row length of kept_out / sigma_out (>= every K that is used).
+ *   kept_out  int32 [L][B][Hkv][max_keep]: kept item indices, ascending.
+ *   sigma_out int32 [L][B][Hkv][max_keep] or NULL: kept item indices in
+ *             sampled order, i.e. by descending perturbed key, equal keys by
+ *             ascending index (the sequence sigma of Eq. 2).
+ *   logp_out  fp32 [L][B][Hkv] or NULL: log-probability of sigma (Eq. 2).
+ * Entries past K of a row of kept_out / sigma_out are unspecified.  Unless
+ * NGC_EVICT_SELECT_ONLY is set, the rows of the kept items are then packed to
+ * the front of their segment in k, v and pos, in ascending order, in place,
+ * and len is updated.  Segments of other layers are not touched.
+ * Limits: ceil(cap / block) <= 16384 items per segment for this entry point
+ * (NGC_EUNSUPPORTED beyond).  ws must hold ngc_workspace_bytes(). */
+int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
+              const int32_t *keep, const ngc_evict_params *p, int32_t max_keep,
+              int32_t *kept_out, int32_t *sigma_out, float *logp_out,
+              void *ws, size_t ws_bytes, void *stream);
+
+/* Eq. 2 for given actions: for each of nseg independent segments
+ *     logp[s] = sum_j ( x[sigma_j] - log sum_{t not in sigma_1..sigma_{j-1}} exp x[t] )
+ * over the first n_items[s] logits of row s.
+ *   logits   fp32 [nseg][logit_stride]
+ *   n_items  int32 [nseg]         items per segment (<= 65536 each)
+ *   sigma    int32 [nseg][sigma_stride], first keep[s] entries used, distinct
+ *   keep     int32 [nseg]
+ *   logp_out fp32 [nseg]
+ * ws needs NGC_STATUS_WORDS * 4 bytes (status only). */
+int ngc_subset_logprob(const float *logits, const int32_t *n_items,
+                       const int32_t *sigma, const int32_t *keep, int32_t nseg,
+                       int64_t logit_stride, int32_t sigma_stride,
+                       float *logp_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Append one new row per (sequence, head) of `layer` (-1 = all layers) at row
+ * len and add 1 to len (Sec. 4.1: between rounds the cache grows as usual).
+ *   k_new, v_new  bf16 [B][Hkv][D]  (or [L][B][Hkv][D] for layer = -1)
+ *   new_pos       int32 [B] token index stored into pos, or NULL
+ * A full segment (len == cap) is skipped and counted. */
+int ngc_cache_append(const ngc_cache *c, int32_t layer, const void *k_new,
+                     const void *v_new, const int32_t *new_pos,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* Decode attention over the surviving entries (Sec. 4.1; scale of Sec. 4.2):
+ * for every sequence b and query head i of `layer` (-1 = all layers), with
+ * h = i / (Hq / Hkv) and n = len[layer][b][h],
+ *     out[b][i][:] = sum_{j<n} softmax_j( scale * <q[b][i], K[h][j]> ) V[h][j][:]
+ *   q    bf16 [B][Hq][D]   (or [L][B][Hq][D] for layer = -1), 16-byte aligned
+ *   out  fp32 same shape
+ *   scale          usually 1 / sqrt(D)
+ *   max_len_hint   an upper bound on len the caller knows (0 = use cap); it
+ *                  only steers how the work is split, never the result.
+ * n == 0 gives zeros (and is counted).  Scores, softmax and accumulation are
+ * fp32.  ws must hold ngc_workspace_bytes(). */
+int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
+                    int32_t max_len_hint, float *out,
+                    void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGC_H */

@@ -1,0 +1,200 @@
+"""Thin ctypes binding of ``libngc.so`` (see ``include/ngc.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch tensors are used as device memory and for the current HIP stream; no
+torch operator takes part in the computation.  There is no CPU fallback: a
+missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+from ._build import LIB_PATH
+
+NGC_OK = 0
+NGC_EINVAL = -1
+NGC_ENOSPC = -2
+NGC_EHIP = -3
+NGC_EUNSUPPORTED = -4
+
+STATUS_WORDS = 64
+STATUS_KEEP_CLAMPED = 0
+STATUS_LEN_CLAMPED = 1
+STATUS_EMPTY_ATTN = 2
+STATUS_APPEND_FULL = 3
+STATUS_BAD_SIGMA = 4
+
+EVICT_SELECT_ONLY = 1
+
+EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
+           "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn")
+
+
+class NgcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class ngc_cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_void_p), ("pos", C.c_void_p),
+                ("L", C.c_int32), ("B", C.c_int32), ("Hkv", C.c_int32), ("Hq", C.c_int32),
+                ("D", C.c_int32), ("cap", C.c_int32)]
+
+
+class ngc_evict_params(C.Structure):
+    _fields_ = [("block", C.c_int32), ("share_heads", C.c_int32), ("noise_scale", C.c_float),
+                ("round", C.c_uint32), ("seed", C.c_uint64), ("flags", C.c_uint32),
+                ("reserved", C.c_uint32)]
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> C.CDLL:
+    """Load the built library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first (python -m paper_2604_18002_amd._build); "
+                           "there is no fallback path")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    cp, pp = C.POINTER(ngc_cache), C.POINTER(ngc_evict_params)
+    lib.ngc_version.argtypes = []
+    lib.ngc_version.restype = C.c_int
+    lib.ngc_strerror.argtypes = [C.c_int]
+    lib.ngc_strerror.restype = C.c_char_p
+    lib.ngc_workspace_bytes.argtypes = [cp, i32]
+    lib.ngc_workspace_bytes.restype = sz
+    lib.ngc_perturbed_keys.argtypes = [cp, i32, vp, pp, vp, vp, sz, vp]
+    lib.ngc_perturbed_keys.restype = C.c_int
+    lib.ngc_evict.argtypes = [cp, i32, vp, vp, pp, i32, vp, vp, vp, vp, sz, vp]
+    lib.ngc_evict.restype = C.c_int
+    lib.ngc_subset_logprob.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp, sz, vp]
+    lib.ngc_subset_logprob.restype = C.c_int
+    lib.ngc_cache_append.argtypes = [cp, i32, vp, vp, vp, vp, sz, vp]
+    lib.ngc_cache_append.restype = C.c_int
+    lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.ngc_decode_attn.restype = C.c_int
+    if path == LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().ngc_strerror(code).decode()
+
+
+def version() -> int:
+    return load_library().ngc_version()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != NGC_OK:
+        raise NgcError(rc, where)
+
+
+@dataclass
+class Cache:
+    """Device buffers of a KV cache (torch tensors as plain memory).
+
+    k, v: bf16 [L, B, Hkv, cap, D]; len: int32 [L, B, Hkv]; pos: int32 [L, B, Hkv, cap] or None."""
+    k: object
+    v: object
+    len: object
+    pos: object
+    Hq: int
+
+    @property
+    def shape(self):
+        L, B, Hkv, cap, D = self.k.shape
+        return L, B, Hkv, cap, D
+
+    def view(self) -> ngc_cache:
+        L, B, Hkv, cap, D = self.k.shape
+        assert self.k.is_contiguous() and self.v.is_contiguous() and self.len.is_contiguous()
+        return ngc_cache(_ptr(self.k), _ptr(self.v), _ptr(self.len), _ptr(self.pos), L, B, Hkv, self.Hq, D, cap)
+
+    @staticmethod
+    def allocate(L, B, Hkv, Hq, D, cap, device="cuda", with_pos=False) -> "Cache":
+        import torch
+        k = torch.zeros(L, B, Hkv, cap, D, dtype=torch.bfloat16, device=device)
+        v = torch.zeros_like(k)
+        ln = torch.zeros(L, B, Hkv, dtype=torch.int32, device=device)
+        pos = torch.zeros(L, B, Hkv, cap, dtype=torch.int32, device=device) if with_pos else None
+        return Cache(k, v, ln, pos, Hq)
+
+
+def make_params(block=1, share_heads=0, noise_scale=1.0, round=0, seed=0, flags=0) -> ngc_evict_params:
+    return ngc_evict_params(block, share_heads, noise_scale, round, seed, flags, 0)
+
+
+def ngc_workspace_bytes(cache: Cache, max_keep: int) -> int:
+    v = cache.view()
+    return int(load_library().ngc_workspace_bytes(C.byref(v), max_keep))
+
+
+def allocate_workspace(cache: Cache, max_keep: int):
+    """A zeroed workspace tensor (uint8) of the size the library asks for."""
+    import torch
+    return torch.zeros(ngc_workspace_bytes(cache, max_keep), dtype=torch.uint8, device=cache.k.device)
+
+
+def read_status(ws):
+    """Status counters at the start of a workspace (copies to host, synchronises)."""
+    return ws[:STATUS_WORDS * 4].view(dtype=_i32()).cpu().tolist()
+
+
+def _i32():
+    import torch
+    return torch.int32
+
+
+def ngc_perturbed_keys(cache: Cache, layer: int, logits, params: ngc_evict_params, keys_out, ws, stream=None):
+    v = cache.view()
+    _check(load_library().ngc_perturbed_keys(C.byref(v), layer, _ptr(logits), C.byref(params), _ptr(keys_out),
+                                             _ptr(ws), ws.numel(), _stream(stream)), "ngc_perturbed_keys")
+
+
+def ngc_evict(cache: Cache, layer: int, logits, keep, params: ngc_evict_params, max_keep: int,
+              kept_out, sigma_out, logp_out, ws, stream=None):
+    v = cache.view()
+    _check(load_library().ngc_evict(C.byref(v), layer, _ptr(logits), _ptr(keep), C.byref(params), max_keep,
+                                    _ptr(kept_out), _ptr(sigma_out), _ptr(logp_out), _ptr(ws), ws.numel(),
+                                    _stream(stream)), "ngc_evict")
+
+
+def ngc_subset_logprob(logits, n_items, sigma, keep, nseg: int, logit_stride: int, sigma_stride: int,
+                       logp_out, ws, stream=None):
+    _check(load_library().ngc_subset_logprob(_ptr(logits), _ptr(n_items), _ptr(sigma), _ptr(keep), nseg,
+                                             logit_stride, sigma_stride, _ptr(logp_out), _ptr(ws), ws.numel(),
+                                             _stream(stream)), "ngc_subset_logprob")
+
+
+def ngc_cache_append(cache: Cache, layer: int, k_new, v_new, new_pos, ws, stream=None):
+    v = cache.view()
+    _check(load_library().ngc_cache_append(C.byref(v), layer, _ptr(k_new), _ptr(v_new), _ptr(new_pos),
+                                           _ptr(ws), ws.numel(), _stream(stream)), "ngc_cache_append")
+
+
+def ngc_decode_attn(cache: Cache, layer: int, q, scale: float, max_len_hint: int, out, ws, stream=None):
+    v = cache.view()
+    _check(load_library().ngc_decode_attn(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
+                                          _ptr(ws), ws.numel(), _stream(stream)), "ngc_decode_attn")

@@ -1,0 +1,449 @@
+// Decode attention over the surviving (compacted, ragged) cache rows on gfx950.
+//
+// One query token per sequence; every KV head serves G = Hq / Hkv query heads.
+// The work is memory bound (each K and V row is read once and used by G
+// queries), so the kernel is built around full-row 16-byte loads and keeps the
+// vector ALU free by running both contractions on the matrix cores with the G
+// query heads padded to a 16-wide tile:
+//
+//   S^T[row][q] = sum_d K[row][d] Q[q][d]     mfma 16x16x32 bf16, A = K rows
+//   O^T[d][q]   = sum_row V[row][d] P[q][row] mfma 16x16x32 bf16, A = V^T
+//
+// Both products put the query head on the lane index (lane % 16), so all
+// soft-max state (running max, running sum, rescale factor) is lane local.
+//
+// Data movement per 32-row tile and wave:
+//   K: 8 (D=128) loads of 16 B per lane, one full row per 16 lanes -> wave
+//      private LDS -> read back in the A-operand layout.
+//   V: loaded straight into the registers that feed the second product.  Lane
+//      (i, kg) loads, for each of the 8 rows that its lane group kg contracts
+//      over, the 16 B holding d = 8i .. 8i+7; eight 2x2 16-bit transposes turn
+//      them into the eight A operands for the d-tiles {8i + c}.  No LDS.
+//   P is split into a bf16 head and a bf16 remainder (two MFMAs) so the second
+//      product is accurate to ~2^-16 relative, not bf16's 2^-8.
+//
+// Long segments are split over several workgroups (flash-decode); each writes
+// an unnormalised partial (max, sum, O) and a second kernel merges them.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/ngc.h"
+#include "ngc_device.h"
+
+namespace ngc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// 2^x by the hardware instruction (-inf -> 0); inputs here are <= 0 or small.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr int ATT_WAVES = 4;
+constexpr int ATT_TILE = 32;   // rows per wave step
+
+struct AttnArgs {
+    const unsigned char *k;
+    const unsigned char *v;
+    const int32_t *len;
+    const unsigned char *q;
+    float *out;
+    float *part_o;    // [nseg_launch][S][G][D]
+    float *part_ml;   // [nseg_launch][S][G][2]
+    int32_t *status;
+    int seg0;         // first segment of the launch
+    int lb0;          // (layer * B + sequence) that q[0] / out[0] belong to
+    int S;            // splits per segment
+    int G, Hkv, cap;
+    float scale_log2e;
+};
+
+// Tiles [t_lo, t_hi) of split s when `tiles` tiles are cut into at most S
+// nearly equal runs; s_eff = number of non-empty splits.
+__device__ __forceinline__ void split_range(int tiles, int S, int s, int &t_lo, int &t_hi, int &s_eff)
+{
+    const int per = (tiles + S - 1) / S;
+    s_eff = per > 0 ? (tiles + per - 1) / per : 0;
+    t_lo = s * per;
+    t_hi = t_lo + per < tiles ? t_lo + per : tiles;
+}
+
+template <int D>
+__global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs a)
+{
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int DPL = D / 16;                 // bf16 per lane in a V row (8 or 4)
+    constexpr int KCH = D / 32;                 // 32-wide d chunks of the first product
+    constexpr int LROW = ROW_BYTES + 16;        // padded LDS row
+    constexpr int K_LOADS = ATT_TILE * ROW_BYTES / (64 * 16);   // 16-B loads per lane per K tile
+    constexpr int K_PIECES = ROW_BYTES / 16;    // lanes per K row
+    constexpr int K_ROWS_PER_LOAD = 64 / K_PIECES;
+    constexpr int WAVE_LDS = ATT_TILE * LROW;
+
+    __shared__ __align__(16) unsigned char lds[ATT_WAVES * WAVE_LDS];
+    __shared__ float red_m[ATT_WAVES][16];
+    __shared__ float red_l[ATT_WAVES][16];
+    __shared__ float fin_l[16];
+
+    const int lane = lane_id(), wv = wave_id();
+    const int li = lane & 15, kg = lane >> 4;
+    const int seg_local = blockIdx.x / a.S;
+    const int seg = a.seg0 + seg_local;
+    const int split = blockIdx.x - seg_local * a.S;
+    const int G = a.G;
+
+    int n = a.len[seg];
+    if (n < 0 || n > a.cap) {
+        if (threadIdx.x == 0 && split == 0) atomicAdd(&a.status[NGC_STATUS_LEN_CLAMPED], 1);
+        n = n < 0 ? 0 : a.cap;
+    }
+    const int h = seg % a.Hkv;
+    const int lb = seg / a.Hkv - a.lb0;   // (layer * B + sequence) relative to q / out
+    float *out_seg = a.out + ((size_t)lb * a.Hkv + h) * G * D;   // [G][D] of this KV head
+
+    if (n == 0) {
+        if (split == 0) {
+            for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) out_seg[i] = 0.f;
+            if (threadIdx.x == 0) atomicAdd(&a.status[NGC_STATUS_EMPTY_ATTN], 1);
+        }
+        return;
+    }
+    const int tiles = (n + ATT_TILE - 1) / ATT_TILE;
+    int t_lo, t_hi, s_eff;
+    split_range(tiles, a.S, split, t_lo, t_hi, s_eff);
+    if (t_lo >= t_hi) return;   // whole workgroup: nothing to do for this split
+
+    const unsigned char *kseg = a.k + (size_t)seg * a.cap * ROW_BYTES;
+    const unsigned char *vseg = a.v + (size_t)seg * a.cap * ROW_BYTES;
+
+    // B operand of the first product: Q[q = li][32c + 8kg .. +7], zero for q >= G
+    bf16x8 qop[KCH];
+    {
+        const unsigned char *qrow = a.q + ((size_t)lb * a.Hkv * G + (size_t)h * G + li) * ROW_BYTES;
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (li < G) w = *reinterpret_cast<const u32x4 *>(qrow + c * 64 + kg * 16);
+            qop[c] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    f32x4 oacc[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) oacc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    unsigned char *wlds = lds + wv * WAVE_LDS;
+    const int last_row = n - 1;
+
+    // rows this lane loads, relative to the tile: K in full-row order, V in the
+    // order its lane group contracts over (matches the layout of the scores)
+    int vrow_rel[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vrow_rel[e] = (e < 4) ? (4 * kg + e) : (16 + 4 * kg + (e - 4));
+
+    u32x4 kbuf[K_LOADS];
+    u32x4 vbuf4[8];   // D = 128: 16 B per row; D = 64: low 8 B used
+    auto load_tile = [&](int tile) {
+        const int row0 = tile * ATT_TILE;
+#pragma unroll
+        for (int r = 0; r < K_LOADS; ++r) {
+            int row = row0 + r * K_ROWS_PER_LOAD + lane / K_PIECES;
+            row = row < last_row ? row : last_row;
+            kbuf[r] = *reinterpret_cast<const u32x4 *>(kseg + (size_t)row * ROW_BYTES + (lane % K_PIECES) * 16);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int row = row0 + vrow_rel[e];
+            row = row < last_row ? row : last_row;
+            const unsigned char *p = vseg + (size_t)row * ROW_BYTES + li * (DPL * 2);
+            if constexpr (DPL == 8) {
+                vbuf4[e] = *reinterpret_cast<const u32x4 *>(p);
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2 *>(p);
+                vbuf4[e] = u32x4{t[0], t[1], 0u, 0u};
+            }
+        }
+    };
+
+    int tile = t_lo + wv;
+    if (tile < t_hi) load_tile(tile);
+    for (; tile < t_hi; tile += ATT_WAVES) {
+        // ---- stage K through LDS, keep V in registers ---------------------
+        u32x4 vcur[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vcur[e] = vbuf4[e];
+#pragma unroll
+        for (int r = 0; r < K_LOADS; ++r) {
+            const int rl = r * K_ROWS_PER_LOAD + lane / K_PIECES;
+            *reinterpret_cast<u32x4 *>(wlds + rl * LROW + (lane % K_PIECES) * 16) = kbuf[r];
+        }
+        const int row0 = tile * ATT_TILE;
+        if (tile + ATT_WAVES < t_hi) load_tile(tile + ATT_WAVES);   // prefetch the next tile
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- scores: two 16-row tiles ------------------------------------
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) {
+            const u32x4 a0 = *reinterpret_cast<const u32x4 *>(wlds + li * LROW + c * 64 + kg * 16);
+            const u32x4 a1 = *reinterpret_cast<const u32x4 *>(wlds + (16 + li) * LROW + c * 64 + kg * 16);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qop[c], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qop[c], s1, 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // lane (q = li, kg) now holds rows 4kg+r (s0[r]) and 16+4kg+r (s1[r])
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float sc = (e < 4) ? s0[e] : s1[e - 4];
+            x[e] = (row0 + vrow_rel[e] < n) ? sc * a.scale_log2e : -INFINITY;
+        }
+        float tmax = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, x[e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, NGC_WAVE));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NGC_WAVE));
+        const float m_new = fmaxf(m_run, tmax);           // finite: a tile has a valid row
+        const float alpha = fast_exp2(m_run - m_new);         // 0 on the first tile
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = fast_exp2(x[e] - m_new);
+            psum += p[e];
+        }
+        l_run = l_run * alpha + psum;   // lane-local part; lane groups are summed at the end
+        m_run = m_new;
+#pragma unroll
+        for (int c = 0; c < DPL; ++c) oacc[c] *= alpha;
+
+        // ---- P as bf16 head + bf16 remainder (B operands) -----------------
+        uint32_t ph[4], pl[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t b0 = __float_as_uint(p[2 * e2]), b1 = __float_as_uint(p[2 * e2 + 1]);
+            const float r0 = p[2 * e2] - __uint_as_float(b0 & 0xFFFF0000u);
+            const float r1 = p[2 * e2 + 1] - __uint_as_float(b1 & 0xFFFF0000u);
+            ph[e2] = (b0 >> 16) | (b1 & 0xFFFF0000u);
+            pl[e2] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+        }
+        const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
+        const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
+
+        // ---- O^T += V^T P --------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < DPL; ++c) {
+            uint32_t va[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const uint32_t w0 = vcur[2 * e2][c >> 1];       // row e = 2*e2,   d pair c/2
+                const uint32_t w1 = vcur[2 * e2 + 1][c >> 1];   // row e = 2*e2+1
+                va[e2] = (c & 1) ? ((w0 >> 16) | (w1 & 0xFFFF0000u))
+                                 : ((w0 & 0xFFFFu) | (w1 << 16));
+            }
+            const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{va[0], va[1], va[2], va[3]});
+            oacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi, oacc[c], 0, 0, 0);
+            oacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo, oacc[c], 0, 0, 0);
+        }
+    }
+
+    // ---- merge the waves of this workgroup ----------------------------------
+    l_run += __shfl_xor(l_run, 16, NGC_WAVE);
+    l_run += __shfl_xor(l_run, 32, NGC_WAVE);
+    if (kg == 0) { red_m[wv][li] = m_run; red_l[wv][li] = l_run; }
+    __syncthreads();   // also: every wave is done with its K staging area
+    float m_all = red_m[0][li];
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) m_all = fmaxf(m_all, red_m[w][li]);
+    float l_all = 0.f;
+#pragma unroll
+    for (int w = 0; w < ATT_WAVES; ++w) {
+        const float mw = red_m[w][li];
+        l_all += (mw == -INFINITY) ? 0.f : red_l[w][li] * fast_exp2(mw - m_all);
+    }
+    const float f = (m_run == -INFINITY) ? 0.f : fast_exp2(m_run - m_all);
+    if (wv == 0 && kg == 0) fin_l[li] = l_all;
+    // O of every wave, scaled to the common max, into LDS as [wave][q][D] fp32
+    // (the K staging area is free now and large enough)
+    static_assert(ATT_WAVES * 16 * D * 4 <= ATT_WAVES * WAVE_LDS, "staging area too small");
+    float *ost = reinterpret_cast<float *>(lds);
+    // lane (q = li, kg), register (c, r) holds d = DPL * (4kg + r) + c
+    if (li < G) {
+#pragma unroll
+        for (int c = 0; c < DPL; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                ost[(wv * 16 + li) * D + DPL * (4 * kg + r) + c] = oacc[c][r] * f;
+    }
+    __syncthreads();
+    const bool direct = (s_eff == 1);   // the only split of its segment: finish here
+    float *dst_o = direct ? out_seg : a.part_o + ((size_t)seg_local * a.S + split) * G * D;
+    for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
+        const int qi = i / D, d = i - qi * D;
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) acc += ost[(w * 16 + qi) * D + d];
+        if (direct) acc /= fin_l[qi];
+        dst_o[i] = acc;
+    }
+    if (!direct && wv == 0 && kg == 0 && li < G) {
+        float *ml = a.part_ml + (((size_t)seg_local * a.S + split) * G + li) * 2;
+        ml[0] = m_all;
+        ml[1] = l_all;
+    }
+}
+
+// Merge of the split partials: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+template <int D>
+__global__ __launch_bounds__(256) void decode_combine_kernel(AttnArgs a)
+{
+    const int seg_local = blockIdx.x;
+    const int seg = a.seg0 + seg_local;
+    const int G = a.G;
+    int n = a.len[seg];
+    n = n < 0 ? 0 : (n > a.cap ? a.cap : n);
+    const int tiles = (n + ATT_TILE - 1) / ATT_TILE;
+    int t_lo, t_hi, s_eff;
+    split_range(tiles, a.S, 0, t_lo, t_hi, s_eff);
+    if (s_eff <= 1) return;   // written directly by the first kernel (or empty)
+    const int h = seg % a.Hkv;
+    const int lb = seg / a.Hkv - a.lb0;
+    float *out_seg = a.out + ((size_t)lb * a.Hkv + h) * G * D;
+    const float *po = a.part_o + (size_t)seg_local * a.S * G * D;
+    const float *pml = a.part_ml + (size_t)seg_local * a.S * G * 2;
+    for (int i = threadIdx.x; i < G * D; i += 256) {
+        const int qi = i / D;
+        float M = -INFINITY;
+        for (int s = 0; s < s_eff; ++s) M = fmaxf(M, pml[(s * G + qi) * 2]);
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < s_eff; ++s) {
+            const float w = fast_exp2(pml[(s * G + qi) * 2] - M);
+            num += po[(size_t)s * G * D + i] * w;
+            den += pml[(s * G + qi) * 2 + 1] * w;
+        }
+        out_seg[i] = num / den;
+    }
+}
+
+}  // namespace ngc
+
+// ============================================================ host side ====
+
+using namespace ngc;
+
+namespace {
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
+constexpr int TARGET_WORKGROUPS = 4096;
+constexpr int MAX_SPLITS = 64;
+constexpr int MIN_TILES_PER_SPLIT = 2 * ATT_WAVES;   // 256 rows
+
+int splits_for(int nseg_launch, int max_len)
+{
+    int s = (TARGET_WORKGROUPS + nseg_launch - 1) / nseg_launch;
+    const int tiles = (max_len + ATT_TILE - 1) / ATT_TILE;
+    int by_len = tiles / MIN_TILES_PER_SPLIT;
+    if (by_len < 1) by_len = 1;
+    if (s > by_len) s = by_len;
+    if (s > MAX_SPLITS) s = MAX_SPLITS;
+    if (s < 1) s = 1;
+    return s;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// workspace layout: [status][seg_meta: nseg_total * 2 int32][partial O][partial (max, sum)]
+size_t attn_offset(const ngc_cache *c)
+{
+    return align256(STATUS_BYTES + (size_t)c->L * c->B * c->Hkv * 2 * sizeof(int32_t));
+}
+size_t partial_o_bytes(const ngc_cache *c, int nseg_launch, int S)
+{
+    return align256((size_t)nseg_launch * S * (c->Hq / c->Hkv) * c->D * sizeof(float));
+}
+size_t partial_ml_bytes(const ngc_cache *c, int nseg_launch, int S)
+{
+    return align256((size_t)nseg_launch * S * (c->Hq / c->Hkv) * 2 * sizeof(float));
+}
+size_t attn_partial_bytes(const ngc_cache *c, int nseg_launch, int S)
+{
+    return S > 1 ? partial_o_bytes(c, nseg_launch, S) + partial_ml_bytes(c, nseg_launch, S) : 0;
+}
+}  // namespace
+
+extern "C" int ngc_version(void) { return 100; }
+
+extern "C" const char *ngc_strerror(int code)
+{
+    switch (code) {
+    case NGC_OK: return "ok";
+    case NGC_EINVAL: return "invalid argument (null or misaligned pointer, bad shape or parameter)";
+    case NGC_ENOSPC: return "workspace too small";
+    case NGC_EHIP: return "a HIP runtime call failed";
+    case NGC_EUNSUPPORTED: return "request outside the limits of this entry point";
+    default: return "unknown error code";
+    }
+}
+
+extern "C" size_t ngc_workspace_bytes(const ngc_cache *c, int32_t max_keep)
+{
+    (void)max_keep;
+    if (!c || c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return 0;
+    const int per_layer = c->B * c->Hkv;
+    const size_t one = attn_partial_bytes(c, per_layer, splits_for(per_layer, c->cap));
+    const size_t all = attn_partial_bytes(c, per_layer * c->L, splits_for(per_layer * c->L, c->cap));
+    return attn_offset(c) + (one > all ? one : all);
+}
+
+extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
+                               int32_t max_len_hint, float *out,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    if (!c || !c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
+    if (!aligned16(c->k) || !aligned16(c->v) || !aligned16(q) || !aligned16(out) || !aligned16(ws)) return NGC_EINVAL;
+    if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
+    if (c->D != 64 && c->D != 128) return NGC_EINVAL;
+    if (c->Hq % c->Hkv != 0 || c->Hq / c->Hkv > 16) return NGC_EINVAL;
+    if (layer < -1 || layer >= c->L || max_len_hint < 0) return NGC_EINVAL;
+    if (!(scale == scale)) return NGC_EINVAL;
+    const int per_layer = c->B * c->Hkv;
+    const int seg0 = layer < 0 ? 0 : layer * per_layer;
+    const int nseg = layer < 0 ? c->L * per_layer : per_layer;
+    const int max_len = (max_len_hint > 0 && max_len_hint < c->cap) ? max_len_hint : c->cap;
+    const int S = splits_for(nseg, max_len);
+    const size_t off = attn_offset(c);
+    if (ws_bytes < off + attn_partial_bytes(c, nseg, S)) return NGC_ENOSPC;
+    if ((long long)nseg * S > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;
+
+    AttnArgs aa;
+    aa.k = reinterpret_cast<const unsigned char *>(c->k);
+    aa.v = reinterpret_cast<const unsigned char *>(c->v);
+    aa.len = c->len;
+    aa.q = reinterpret_cast<const unsigned char *>(q);
+    aa.out = out;
+    aa.part_o = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off);
+    aa.part_ml = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off +
+                                           partial_o_bytes(c, nseg, S));
+    aa.status = reinterpret_cast<int32_t *>(ws);
+    aa.seg0 = seg0;
+    aa.lb0 = layer < 0 ? 0 : layer * c->B;
+    aa.S = S; aa.G = c->Hq / c->Hkv; aa.Hkv = c->Hkv; aa.cap = c->cap;
+    aa.scale_log2e = scale * 1.4426950408889634f;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (c->D == 128)
+        hipLaunchKernelGGL(decode_partial_kernel<128>, dim3(nseg * S), dim3(ATT_WAVES * 64), 0, st, aa);
+    else
+        hipLaunchKernelGGL(decode_partial_kernel<64>, dim3(nseg * S), dim3(ATT_WAVES * 64), 0, st, aa);
+    NGC_HIP_CHECK(hipGetLastError());
+    if (S > 1) {
+        if (c->D == 128)
+            hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(nseg), dim3(256), 0, st, aa);
+        else
+            hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(nseg), dim3(256), 0, st, aa);
+        NGC_HIP_CHECK(hipGetLastError());
+    }
+    return NGC_OK;
+}

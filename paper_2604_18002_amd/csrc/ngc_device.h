@@ -1,0 +1,137 @@
+// Shared device helpers for the gfx950 kernels: wave64 primitives, block
+// scans and reductions.  Everything assumes 64-wide wavefronts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define NGC_WAVE 64
+
+#define NGC_HIP_CHECK(expr)                         \
+    do {                                            \
+        hipError_t _e = (expr);                     \
+        if (_e != hipSuccess) return NGC_EHIP;      \
+    } while (0)
+
+namespace ngc {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (NGC_WAVE - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Number of set bits of `mask` below this lane.
+__device__ __forceinline__ int popc_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, NGC_WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, NGC_WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, NGC_WAVE));
+    return v;
+}
+__device__ __forceinline__ int wave_incl_scan_i(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < NGC_WAVE; o <<= 1) {
+        int t = __shfl_up(v, o, NGC_WAVE);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+__device__ __forceinline__ float wave_incl_scan_f(float v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < NGC_WAVE; o <<= 1) {
+        float t = __shfl_up(v, o, NGC_WAVE);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// Block-wide exclusive scan of one int per thread.  `tmp` holds one int per
+// wave (+1).  Returns the exclusive prefix; *total receives the block sum.
+// Contains two barriers; every thread of the block must call it.
+template <int THREADS>
+__device__ __forceinline__ int block_excl_scan_i(int v, int *tmp, int *total)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    const int incl = wave_incl_scan_i(v);
+    if (lane_id() == NGC_WAVE - 1) tmp[wave_id()] = incl;
+    __syncthreads();
+    int base = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        int t = tmp[w];
+        if (w < wave_id()) base += t;
+        all += t;
+    }
+    __syncthreads();
+    *total = all;
+    return base + incl - v;
+}
+
+template <int THREADS>
+__device__ __forceinline__ float block_excl_scan_f(float v, float *tmp, float *total)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    const float incl = wave_incl_scan_f(v);
+    if (lane_id() == NGC_WAVE - 1) tmp[wave_id()] = incl;
+    __syncthreads();
+    float base = 0.f, all = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        float t = tmp[w];
+        if (w < wave_id()) base += t;
+        all += t;
+    }
+    __syncthreads();
+    *total = all;
+    float prev = __shfl_up(incl, 1, NGC_WAVE);   // sum of the lanes below, no subtraction
+    if (lane_id() == 0) prev = 0.f;
+    return base + prev;
+}
+
+template <int THREADS>
+__device__ __forceinline__ float block_sum_f(float v, float *tmp)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    v = wave_sum_f(v);
+    if (lane_id() == 0) tmp[wave_id()] = v;
+    __syncthreads();
+    float all = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) all += tmp[w];
+    __syncthreads();
+    return all;
+}
+
+template <int THREADS>
+__device__ __forceinline__ float block_max_f(float v, float *tmp)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    v = wave_max_f(v);
+    if (lane_id() == 0) tmp[wave_id()] = v;
+    __syncthreads();
+    float all = tmp[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) all = fmaxf(all, tmp[w]);
+    __syncthreads();
+    return all;
+}
+
+}  // namespace ngc

@@ -1,0 +1,787 @@
+// Eviction step kernels for gfx950: perturbed keys, segmented Gumbel-top-k
+// selection with its ordered-subset log-probability, in-place compaction of
+// the surviving K/V rows, and the row append used between rounds.
+//
+// Compiled with -ffp-contract=off: the noise arithmetic is an exact operation
+// sequence (see ngc_noise.h).
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/ngc.h"
+#include "ngc_device.h"
+#include "ngc_noise.h"
+
+namespace ngc {
+
+// ------------------------------------------------------------ geometry ----
+
+struct SegGeom {
+    int B, Hkv, cap, block;
+};
+
+__device__ __forceinline__ void seg_coords(int seg, const SegGeom &g, int &l, int &b, int &h)
+{
+    h = seg % g.Hkv;
+    const int lb = seg / g.Hkv;
+    b = lb % g.B;
+    l = lb / g.B;
+}
+
+// Rows in use of a segment, clamped to [0, cap]; counts a clamp.
+__device__ __forceinline__ int seg_rows(const int32_t *len, int seg, int cap, int32_t *status)
+{
+    int n = len[seg];
+    if (n < 0 || n > cap) {
+        if (threadIdx.x == 0) atomicAdd(&status[NGC_STATUS_LEN_CLAMPED], 1);
+        n = n < 0 ? 0 : cap;
+    }
+    return n;
+}
+
+// ------------------------------------------------------ perturbed keys ----
+
+struct NoiseArgs {
+    uint64_t seed;
+    uint32_t round;
+    float tau;
+    int share_heads;
+};
+
+// Keys of items 4*quad .. 4*quad+3 (those below n_items), one Philox call.
+__device__ __forceinline__ void keys_of_quad(const float *row, int n_items, int quad,
+                                             const NoiseArgs &na, int l, int b, int h,
+                                             float s[4], float key[4])
+{
+    const int t0 = 4 * quad;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float x = (t0 + i < n_items) ? row[t0 + i] : -INFINITY;
+        if (x != x) x = -INFINITY;   // NaN logits count as masked
+        s[i] = x;
+    }
+    if (na.tau == 0.0f) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) key[i] = s[i];
+        return;
+    }
+    uint32_t w[4];
+    item_words(na.seed, na.round, (uint32_t)l, (uint32_t)b,
+               na.share_heads ? 0xFFFFu : (uint32_t)h, (uint32_t)quad, w);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) key[i] = perturb(s[i], na.tau, w[i]);
+}
+
+__global__ __launch_bounds__(256) void perturbed_keys_kernel(
+    const float *__restrict__ logits, const int32_t *__restrict__ len, float *__restrict__ keys_out,
+    int seg0, SegGeom g, NoiseArgs na, int32_t *status)
+{
+    const int seg = seg0 + blockIdx.x;
+    int l, b, h;
+    seg_coords(seg, g, l, b, h);
+    const int n = seg_rows(len, seg, g.cap, status);
+    const int n_items = (n + g.block - 1) / g.block;
+    const float *row = logits + (size_t)seg * g.cap;
+    float *out = keys_out + (size_t)seg * g.cap;
+    for (int quad = threadIdx.x; 4 * quad < n_items; quad += 256) {
+        float s[4], key[4];
+        keys_of_quad(row, n_items, quad, na, l, b, h, s, key);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * quad + i < n_items) out[4 * quad + i] = key[i];
+    }
+}
+
+// ------------------------------------------------------------- select -----
+//
+// One workgroup per segment.  LDS holds the order-preserving code of every
+// perturbed key (4 B per item), two index buffers for the sort of the kept
+// items (2 B per kept item each) and a histogram area.
+//
+//   1. keys:    4 items per thread per step, one Philox call per 4 items.
+//   2. select:  the K-th largest code by a 3-pass radix select (11+11+10 bits)
+//               over LDS histograms.
+//   3. kept:    each wave owns a contiguous range of items; ballots and lane
+//               prefix counts give every kept item its ascending output slot.
+//               Items equal to the threshold are taken lowest index first.
+//   4. sigma:   stable LSD radix sort (4 x 8 bits) of the kept indices by
+//               descending code; stability plus the ascending start order is
+//               the index tie-break.
+//   5. logp:    Eq. 2 in the reverse-running-sum form: U = mass never picked,
+//               R_j = U + sum_{i>=j} e_sigma_i built from the last pick
+//               backwards; log p = sum_j (s_sigma_j - m) - sum_j log R_j.
+
+constexpr int SEL_BINS = 2048;
+
+struct SelectArgs {
+    const float *logits;
+    const int32_t *len;
+    const int32_t *keep;
+    int32_t *kept_out;
+    int32_t *sigma_out;
+    float *logp_out;
+    int32_t *seg_meta;   // [nseg][2]: kept items, rows after compaction
+    int32_t *status;
+    int seg0;
+    int max_keep;
+    int items_cap;       // ceil(cap / block): size of the code array in LDS
+    int keep_cap;        // size of each index buffer in LDS
+    SegGeom g;
+    NoiseArgs na;
+};
+
+// For each lane: the set of lanes of this wave whose 8-bit digit equals its
+// own, restricted to `valid` lanes.
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, uint64_t valid)
+{
+    uint64_t m = valid;
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+        const bool on = (d >> bit) & 1u;
+        const uint64_t bal = __ballot(on);
+        m &= on ? bal : ~bal;
+    }
+    return m;
+}
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void select_kernel(SelectArgs a)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    constexpr int HIST = (SEL_BINS > 256 * NW) ? SEL_BINS : 256 * NW;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint32_t *code = reinterpret_cast<uint32_t *>(smem_raw);
+    uint32_t *hist = code + a.items_cap;
+    int *misc = reinterpret_cast<int *>(hist + HIST);            // 64 ints
+    uint16_t *idxA = reinterpret_cast<uint16_t *>(misc + 64);
+    uint16_t *idxB = idxA + a.keep_cap;
+    float *fmisc = reinterpret_cast<float *>(misc);
+
+    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const int seg = a.seg0 + blockIdx.x;
+    int l, b, h;
+    seg_coords(seg, a.g, l, b, h);
+    const int n = seg_rows(a.len, seg, a.g.cap, a.status);
+    const int N = (n + a.g.block - 1) / a.g.block;
+    int K = a.keep[seg];
+    {
+        int lim = N < a.max_keep ? N : a.max_keep;
+        if (K < 0 || K > lim) {
+            if (tid == 0 && (K < 0 || K > N)) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+            K = K < 0 ? 0 : lim;
+        }
+    }
+    const float *row = a.logits + (size_t)seg * a.g.cap;
+    const bool want_logp = a.logp_out != nullptr;
+    const bool want_sort = want_logp || a.sigma_out != nullptr;
+
+    if (K == 0) {
+        if (tid == 0) {
+            a.seg_meta[2 * seg] = 0;
+            a.seg_meta[2 * seg + 1] = 0;
+            if (want_logp) a.logp_out[seg] = 0.f;
+        }
+        return;
+    }
+
+    // ---- 1. keys ----------------------------------------------------------
+    float smax = -INFINITY;
+    for (int quad = tid; 4 * quad < N; quad += THREADS) {
+        float s[4], key[4];
+        keys_of_quad(row, N, quad, a.na, l, b, h, s, key);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * quad + i < N) {
+                code[4 * quad + i] = ordered_code(key[i]);
+                smax = fmaxf(smax, s[i]);
+            }
+    }
+    if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
+
+    // ---- 2. radix select of the K-th largest code -------------------------
+    uint32_t prefix = 0, pmask = 0;
+    int need = K;   // how many of the items matching `prefix` are still to take
+    {
+        const int shifts[3] = {21, 10, 0};
+        const int widths[3] = {11, 11, 10};
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = shifts[pass], nb = 1 << widths[pass];
+            for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+            __syncthreads();
+            for (int t = tid; t < N; t += THREADS) {
+                const uint32_t u = code[t];
+                if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
+            }
+            __syncthreads();
+            // bins in descending digit order; each thread owns `per` of them
+            const int per = (nb + THREADS - 1) / THREADS;
+            int mine = 0;
+            for (int i = 0; i < per; ++i) {
+                const int p = tid * per + i;
+                if (p < nb) mine += (int)hist[nb - 1 - p];
+            }
+            int total;
+            int above = block_excl_scan_i<THREADS>(mine, misc, &total);
+            if (above < need && need <= above + mine) {
+                for (int i = 0; i < per; ++i) {
+                    const int p = tid * per + i;
+                    const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
+                    if (need <= above + c) {
+                        misc[32] = nb - 1 - p;   // digit of the K-th largest
+                        misc[33] = above;        // matching items with a larger digit
+                        break;
+                    }
+                    above += c;
+                }
+            }
+            __syncthreads();
+            const uint32_t digit = (uint32_t)misc[32];
+            need -= misc[33];
+            prefix |= digit << shift;
+            pmask |= (uint32_t)(nb - 1) << shift;
+            __syncthreads();
+        }
+    }
+    const uint32_t thr = prefix;   // code of the K-th largest key; `need` items equal to it are kept
+
+    // ---- 3. kept list, ascending ------------------------------------------
+    const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+    const int w_begin = wv * per_wave;
+    const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
+    {
+        int gt = 0, eq = 0;
+        for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
+            const int t = t0 + lane;
+            const uint32_t u = (t < w_end) ? code[t] : 0u;
+            gt += __popcll(__ballot(t < w_end && u > thr));
+            eq += __popcll(__ballot(t < w_end && u == thr));
+        }
+        if (lane == 0) { misc[wv] = gt; misc[16 + wv] = eq; }
+    }
+    __syncthreads();
+    int gt_base = 0, eq_base = 0;
+    for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
+    float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
+    int32_t *kept_row = a.kept_out + (size_t)seg * a.max_keep;
+    for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
+        const int t = t0 + lane;
+        const bool in = t < w_end;
+        const uint32_t u = in ? code[t] : 0u;
+        const bool is_gt = in && u > thr, is_eq = in && u == thr;
+        const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
+        const int gt_before = gt_base + popc_below(bgt);
+        const int eq_before = eq_base + popc_below(beq);
+        const bool sel = is_gt || (is_eq && eq_before < need);
+        if (sel) {
+            const int slot = gt_before + (eq_before < need ? eq_before : need);
+            kept_row[slot] = t;
+            if (want_sort) idxA[slot] = (uint16_t)t;
+            if (slot == K - 1) misc[34] = t;   // highest kept index
+        } else if (in && want_logp) {
+            float x = row[t];
+            if (x != x) x = -INFINITY;
+            unpicked += expf(x - smax);
+        }
+        gt_base += __popcll(bgt);
+        eq_base += __popcll(beq);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int last_item = misc[34];
+        const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
+        a.seg_meta[2 * seg] = K;
+        a.seg_meta[2 * seg + 1] = (K - 1) * a.g.block + last_rows;
+    }
+    if (!want_sort) return;
+
+    // ---- 4. sigma: stable sort of the kept indices by descending code ------
+    const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+    const int k_begin = wv * per_wave_k;
+    const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
+    uint16_t *src = idxA, *dst = idxB;
+    volatile uint32_t *vh = hist;
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 8 * pass;
+        for (int i = tid; i < 256 * NW; i += THREADS) hist[i] = 0;
+        __syncthreads();
+        // per-wave digit counts over the wave's own contiguous range
+        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+            const int j = j0 + lane;
+            const bool in = j < k_end;
+            const uint32_t d = in ? ((~code[src[j]]) >> shift) & 255u : 0u;
+            const uint64_t peers = match_digit(d, __ballot(in));
+            if (in && popc_below(peers) == 0) vh[wv * 256 + d] += (uint32_t)__popcll(peers);
+        }
+        __syncthreads();
+        // exclusive scan in (digit, wave) order; thread owns 4 consecutive entries
+        {
+            int vals[4], sum = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid * 4 + i;
+                vals[i] = (int)hist[(e % NW) * 256 + e / NW];
+                sum += vals[i];
+            }
+            int total;
+            int run = block_excl_scan_i<THREADS>(sum, misc, &total);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid * 4 + i;
+                hist[(e % NW) * 256 + e / NW] = (uint32_t)run;
+                run += vals[i];
+            }
+        }
+        __syncthreads();
+        // scatter in order: rank within the batch + running offset of (wave, digit)
+        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+            const int j = j0 + lane;
+            const bool in = j < k_end;
+            const uint16_t idx = in ? src[j] : (uint16_t)0;
+            const uint32_t d = in ? ((~code[idx]) >> shift) & 255u : 0u;
+            const uint64_t peers = match_digit(d, __ballot(in));
+            const int rank = popc_below(peers);
+            uint32_t base = 0;
+            if (in) base = vh[wv * 256 + d];
+            __builtin_amdgcn_wave_barrier();
+            if (in) {
+                dst[base + rank] = idx;
+                if (rank == 0) vh[wv * 256 + d] = base + (uint32_t)__popcll(peers);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        uint16_t *tmp = src; src = dst; dst = tmp;
+    }
+    // four passes: the sorted list is back in idxA (== src)
+    if (a.sigma_out) {
+        int32_t *sig_row = a.sigma_out + (size_t)seg * a.max_keep;
+        for (int j = tid; j < K; j += THREADS) sig_row[j] = (int32_t)src[j];
+    }
+    if (!want_logp) return;
+
+    // ---- 5. log-probability of sigma (Eq. 2) -------------------------------
+    const float U = block_sum_f<THREADS>(unpicked, fmisc);
+    const int chunk = (K + THREADS - 1) / THREADS;
+    const int nchunks = (K + chunk - 1) / chunk;
+    // thread 0 owns the LAST chunk, so an ordinary exclusive scan over threads
+    // yields the mass of everything picked after a thread's chunk
+    const int cidx = nchunks - 1 - tid;
+    const int j_lo = cidx * chunk;
+    const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+    float mass = 0.f;
+    if (cidx >= 0)
+        for (int j = j_lo; j < j_hi; ++j) {
+            float x = row[src[j]];
+            if (x != x) x = -INFINITY;
+            mass += expf(x - smax);
+        }
+    float total_mass;
+    const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
+    float acc = 0.f;
+    if (cidx >= 0) {
+        float R = U + after;
+        for (int j = j_hi - 1; j >= j_lo; --j) {
+            float x = row[src[j]];
+            if (x != x) x = -INFINITY;
+            const float d = x - smax;
+            R += expf(d);
+            acc += d - logf(R);
+        }
+    }
+    const float lp = block_sum_f<THREADS>(acc, fmisc);
+    if (tid == 0) a.logp_out[seg] = lp;
+}
+
+// ------------------------------------------- log-prob of given actions ----
+
+struct LogprobArgs {
+    const float *logits;
+    const int32_t *n_items;
+    const int32_t *sigma;
+    const int32_t *keep;
+    float *logp_out;
+    int32_t *status;
+    int64_t logit_stride;
+    int sigma_stride;
+};
+
+// One workgroup per segment; LDS bitmap of picked items (65536 bits).
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
+{
+    __shared__ uint32_t picked[2048];
+    __shared__ float fmisc[32];
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x;
+    int N = a.n_items[seg];
+    if (N < 0) N = 0;
+    if (N > 65536) N = 65536;
+    int K = a.keep[seg];
+    if (K < 0 || K > N) {
+        if (tid == 0) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+        K = K < 0 ? 0 : N;
+    }
+    const float *row = a.logits + (size_t)seg * a.logit_stride;
+    const int32_t *sig = a.sigma + (size_t)seg * a.sigma_stride;
+    if (K == 0) {
+        if (tid == 0) a.logp_out[seg] = 0.f;
+        return;
+    }
+    for (int i = tid; i < 2048; i += THREADS) picked[i] = 0;
+    __syncthreads();
+    int bad = 0;
+    for (int j = tid; j < K; j += THREADS) {
+        const int t = sig[j];
+        if (t < 0 || t >= N) { bad = 1; continue; }
+        const uint32_t bit = 1u << (t & 31);
+        if (atomicOr(&picked[t >> 5], bit) & bit) bad = 1;
+    }
+    if (bad) atomicAdd(&a.status[NGC_STATUS_BAD_SIGMA], 1);
+    float smax = -INFINITY;
+    for (int t = tid; t < N; t += THREADS) {
+        float x = row[t];
+        if (x == x) smax = fmaxf(smax, x);
+    }
+    smax = block_max_f<THREADS>(smax, fmisc);   // barriers also publish `picked`
+    float unpicked = 0.f;
+    for (int t = tid; t < N; t += THREADS) {
+        if (picked[t >> 5] & (1u << (t & 31))) continue;
+        float x = row[t];
+        if (x != x) x = -INFINITY;
+        unpicked += expf(x - smax);
+    }
+    const float U = block_sum_f<THREADS>(unpicked, fmisc);
+    const int chunk = (K + THREADS - 1) / THREADS;
+    const int nchunks = (K + chunk - 1) / chunk;
+    const int cidx = nchunks - 1 - tid;
+    const int j_lo = cidx * chunk;
+    const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+    auto logit_of = [&](int j) {
+        int t = sig[j];
+        t = t < 0 ? 0 : (t >= N ? N - 1 : t);
+        float x = row[t];
+        return (x != x) ? -INFINITY : x;
+    };
+    float mass = 0.f;
+    if (cidx >= 0)
+        for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of(j) - smax);
+    float total_mass;
+    const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
+    float acc = 0.f;
+    if (cidx >= 0) {
+        float R = U + after;
+        for (int j = j_hi - 1; j >= j_lo; --j) {
+            const float d = logit_of(j) - smax;
+            R += expf(d);
+            acc += d - logf(R);
+        }
+    }
+    const float lp = block_sum_f<THREADS>(acc, fmisc);
+    if (tid == 0) a.logp_out[seg] = lp;
+}
+
+// --------------------------------------------------------- compaction -----
+//
+// In place: the row that ends at slot j comes from a slot >= j, so a
+// workgroup that walks a segment front to back, reads a whole tile into
+// registers, waits for the tile's reads (barrier) and only then writes, never
+// overwrites a row it (or a later tile) still has to read.  One workgroup per
+// (segment, K-or-V); 16-byte loads and stores; rows that stay where they are
+// are neither read nor written.
+
+struct CompactArgs {
+    void *k;
+    void *v;
+    int32_t *pos;
+    int32_t *len;
+    const int32_t *kept;
+    const int32_t *seg_meta;
+    int seg0;
+    int max_keep;
+    int cap;
+    int block;
+};
+
+template <int ROW_BYTES>
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
+{
+    constexpr int PIECES = ROW_BYTES / 16;       // 16-byte pieces per row
+    constexpr int ROWS_PER_STEP = 256 / PIECES;  // rows covered by one load per thread
+    constexpr int UNROLL = 8;
+    constexpr int TILE_ROWS = ROWS_PER_STEP * UNROLL;
+    __shared__ int first_moved;
+
+    const int tid = threadIdx.x;
+    const int seg = a.seg0 + blockIdx.x;
+    const bool is_v = blockIdx.y == 1;
+    const int K = a.seg_meta[2 * seg];
+    const int rows_new = a.seg_meta[2 * seg + 1];
+    const int32_t *kept = a.kept + (size_t)seg * a.max_keep;
+    const int block = a.block;
+
+    // first item that changes place (kept is ascending and kept[j] >= j)
+    if (tid == 0) first_moved = K;
+    __syncthreads();
+    {
+        int mine = K;
+        for (int j = tid; j < K; j += 256)
+            if (kept[j] != j) { mine = j; break; }
+        if (mine < K) atomicMin(&first_moved, mine);
+    }
+    __syncthreads();
+    const int row_start = first_moved * block;
+
+    unsigned char *base = reinterpret_cast<unsigned char *>(is_v ? a.v : a.k) +
+                          (size_t)seg * a.cap * ROW_BYTES;
+    const int piece = tid % PIECES, rsub = tid / PIECES;
+    for (int tile = (row_start / TILE_ROWS) * TILE_ROWS; tile < rows_new; tile += TILE_ROWS) {
+        uint4 buf[UNROLL];
+        int srcrow[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int r = tile + u * ROWS_PER_STEP + rsub;
+            srcrow[u] = -1;
+            if (r < rows_new) {
+                const int item = (block == 1) ? r : r / block;
+                const int s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
+                if (s != r) {
+                    srcrow[u] = s;
+                    buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)s * ROW_BYTES + piece * 16);
+                }
+            }
+        }
+        __syncthreads();   // every read of this tile has landed
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int r = tile + u * ROWS_PER_STEP + rsub;
+            if (srcrow[u] >= 0)
+                *reinterpret_cast<uint4 *>(base + (size_t)r * ROW_BYTES + piece * 16) = buf[u];
+        }
+    }
+
+    if (!is_v) {
+        if (a.pos) {
+            int32_t *pos = a.pos + (size_t)seg * a.cap;
+            for (int tile = (row_start / 1024) * 1024; tile < rows_new; tile += 1024) {
+                int32_t val[4];
+                int srcrow[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int r = tile + u * 256 + tid;
+                    srcrow[u] = -1;
+                    if (r < rows_new) {
+                        const int item = (block == 1) ? r : r / block;
+                        const int s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
+                        if (s != r) { srcrow[u] = s; val[u] = pos[s]; }
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (srcrow[u] >= 0) pos[tile + u * 256 + tid] = val[u];
+            }
+        }
+        if (tid == 0) a.len[seg] = rows_new;
+    }
+}
+
+// -------------------------------------------------------------- append ----
+
+struct AppendArgs {
+    void *k;
+    void *v;
+    int32_t *pos;
+    int32_t *len;
+    const void *k_new;
+    const void *v_new;
+    const int32_t *new_pos;
+    int32_t *status;
+    int seg0;       // first segment of the launch
+    int src_seg0;   // segment index that k_new[0] belongs to
+    int B, Hkv, cap;
+};
+
+// One wave per segment: lanes [0, PIECES) copy the K row, the next PIECES the V row.
+template <int ROW_BYTES>
+__global__ __launch_bounds__(64) void append_kernel(AppendArgs a)
+{
+    constexpr int PIECES = ROW_BYTES / 16;
+    const int seg = a.seg0 + blockIdx.x;
+    const int lane = threadIdx.x;
+    const int n = a.len[seg];
+    if (n < 0 || n >= a.cap) {
+        if (lane == 0) atomicAdd(&a.status[NGC_STATUS_APPEND_FULL], 1);
+        return;
+    }
+    const size_t src_off = (size_t)(seg - a.src_seg0) * ROW_BYTES;
+    const size_t dst_off = ((size_t)seg * a.cap + n) * ROW_BYTES;
+    if (lane < 2 * PIECES) {
+        const bool is_v = lane >= PIECES;
+        const int piece = is_v ? lane - PIECES : lane;
+        const unsigned char *s = reinterpret_cast<const unsigned char *>(is_v ? a.v_new : a.k_new) + src_off;
+        unsigned char *d = reinterpret_cast<unsigned char *>(is_v ? a.v : a.k) + dst_off;
+        *reinterpret_cast<uint4 *>(d + piece * 16) = *reinterpret_cast<const uint4 *>(s + piece * 16);
+    }
+    __syncthreads();
+    if (lane == 0) {
+        if (a.pos && a.new_pos) a.pos[(size_t)seg * a.cap + n] = a.new_pos[(seg / a.Hkv) % a.B];
+        a.len[seg] = n + 1;
+    }
+}
+
+}  // namespace ngc
+
+// ============================================================ host side ====
+
+using namespace ngc;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cache(const ngc_cache *c)
+{
+    if (!c || !c->k || !c->v || !c->len) return NGC_EINVAL;
+    if (!aligned16(c->k) || !aligned16(c->v)) return NGC_EINVAL;
+    if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
+    if (c->D != 64 && c->D != 128) return NGC_EINVAL;
+    if (c->Hq % c->Hkv != 0 || c->Hq / c->Hkv > 16) return NGC_EINVAL;
+    if (c->L > 65535 || c->Hkv > 65534) return NGC_EINVAL;   // noise counter packs layer and head in 16 bits each
+    return NGC_OK;
+}
+
+int layer_range(const ngc_cache *c, int layer, int *seg0, int *nseg)
+{
+    if (layer < -1 || layer >= c->L) return NGC_EINVAL;
+    const int per_layer = c->B * c->Hkv;
+    *seg0 = layer < 0 ? 0 : layer * per_layer;
+    *nseg = layer < 0 ? c->L * per_layer : per_layer;
+    return NGC_OK;
+}
+
+constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
+
+size_t select_lds_bytes(int threads, int items_cap, int keep_cap)
+{
+    const int nw = threads / 64;
+    const int hist = (SEL_BINS > 256 * nw) ? SEL_BINS : 256 * nw;
+    return (size_t)items_cap * 4 + (size_t)hist * 4 + 64 * 4 + (size_t)keep_cap * 2 * 2;
+}
+
+}  // namespace
+
+extern "C" int ngc_perturbed_keys(const ngc_cache *c, int32_t layer, const float *logits,
+                                  const ngc_evict_params *p, float *keys_out,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_cache(c);
+    if (rc) return rc;
+    if (!logits || !keys_out || !p || !ws || p->block < 1) return NGC_EINVAL;
+    if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
+    int seg0, nseg;
+    rc = layer_range(c, layer, &seg0, &nseg);
+    if (rc) return rc;
+    SegGeom g{c->B, c->Hkv, c->cap, p->block};
+    NoiseArgs na{p->seed, p->round, p->noise_scale, p->share_heads};
+    hipLaunchKernelGGL(perturbed_keys_kernel, dim3(nseg), dim3(256), 0, (hipStream_t)stream,
+                       logits, c->len, keys_out, seg0, g, na, reinterpret_cast<int32_t *>(ws));
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
+                         const int32_t *keep, const ngc_evict_params *p, int32_t max_keep,
+                         int32_t *kept_out, int32_t *sigma_out, float *logp_out,
+                         void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_cache(c);
+    if (rc) return rc;
+    if (!logits || !keep || !p || !kept_out || !ws || p->block < 1 || max_keep < 1) return NGC_EINVAL;
+    int seg0, nseg;
+    rc = layer_range(c, layer, &seg0, &nseg);
+    if (rc) return rc;
+    const int nseg_total = c->L * c->B * c->Hkv;
+    if (ws_bytes < STATUS_BYTES + (size_t)nseg_total * 8) return NGC_ENOSPC;
+    if (!aligned16(ws)) return NGC_EINVAL;
+
+    const int items_cap = (c->cap + p->block - 1) / p->block;
+    if (items_cap > 16384) return NGC_EUNSUPPORTED;
+    int keep_cap = max_keep < items_cap ? max_keep : items_cap;
+    keep_cap = (keep_cap + 7) & ~7;
+    const int items_cap_al = (items_cap + 3) & ~3;
+    const int threads = items_cap > 2048 ? 1024 : 256;
+    const size_t lds = select_lds_bytes(threads, items_cap_al, keep_cap);
+    if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
+
+    int32_t *status = reinterpret_cast<int32_t *>(ws);
+    int32_t *seg_meta = status + NGC_STATUS_WORDS;
+
+    SelectArgs sa;
+    sa.logits = logits; sa.len = c->len; sa.keep = keep;
+    sa.kept_out = kept_out; sa.sigma_out = sigma_out; sa.logp_out = logp_out;
+    sa.seg_meta = seg_meta; sa.status = status;
+    sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
+    sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
+    sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
+
+    hipStream_t st = (hipStream_t)stream;
+    if (threads == 1024) {
+        NGC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<1024>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(select_kernel<1024>, dim3(nseg), dim3(1024), lds, st, sa);
+    } else {
+        NGC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<256>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(select_kernel<256>, dim3(nseg), dim3(256), lds, st, sa);
+    }
+    NGC_HIP_CHECK(hipGetLastError());
+
+    if (!(p->flags & NGC_EVICT_SELECT_ONLY)) {
+        CompactArgs ca{c->k, c->v, c->pos, c->len, kept_out, seg_meta, seg0, max_keep, c->cap, p->block};
+        if (c->D == 128)
+            hipLaunchKernelGGL(compact_kernel<256>, dim3(nseg, 2), dim3(256), 0, st, ca);
+        else
+            hipLaunchKernelGGL(compact_kernel<128>, dim3(nseg, 2), dim3(256), 0, st, ca);
+        NGC_HIP_CHECK(hipGetLastError());
+    }
+    return NGC_OK;
+}
+
+extern "C" int ngc_subset_logprob(const float *logits, const int32_t *n_items,
+                                  const int32_t *sigma, const int32_t *keep, int32_t nseg,
+                                  int64_t logit_stride, int32_t sigma_stride,
+                                  float *logp_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!logits || !n_items || !sigma || !keep || !logp_out || !ws) return NGC_EINVAL;
+    if (nseg < 0 || logit_stride < 0 || sigma_stride < 0) return NGC_EINVAL;
+    if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
+    if (nseg == 0) return NGC_OK;
+    LogprobArgs la{logits, n_items, sigma, keep, logp_out, reinterpret_cast<int32_t *>(ws),
+                   logit_stride, sigma_stride};
+    hipLaunchKernelGGL(subset_logprob_kernel<512>, dim3(nseg), dim3(512), 0, (hipStream_t)stream, la);
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_cache_append(const ngc_cache *c, int32_t layer, const void *k_new,
+                                const void *v_new, const int32_t *new_pos,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_cache(c);
+    if (rc) return rc;
+    if (!k_new || !v_new || !ws || !aligned16(k_new) || !aligned16(v_new)) return NGC_EINVAL;
+    if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
+    int seg0, nseg;
+    rc = layer_range(c, layer, &seg0, &nseg);
+    if (rc) return rc;
+    AppendArgs aa{c->k, c->v, c->pos, c->len, k_new, v_new, new_pos,
+                  reinterpret_cast<int32_t *>(ws), seg0, seg0, c->B, c->Hkv, c->cap};
+    if (c->D == 128)
+        hipLaunchKernelGGL(append_kernel<256>, dim3(nseg), dim3(64), 0, (hipStream_t)stream, aa);
+    else
+        hipLaunchKernelGGL(append_kernel<128>, dim3(nseg), dim3(64), 0, (hipStream_t)stream, aa);
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}

@@ -1,0 +1,170 @@
+"""GPU parity of decode attention (and of the whole evict -> append -> attend
+sequence) against the CPU oracle, through the C ABI.
+
+Tolerance: 2e-3 max-abs (bf16 inputs, fp32 scores / softmax / accumulation;
+the kernel's own rounding is ~1e-5, see the split of P into two bf16 parts)."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2604_18002_amd import synth
+
+from _harness import from_bf16_tensor, host_case, oracle_evict_segment, to_bf16_tensor, upload
+
+pytestmark = pytest.mark.gpu
+
+ATOL = 2e-3
+
+
+def _ngc():
+    from paper_2604_18002_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _attend(ngc, cache, q_u16, layer, scale, hint=0, ws=None):
+    import torch
+    ws = ws if ws is not None else ngc.allocate_workspace(cache, 1)
+    q = to_bf16_tensor(q_u16, "cuda")
+    out = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    print(f"[attn] layer={layer} q={tuple(q.shape)} cap={cache.k.shape[3]} hint={hint}", flush=True)
+    ngc.ngc_decode_attn(cache, layer, q, scale, hint, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), ws
+
+
+def _oracle_attend(w, hk, hv, hlen, q_u16, l, scale):
+    """hk, hv: host copies [L,B,Hkv,cap,D]; q_u16 [B,Hq,D] -> fp32 [B,Hq,D]."""
+    out = np.zeros((w.B, w.Hq, w.D), np.float32)
+    G = w.G
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            n = int(hlen[l, b, h])
+            out[b, h * G:(h + 1) * G] = orc.decode_attn(q_u16[b, h * G:(h + 1) * G], hk[l, b, h, :n],
+                                                        hv[l, b, h, :n], scale)
+    return out
+
+
+@pytest.mark.parametrize("idx,over", [
+    (0, {}),                                             # D = 64, G = 4, n = 512
+    (1, {}),                                             # D = 128, G = 6, ragged 1024..2048
+    (3, dict(L=2, B=5, n_lo=33, n_hi=700)),              # G = 7, short ragged
+    (1, dict(B=3, n_lo=1, n_hi=70)),                     # tiny lengths incl. partial tiles
+    (0, dict(B=7, Hq=32, Hkv=2, n_lo=100, n_hi=1000)),   # G = 16, D = 64
+    (1, dict(B=2, Hq=2, Hkv=2, n_lo=3000, n_hi=5000)),   # G = 1, long
+])
+def test_dense_attention_parity(idx, over):
+    ngc = _ngc()
+    w = synth.workload(idx, **over)
+    case = host_case(w)
+    cache, _, _ = upload(case)
+    hk, hv, hlen = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v), cache.len.cpu().numpy()
+    scale = 1.0 / np.sqrt(w.D)
+    qs = np.stack([synth.queries(w, l) for l in range(w.L)])          # [L,B,Hq,D]
+    got_all, ws = _attend(ngc, cache, qs, -1, scale)
+    for l in range(w.L):
+        want = _oracle_attend(w, hk, hv, hlen, qs[l], l, scale)
+        assert np.abs(got_all[l] - want).max() <= ATOL, f"all-layers call, layer {l}"
+        got_one, _ = _attend(ngc, cache, qs[l], l, scale, ws=ws)
+        assert np.abs(got_one - want).max() <= ATOL, f"single-layer call, layer {l}"
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_split_count_does_not_change_the_result():
+    # the length hint only steers the split; results agree to fp32 reassociation
+    ngc = _ngc()
+    w = synth.workload(1, B=2, n_lo=2048, n_hi=2048)
+    case = host_case(w)
+    cache, _, _ = upload(case)
+    q = synth.queries(w, 0)
+    scale = 1.0 / np.sqrt(w.D)
+    ref, ws = _attend(ngc, cache, q, 0, scale, hint=0)
+    for hint in (1, 256, 512, 1024, 2047):
+        got, _ = _attend(ngc, cache, q, 0, scale, hint=hint, ws=ws)
+        assert np.abs(got - ref).max() <= 2e-5, hint
+
+
+def test_peaked_softmax_and_large_scores():
+    # one key nearly parallel to the query: softmax weight ~1 on a single row,
+    # plus large score magnitudes; exercises the two-part P and the running max
+    ngc = _ngc()
+    w = synth.workload(1, B=2, n_lo=600, n_hi=900)
+    case = host_case(w)
+    q = synth.queries(w, 0)
+    for (l, b, h) in case.segs:
+        k = synth.bf16_bits_to_f32(case.k[(l, b, h)])
+        qf = synth.bf16_bits_to_f32(q[b, h * w.G])
+        k[137] = 4.0 * qf
+        k[5] = 3.9 * qf
+        case.k[(l, b, h)] = synth.f32_to_bf16_bits(k)
+    cache, _, _ = upload(case)
+    hk, hv, hlen = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v), cache.len.cpu().numpy()
+    for scale in (1.0 / np.sqrt(w.D), 1.0):
+        got, ws = _attend(ngc, cache, q, 0, scale)
+        want = _oracle_attend(w, hk, hv, hlen, q, 0, scale)
+        assert np.all(np.isfinite(got))
+        assert np.abs(got - want).max() <= ATOL, scale
+
+
+def test_permutation_of_retained_rows():
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, B=2, n_lo=777, n_hi=777)
+    case = host_case(w)
+    cache, _, _ = upload(case)
+    q = synth.queries(w, 0)
+    scale = 1.0 / np.sqrt(w.D)
+    a, ws = _attend(ngc, cache, q, 0, scale)
+    perm = torch.from_numpy(np.random.default_rng(1).permutation(777)).cuda()
+    cache.k[:, :, :, :777] = cache.k[:, :, :, perm]
+    cache.v[:, :, :, :777] = cache.v[:, :, :, perm]
+    b, _ = _attend(ngc, cache, q, 0, scale, ws=ws)
+    assert np.abs(a - b).max() <= 2e-5
+
+
+def test_empty_segment_gives_zeros_and_is_counted():
+    ngc = _ngc()
+    w = synth.workload(0, B=3)
+    case = host_case(w)
+    cache, _, _ = upload(case)
+    cache.len[0, 1, :] = 0
+    q = synth.queries(w, 0)
+    got, ws = _attend(ngc, cache, q, 0, 0.125)
+    assert np.array_equal(got[1], np.zeros_like(got[1]))
+    assert np.all(np.isfinite(got))
+    assert ngc.read_status(ws)[ngc.STATUS_EMPTY_ATTN] == w.Hkv
+
+
+@pytest.mark.parametrize("idx,over", [(0, {}), (1, dict(B=6)), (4, dict(L=1, B=2))])
+def test_evict_append_attend_sequence(idx, over):
+    """The whole step: sample + compact, append the next token, attend."""
+    import torch
+    ngc = _ngc()
+    w = synth.workload(idx, **over)
+    case = host_case(w)
+    cache, logits, keep = upload(case)
+    max_keep = int(case.keep.max())
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.zeros(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device="cuda")
+    sigma = torch.zeros_like(kept)
+    logp = torch.zeros(w.L, w.B, w.Hkv, dtype=torch.float32, device="cuda")
+    p = ngc.make_params(noise_scale=1.0, round=0, seed=w.gumbel_seed)
+    print(f"[step] workload={w.name} evict -> append -> attend", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    new = [synth.new_token_kv(w, l, 0) for l in range(w.L)]
+    nk, nv = np.stack([x[0] for x in new]), np.stack([x[1] for x in new])
+    ngc.ngc_cache_append(cache, -1, to_bf16_tensor(nk, "cuda"), to_bf16_tensor(nv, "cuda"), None, ws)
+    qs = np.stack([synth.queries(w, l, 1) for l in range(w.L)])
+    scale = 1.0 / np.sqrt(w.D)
+    got, _ = _attend(ngc, cache, qs, -1, scale, hint=max_keep + 1, ws=ws)
+    # oracle: same steps on the host copies
+    for l in range(w.L):
+        for b in range(w.B):
+            for h in range(w.Hkv):
+                _, _, _, k_after, v_after = oracle_evict_segment(case, (l, b, h), 1.0, w.gumbel_seed, 0)
+                kk = np.concatenate([k_after, nk[l, b, h][None]])
+                vv = np.concatenate([v_after, nv[l, b, h][None]])
+                want = orc.decode_attn(qs[l, b, h * w.G:(h + 1) * w.G], kk, vv, scale)
+                diff = np.abs(got[l, b, h * w.G:(h + 1) * w.G] - want).max()
+                assert diff <= ATOL, ((l, b, h), diff)
+    assert all(x == 0 for x in ngc.read_status(ws))

@@ -1,0 +1,352 @@
+"""GPU parity of the eviction step against the CPU oracle, through the C ABI.
+
+Indices, lengths and compacted bytes must be bit-exact; log-probabilities
+within 1e-4 relative (fp32 kernel vs fp64 oracle: K terms of magnitude ~log n,
+each carrying ~1e-7 relative error, summed pairwise)."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2604_18002_amd import synth
+
+from _harness import (from_bf16_tensor, host_case, oracle_evict_segment, oracle_logprob, to_bf16_tensor, upload)
+
+pytestmark = pytest.mark.gpu
+
+LOGP_RTOL = 1e-4
+
+
+def _ngc():
+    from paper_2604_18002_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _run_evict(case, tau=1.0, rnd=0, block=1, share_heads=0, with_pos=True, layer=-1, select_only=False,
+               want_sigma=True, want_logp=True):
+    import torch
+    ngc = _ngc()
+    w = case.w
+    cache, logits, keep = upload(case, with_pos=with_pos)
+    max_keep = int(case.keep.max()) if case.keep.size else 1
+    max_keep = max(max_keep, 1)
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1) if want_sigma else None
+    logp = torch.full((w.L, w.B, w.Hkv), float("nan"), dtype=torch.float32, device="cuda") if want_logp else None
+    p = ngc.make_params(block=block, share_heads=share_heads, noise_scale=tau, round=rnd, seed=w.gumbel_seed,
+                        flags=ngc.EVICT_SELECT_ONLY if select_only else 0)
+    print(f"[evict] workload={w.name} L={w.L} B={w.B} Hkv={w.Hkv} cap={w.cap} tau={tau} block={block} "
+          f"layer={layer} max_keep={max_keep}", flush=True)
+    ngc.ngc_evict(cache, layer, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    return cache, kept, sigma, logp, ws
+
+
+def _check_against_oracle(case, cache, kept, sigma, logp, tau, rnd, block=1, share_heads=False, segs=None,
+                          moved=True):
+    w = case.w
+    hk, hv = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v)
+    hlen = cache.len.cpu().numpy()
+    hkept = kept.cpu().numpy()
+    hsig = sigma.cpu().numpy() if sigma is not None else None
+    hlp = logp.cpu().numpy() if logp is not None else None
+    hpos = cache.pos.cpu().numpy() if cache.pos is not None else None
+    for seg in (segs or case.segs):
+        l, b, h = seg
+        okept, osig, olp, ok, ov = oracle_evict_segment(case, seg, tau, w.gumbel_seed, rnd, block, share_heads)
+        K = okept.size
+        assert hkept[l, b, h, :K].tolist() == okept.tolist(), f"kept differs at segment {seg}"
+        if hsig is not None:
+            assert hsig[l, b, h, :K].tolist() == osig.tolist(), f"sigma differs at segment {seg}"
+        if hlp is not None:
+            assert hlp[l, b, h] == pytest.approx(olp, rel=LOGP_RTOL, abs=1e-5), f"logp differs at segment {seg}"
+        if moved:
+            n_new = ok.shape[0]
+            assert hlen[l, b, h] == n_new, f"len differs at segment {seg}"
+            assert hk[l, b, h, :n_new].tobytes() == ok.tobytes(), f"K bytes differ at segment {seg}"
+            assert hv[l, b, h, :n_new].tobytes() == ov.tobytes(), f"V bytes differ at segment {seg}"
+            if hpos is not None:
+                n_old = case.k[seg].shape[0]
+                want = orc.compact_i32(np.arange(n_old, dtype=np.int32), okept, block)
+                assert hpos[l, b, h, :n_new].tolist() == want.tolist(), f"pos differs at segment {seg}"
+
+
+# ---------------------------------------------------------------- keys -----
+
+@pytest.mark.parametrize("tau", [1.0, 0.37])
+def test_perturbed_keys_bit_exact(tau):
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, L=3, B=5, Hkv=2, Hq=12, n_lo=900, n_hi=4099)
+    case = host_case(w)
+    cache, logits, _ = upload(case)
+    ws = ngc.allocate_workspace(cache, 1)
+    keys = torch.zeros_like(logits)
+    for share in (0, 1):
+        p = ngc.make_params(noise_scale=tau, round=5, seed=0xDEADBEEF12345678, share_heads=share)
+        print(f"[keys] tau={tau} share_heads={share}", flush=True)
+        ngc.ngc_perturbed_keys(cache, -1, logits, p, keys, ws)
+        torch.cuda.synchronize()
+        hkeys = keys.cpu().numpy()
+        for (l, b, h) in case.segs:
+            s = case.logits[(l, b, h)]
+            want = orc.perturbed_keys(s, tau, 0xDEADBEEF12345678, 5, l, b, 0xFFFF if share else h)
+            got = hkeys[l, b, h, :s.size]
+            assert got.tobytes() == want.tobytes(), f"keys differ at {(l, b, h)} share={share}"
+
+
+def test_perturbed_keys_many_counters():
+    # 2^20 items in one go: the random words and the defined logarithm agree bit for bit
+    import torch
+    ngc = _ngc()
+    w = synth.workload(2, L=2, B=16, Hkv=2, Hq=12, n_lo=16384, n_hi=16384)
+    lens = synth.lengths(w)
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, 64, w.cap)
+    cache.len.fill_(w.cap)
+    logits = torch.zeros(w.L, w.B, w.Hkv, w.cap, dtype=torch.float32, device="cuda")
+    keys = torch.zeros_like(logits)
+    ws = ngc.allocate_workspace(cache, 1)
+    p = ngc.make_params(noise_scale=1.0, round=77, seed=2 ** 63 + 12345)
+    print("[keys] 2^20 counters", flush=True)
+    ngc.ngc_perturbed_keys(cache, -1, logits, p, keys, ws)
+    torch.cuda.synchronize()
+    hkeys = keys.cpu().numpy()
+    zeros = np.zeros(w.cap, np.float32)
+    for l in range(w.L):
+        for b in range(w.B):
+            for h in range(w.Hkv):
+                want = orc.perturbed_keys(zeros, 1.0, 2 ** 63 + 12345, 77, l, b, h)
+                assert hkeys[l, b, h].tobytes() == want.tobytes(), (l, b, h)
+
+
+# --------------------------------------------------------------- evict -----
+
+def test_config0_tiny():
+    case = host_case(synth.workload(0))
+    cache, kept, sigma, logp, ws = _run_evict(case)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
+    assert all(x == 0 for x in _ngc().read_status(ws))
+
+
+def test_config1_small_rollout_batch():
+    case = host_case(synth.workload(1))
+    cache, kept, sigma, logp, ws = _run_evict(case)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
+    assert all(x == 0 for x in _ngc().read_status(ws))
+
+
+def test_greedy_eval_mode_with_ties():
+    # tau = 0 on logits with many exact ties: index order must decide
+    w = synth.workload(1, B=4, n_lo=1500, n_hi=2048)
+    case = host_case(w)
+    for seg in case.segs:
+        case.logits[seg] = np.round(case.logits[seg] * 4).astype(np.float32) / 4   # ~25 distinct values
+    cache, kept, sigma, logp, ws = _run_evict(case, tau=0.0)
+    _check_against_oracle(case, cache, kept, sigma, logp, 0.0, 0)
+
+
+def test_drift_and_heavy_tail_logits():
+    for idx, n in ((2, 4096), (4, 16384)):
+        w = synth.workload(idx, L=2, B=2, n_lo=n, n_hi=n)
+        case = host_case(w)
+        cache, kept, sigma, logp, ws = _run_evict(case, with_pos=False)
+        _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
+
+
+def test_ragged_7b_shape_reduced():
+    w = synth.workload(3, L=2, B=6)
+    case = host_case(w)
+    cache, kept, sigma, logp, ws = _run_evict(case, rnd=3, with_pos=False)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 3)
+
+
+def test_block_items_and_shared_heads():
+    # the paper's granularity: blocks of 32 rows, one noise draw per (layer, sequence)
+    w = synth.workload(1, L=2, B=3, n_lo=1000, n_hi=2048)
+    case = host_case(w, block=32)
+    cache, kept, sigma, logp, ws = _run_evict(case, block=32, share_heads=1)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0, block=32, share_heads=True)
+
+
+def test_single_layer_call_leaves_other_layers_alone():
+    import torch
+    w = synth.workload(1, L=3, B=2, n_lo=1200, n_hi=1800)
+    case = host_case(w)
+    cache0, _, _ = upload(case)
+    before_k = from_bf16_tensor(cache0.k)
+    cache, kept, sigma, logp, ws = _run_evict(case, layer=1)
+    segs = [s for s in case.segs if s[0] == 1]
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0, segs=segs)
+    after_k = from_bf16_tensor(cache.k)
+    hlen = cache.len.cpu().numpy()
+    for l in (0, 2):
+        assert after_k[l].tobytes() == before_k[l].tobytes()
+        assert (hlen[l] == case.lens[:, None]).all()
+
+
+def test_select_only_moves_nothing():
+    w = synth.workload(1, B=2)
+    case = host_case(w)
+    cache0, _, _ = upload(case)
+    cache, kept, sigma, logp, ws = _run_evict(case, select_only=True)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0, moved=False)
+    assert from_bf16_tensor(cache.k).tobytes() == from_bf16_tensor(cache0.k).tobytes()
+    assert (cache.len.cpu().numpy() == case.lens[None, :, None]).all()
+
+
+def test_no_sigma_no_logp_fast_path():
+    w = synth.workload(1, B=3)
+    case = host_case(w)
+    cache, kept, sigma, logp, ws = _run_evict(case, want_sigma=False, want_logp=False)
+    _check_against_oracle(case, cache, kept, None, None, 1.0, 0)
+
+
+def test_determinism_and_round_dependence():
+    w = synth.workload(1, B=2)
+    case = host_case(w)
+    a = _run_evict(case, rnd=4)
+    b = _run_evict(case, rnd=4)
+    c = _run_evict(case, rnd=5)
+    assert a[1].cpu().numpy().tobytes() == b[1].cpu().numpy().tobytes()
+    assert a[2].cpu().numpy().tobytes() == b[2].cpu().numpy().tobytes()
+    assert from_bf16_tensor(a[0].k).tobytes() == from_bf16_tensor(b[0].k).tobytes()
+    assert a[2].cpu().numpy().tobytes() != c[2].cpu().numpy().tobytes()
+
+
+def test_edge_keep_counts():
+    # K = 0, K = 1, K = n (no-op round), K > n (clamped and counted), empty segment
+    import torch
+    ngc = _ngc()
+    w = synth.workload(0, B=6, n_lo=300, n_hi=300, fixed_keep=None)
+    case = host_case(w)
+    case.keep[0, 0, :] = 0
+    case.keep[0, 1, :] = 1
+    case.keep[0, 2, :] = 300
+    case.keep[0, 3, :] = 299
+    case.keep[0, 4, :] = 150
+    case.keep[0, 5, :] = 150
+    cache, kept, sigma, logp, ws = _run_evict(case)
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
+    assert all(x == 0 for x in ngc.read_status(ws))
+    # clamped keep: 400 > 300 behaves as 300 and is counted once per segment
+    case2 = host_case(w)
+    case2.keep[:] = 150
+    cache2, logits2, keep2 = upload(case2)
+    keep2[0, 2, :] = 400
+    cache2.len[0, 5, :] = 0          # empty segments
+    ws2 = ngc.allocate_workspace(cache2, 400)
+    kept2 = torch.full((1, 6, 2, 400), -1, dtype=torch.int32, device="cuda")
+    sig2 = torch.full_like(kept2, -1)
+    lp2 = torch.zeros(1, 6, 2, dtype=torch.float32, device="cuda")
+    print("[evict] clamped keep + empty segments", flush=True)
+    ngc.ngc_evict(cache2, -1, logits2, keep2, ngc.make_params(seed=w.gumbel_seed), 400, kept2, sig2, lp2, ws2)
+    torch.cuda.synchronize()
+    st = ngc.read_status(ws2)
+    assert st[ngc.STATUS_KEEP_CLAMPED] == 2 + 2      # two heads asked for 400 of 300, two for 150 of 0
+    assert kept2[0, 2, 0, :300].cpu().tolist() == list(range(300))
+    assert cache2.len[0, 2].cpu().tolist() == [300, 300]
+    assert cache2.len[0, 5].cpu().tolist() == [0, 0]
+    assert lp2[0, 5].cpu().tolist() == [0.0, 0.0]
+
+
+def test_argument_errors_are_reported_not_launched():
+    import torch
+    ngc = _ngc()
+    w = synth.workload(0)
+    case = host_case(w)
+    cache, logits, keep = upload(case)
+    ws = ngc.allocate_workspace(cache, 256)
+    kept = torch.zeros(1, 1, 2, 256, dtype=torch.int32, device="cuda")
+    p = ngc.make_params(seed=1)
+    with pytest.raises(ngc.NgcError) as e:
+        ngc.ngc_evict(cache, 5, logits, keep, p, 256, kept, None, None, ws)       # layer out of range
+    assert e.value.code == ngc.NGC_EINVAL
+    with pytest.raises(ngc.NgcError) as e:
+        ngc.ngc_evict(cache, -1, logits, keep, p, 256, kept, None, None, ws[:64])  # workspace too small
+    assert e.value.code == ngc.NGC_ENOSPC
+    with pytest.raises(ngc.NgcError) as e:
+        ngc.ngc_evict(cache, -1, None, keep, p, 256, kept, None, None, ws)         # null logits
+    assert e.value.code == ngc.NGC_EINVAL
+    bad = ngc.make_params(seed=1, block=0)
+    with pytest.raises(ngc.NgcError) as e:
+        ngc.ngc_evict(cache, -1, logits, keep, bad, 256, kept, None, None, ws)
+    assert e.value.code == ngc.NGC_EINVAL
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------ log-prob of given sigma --
+
+def test_subset_logprob_given_actions():
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(5)
+    nseg, stride = 9, 20000
+    n_items = np.array([1, 2, 7, 64, 65, 1000, 4097, 16384, 20000], np.int32)
+    keep = np.array([1, 2, 3, 64, 1, 333, 2000, 5462, 6000], np.int32)
+    logits = np.zeros((nseg, stride), np.float32)
+    sigma = np.zeros((nseg, 6000), np.int32)
+    for s in range(nseg):
+        x = rng.standard_normal(n_items[s]).astype(np.float32)
+        if s >= 6:
+            out = rng.random(n_items[s]) < 0.05
+            x = np.where(out, rng.laplace(0, 4, n_items[s]), x).astype(np.float32)
+        logits[s, :n_items[s]] = x
+        # a sampled order for half the segments, an arbitrary order for the rest
+        if s % 2 == 0:
+            _, sg = orc.evict_select(x, int(keep[s]), 1.0, 11, s, 0, 0, 0)
+        else:
+            sg = rng.permutation(n_items[s])[:keep[s]].astype(np.int32)
+        sigma[s, :keep[s]] = sg
+    d = lambda a: torch.from_numpy(a).cuda()
+    out = torch.zeros(nseg, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(ngc.STATUS_WORDS * 4, dtype=torch.uint8, device="cuda")
+    print("[logprob] given actions", flush=True)
+    ngc.ngc_subset_logprob(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, 6000, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for s in range(nseg):
+        want = oracle_logprob(logits[s, :n_items[s]], sigma[s, :keep[s]])
+        assert got[s] == pytest.approx(want, rel=LOGP_RTOL, abs=1e-5), s
+    assert all(x == 0 for x in ngc.read_status(ws))
+    # a repeated index is counted, not trapped
+    sigma[3, 1] = sigma[3, 0]
+    ngc.ngc_subset_logprob(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, 6000, out, ws)
+    torch.cuda.synchronize()
+    assert ngc.read_status(ws)[ngc.STATUS_BAD_SIGMA] >= 1
+
+
+# --------------------------------------------------------------- append ----
+
+def test_append_rows():
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, L=2, B=3, n_lo=10, n_hi=40)
+    case = host_case(w)
+    cache, _, _ = upload(case, with_pos=True, cap=43)
+    ws = ngc.allocate_workspace(cache, 1)
+    hk0, hv0 = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v)
+    new_k = np.stack([synth.new_token_kv(w, l, 0)[0] for l in range(w.L)])
+    new_v = np.stack([synth.new_token_kv(w, l, 0)[1] for l in range(w.L)])
+    new_pos = torch.tensor([100, 200, 300], dtype=torch.int32, device="cuda")
+    print("[append] all layers, then layer 1 only", flush=True)
+    ngc.ngc_cache_append(cache, -1, to_bf16_tensor(new_k, "cuda"), to_bf16_tensor(new_v, "cuda"), new_pos, ws)
+    ngc.ngc_cache_append(cache, 1, to_bf16_tensor(new_k[1], "cuda"), to_bf16_tensor(new_v[1], "cuda"), new_pos, ws)
+    torch.cuda.synchronize()
+    hk, hv = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v)
+    hlen, hpos = cache.len.cpu().numpy(), cache.pos.cpu().numpy()
+    for (l, b, h) in case.segs:
+        n = int(case.lens[b])
+        assert hlen[l, b, h] == n + (2 if l == 1 else 1)
+        assert hk[l, b, h, :n].tobytes() == hk0[l, b, h, :n].tobytes()
+        assert hk[l, b, h, n].tobytes() == new_k[l, b, h].tobytes()
+        assert hv[l, b, h, n].tobytes() == new_v[l, b, h].tobytes()
+        assert hpos[l, b, h, n] == [100, 200, 300][b]
+        if l == 1:
+            assert hk[l, b, h, n + 1].tobytes() == new_k[l, b, h].tobytes()
+    # a full segment is skipped and counted
+    cache.len.fill_(43)
+    ngc.ngc_cache_append(cache, 0, to_bf16_tensor(new_k[0], "cuda"), to_bf16_tensor(new_v[0], "cuda"), None, ws)
+    torch.cuda.synchronize()
+    assert ngc.read_status(ws)[ngc.STATUS_APPEND_FULL] == w.B * w.Hkv
+    assert (cache.len.cpu().numpy() == 43).all()
