@@ -1,0 +1,335 @@
+#!/usr/bin/env python3
+"""Benchmark of the NGC hot path on one MI355X.
+
+A *step* is one grow-then-evict period of the whole batch: `delta` decode
+token-steps (append one K/V row per segment, then decode attention over the
+surviving rows, all layers) followed by one eviction round (Gumbel-top-k
+sample + ordered-subset log-probability + in-place compaction, all layers)
+that brings every segment back to its budget.  Inputs are synthetic, seeded,
+and resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the design doc for every field).  `value` is tokens/s of
+the whole cycle; the attention-only rate, the round-0 eviction time at peak
+cache and the roofline fractions are reported beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "decode-attn tokens/s + eviction-step µs over evicted cache; % HBM peak"
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default 3: 7B-shaped)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (0 = the workload's)")
+    ap.add_argument("--evict-reps", type=int, default=5, help="timed repetitions of the round-0 eviction")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-layer", action="store_true", help="also time decode attention launched layer by layer")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy first (reference dispatch for the HBM byte counters)")
+    return ap.parse_args()
+
+
+def build_workload(args):
+    from paper_2604_18002_amd import synth
+    over = {}
+    if args.layers:
+        over["L"] = args.layers
+    if args.batch:
+        over["B"] = args.batch
+    return synth.workload(args.config, **over)
+
+
+def keep_budget(w, lens):
+    """Items kept per segment: the retention budget fixed at round 0."""
+    from paper_2604_18002_amd import schedule, synth
+    keep = np.zeros((w.L, w.B, w.Hkv), np.int32)
+    for b in range(w.B):
+        n = int(lens[b])
+        if w.fixed_keep is not None:
+            keep[:, b, :] = min(n, w.fixed_keep)
+        elif w.per_head_budget:
+            total = schedule.keep_count(w.Hkv * n, w.keep_num, w.keep_den)
+            for l in range(w.L):
+                keep[l, b, :] = schedule.split_budget(total, synth.head_budget_weights(w, l, b), np.full(w.Hkv, n))
+        else:
+            keep[:, b, :] = schedule.keep_count(n, w.keep_num, w.keep_den)
+    return keep
+
+
+def attn_bytes(w, seg_rows_total: int, nseg: int) -> float:
+    """Algorithmic bytes of one decode-attention launch: every surviving K and V
+    row once (bf16), plus the queries (bf16) and outputs (fp32)."""
+    return seg_rows_total * 2 * w.D * 2 + nseg * w.G * w.D * (2 + 4)
+
+
+def evict_bytes(w, n_items: np.ndarray, keep: np.ndarray, moved_rows: float, with_sigma=True, with_logp=True) -> float:
+    """Algorithmic bytes of one eviction round: logits read once, kept (and
+    sigma) written, every row that changes place read and written once in K and
+    V, one log-probability per segment."""
+    b = 4.0 * n_items.sum() + 4.0 * keep.sum() * (2 if with_sigma else 1)
+    b += moved_rows * (2 * w.D) * 2 * 2
+    if with_logp:
+        b += 4.0 * keep.size
+    return b
+
+
+def cpu_baseline(w, lens, keep, n_after_mid):
+    """The oracle, as it stands, on one layer of the workload (bounded sample of
+    sequences): one eviction round at the steady-state size and one decode
+    attention step, scaled to a full period and to all layers."""
+    import oracle as orc
+    from paper_2604_18002_amd import synth
+    rng = np.random.default_rng(w.data_seed)
+    nb = min(w.B, 32)
+    t_evict = t_attn = 0.0
+    kmax = int(max(lens)) + w.delta
+    kbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
+    vbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
+    q = synth.queries(w, 0)
+    scale = 1.0 / math.sqrt(w.D)
+    for b in range(nb):
+        for h in range(w.Hkv):
+            K = int(keep[0, b, h])
+            n = K + w.delta
+            s = synth.segment_logits(w, 0, b, h, n)
+            t0 = time.perf_counter()
+            kept, sigma = orc.evict_select(s, K, 1.0, w.gumbel_seed, 1, 0, b, h)
+            orc.logprob_suffix(s, sigma)
+            ka = orc.compact_rows(kbits[:n], kept)
+            va = orc.compact_rows(vbits[:n], kept)
+            t_evict += time.perf_counter() - t0
+            m = int(n_after_mid[0, b, h])
+            t0 = time.perf_counter()
+            orc.decode_attn(q[b, h * w.G:(h + 1) * w.G], kbits[:m], vbits[:m], scale)
+            t_attn += time.perf_counter() - t0
+    period = w.L * (t_evict + w.delta * t_attn)        # one layer measured, L layers, delta token-steps
+    return {
+        "value": nb * w.delta / period, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": f"{nb} of {w.B} sequences, 1 of {w.L} layers: one eviction round (select + log-prob + "
+                  f"compaction) and one decode-attention step at mid-period length, scaled x{w.L} layers and "
+                  f"x{w.delta} token-steps; fp64 single-threaded oracle",
+        "eviction_step_us": w.L * t_evict * 1e6 * (w.B / nb),
+        "decode_attn_tokens_per_s": nb / (w.L * t_attn),
+        "cpu_seconds": t_evict + t_attn,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; every rollout is independent, so more GPUs would only "
+              "replicate this run on disjoint sequences (see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_18002_amd import binding as ngc
+    from paper_2604_18002_amd import synth
+
+    ngc.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    w = build_workload(args)
+    t_setup = time.time()
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1)
+        b.copy_(a)          # the plain copy of known size: 1 GiB read, 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
+
+    # ---------------------------------------------------------------- inputs
+    lens = synth.lengths(w)                                   # [B] peak rows per sequence
+    keep_h = keep_budget(w, lens)                             # [L,B,Hkv]
+    max_keep = int(keep_h.max())
+    cap = w.cap
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, cap, device=dev)
+    synth.fill_normal_bf16_(cache.k, w.data_seed * 2 + 0)
+    synth.fill_normal_bf16_(cache.v, w.data_seed * 2 + 1)
+    logits = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.float32, device=dev)
+    synth.fill_logits_(logits, w, w.data_seed * 2 + 2)
+    len0 = torch.from_numpy(np.broadcast_to(lens[None, :, None], (w.L, w.B, w.Hkv)).copy()).to(dev)
+    keep = torch.from_numpy(keep_h).to(dev)
+    ws = ngc.allocate_workspace(cache, max_keep)
+    nseg = w.L * w.B * w.Hkv
+    kept = torch.empty(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device=dev)
+    sigma = torch.empty_like(kept)
+    logp = torch.empty(w.L, w.B, w.Hkv, dtype=torch.float32, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.data_seed * 2 + 3)
+    q = torch.randn(w.L, w.B, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
+    k_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    v_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty(w.L, w.B, w.Hq, w.D, dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(w.D)
+    hint = max_keep + w.delta
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def evict(rnd):
+        ngc.ngc_evict(cache, -1, logits, keep, ngc.make_params(noise_scale=1.0, round=rnd, seed=w.gumbel_seed),
+                      max_keep, kept, sigma if w.with_logprob else None, logp if w.with_logprob else None, ws)
+
+    # ------------------------------------- P1: round-0 eviction at peak cache
+    # (the rows' values do not matter for timing, so only `len` is restored)
+    p1_ms = []
+    for rep in range(args.evict_reps + 1):
+        cache.len.copy_(len0)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        evict(0)
+        e1.record()
+        torch.cuda.synchronize()
+        if rep > 0:
+            p1_ms.append(e0.elapsed_time(e1))
+    slot = torch.arange(max_keep, device=dev, dtype=torch.int32)
+
+    def moved_rows():
+        """Rows of the last round that changed place (kept index != slot)."""
+        valid = slot < keep.unsqueeze(-1)
+        return float(((kept != slot) & valid).sum().item())
+
+    moved0 = moved_rows()
+    n_items0 = np.broadcast_to(lens[None, :, None], keep_h.shape)
+    p1_bytes = evict_bytes(w, n_items0, keep_h, moved0, w.with_logprob, w.with_logprob)
+    p1_us = 1e3 * float(np.mean(p1_ms))
+
+    # ------------------------------------------- steady-state periods (steps)
+    rows_after = int(keep_h.sum())             # rows in use right after a round
+    attn_events = []
+
+    def period(rnd, record):
+        for t in range(w.delta):
+            ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+            if record:
+                e0, e1 = ev(), ev()
+                e0.record()
+            ngc.ngc_decode_attn(cache, -1, q, scale, hint, out, ws)
+            if record:
+                e1.record()
+                attn_events.append((e0, e1, rows_after + (t + 1) * nseg))
+        if record:
+            e0, e1 = ev(), ev()
+            e0.record()
+        evict(rnd)
+        if record:
+            e1.record()
+            evict_events.append((e0, e1))
+
+    evict_events = []
+    rnd = 1
+    for _ in range(args.warmup):
+        period(rnd, False)
+        rnd += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        period(rnd, True)
+        rnd += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    attn_ms = sum(a.elapsed_time(b) for a, b, _ in attn_events)
+    attn_b = sum(attn_bytes(w, rows, nseg) for _, _, rows in attn_events)
+    n_attn = len(attn_events)
+    steady_evict_ms = [a.elapsed_time(b) for a, b in evict_events]
+    n_mid = keep_h + w.delta // 2
+    steady_bytes = evict_bytes(w, keep_h + w.delta, keep_h, moved_rows(), w.with_logprob, w.with_logprob)
+    steady_us = 1e3 * float(np.mean(steady_evict_ms))
+
+    tokens = w.B * w.delta * args.steps
+    value = tokens / elapsed
+    attn_gbs = attn_b / (attn_ms * 1e-3) / 1e9
+    p1_gbs = p1_bytes / (p1_us * 1e-6) / 1e9
+
+    status = ngc.read_status(ws)
+    assert all(x == 0 for x in status), f"device status words not clean: {status[:8]}"
+    # sanity: lengths are back at the budget after the last round
+    assert torch.equal(cache.len.cpu(), torch.from_numpy(keep_h)), "lengths drifted from the schedule"
+
+    per_layer = None
+    if args.per_layer:
+        reps = 20
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            for l in range(w.L):
+                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        per_layer = {"ms_per_token_step": ms, "tokens_per_s": w.B / (ms * 1e-3),
+                     "hbm_frac": attn_bytes(w, rows_after, nseg) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    line = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"configs[{w.index}] {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} "
+                        f"peak cache {w.n_lo}..{w.n_hi} rows, keep {w.keep_num}/{w.keep_den} (budget rule), "
+                        f"delta={w.delta}, logits {w.logits_kind}, log-prob {'on' if w.with_logprob else 'off'}",
+            "step": f"{w.delta} x (append + decode attention, all {w.L} layers in one launch) + 1 eviction round",
+            "tokens_per_step": w.B * w.delta,
+        },
+        "decode_attn_tokens_per_s": w.B * n_attn / (attn_ms * 1e-3),
+        "decode_attn_ms_per_token_step": attn_ms / n_attn,
+        "eviction_step_us": p1_us,
+        "eviction_step_us_steady": steady_us,
+        "eviction_steady_hbm_frac": steady_bytes / (steady_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {
+            "kernel": "decode_partial_kernel<%d>" % w.D,
+            "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": attn_gbs / HBM_PEAK_GBS, "traffic": None,
+            "bytes_per_launch": attn_b / n_attn, "launch_ms": attn_ms / n_attn, "launches": n_attn,
+        },
+        "roofline_evict": {
+            "kernels": "select_kernel + compact_kernel (round 0 at peak cache)",
+            "bound": "hbm", "achieved": p1_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": p1_gbs / HBM_PEAK_GBS, "traffic": None,
+            "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
+        },
+        "setup_s": t_setup,
+    }
+    if per_layer:
+        line["decode_attn_per_layer_launches"] = per_layer
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, lens, keep_h, n_mid)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

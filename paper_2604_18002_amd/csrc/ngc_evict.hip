@@ -16,6 +16,8 @@ namespace ngc {
 
 // ------------------------------------------------------------ geometry ----
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 struct SegGeom {
     int B, Hkv, cap, block;
 };
@@ -504,12 +506,11 @@ struct CompactArgs {
     int block;
 };
 
-template <int ROW_BYTES>
-__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
+template <int ROW_BYTES, int THREADS = 256, int UNROLL = 8>
+__global__ __launch_bounds__(THREADS) void compact_kernel(CompactArgs a)
 {
-    constexpr int PIECES = ROW_BYTES / 16;       // 16-byte pieces per row
-    constexpr int ROWS_PER_STEP = 256 / PIECES;  // rows covered by one load per thread
-    constexpr int UNROLL = 8;
+    constexpr int PIECES = ROW_BYTES / 16;           // 16-byte pieces per row
+    constexpr int ROWS_PER_STEP = THREADS / PIECES;  // rows covered by one load per thread
     constexpr int TILE_ROWS = ROWS_PER_STEP * UNROLL;
     __shared__ int first_moved;
 
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
     __syncthreads();
     {
         int mine = K;
-        for (int j = tid; j < K; j += 256)
+        for (int j = tid; j < K; j += THREADS)
             if (kept[j] != j) { mine = j; break; }
         if (mine < K) atomicMin(&first_moved, mine);
     }
@@ -537,50 +538,50 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
                           (size_t)seg * a.cap * ROW_BYTES;
     const int piece = tid % PIECES, rsub = tid / PIECES;
     for (int tile = (row_start / TILE_ROWS) * TILE_ROWS; tile < rows_new; tile += TILE_ROWS) {
-        uint4 buf[UNROLL];
-        int srcrow[UNROLL];
+        u32x4 buf[UNROLL];
+        bool moves[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int r = tile + u * ROWS_PER_STEP + rsub;
-            srcrow[u] = -1;
+            int s = r;
             if (r < rows_new) {
                 const int item = (block == 1) ? r : r / block;
-                const int s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
-                if (s != r) {
-                    srcrow[u] = s;
-                    buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)s * ROW_BYTES + piece * 16);
-                }
+                s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
             }
+            moves[u] = (s != r);
+            buf[u] = u32x4{0u, 0u, 0u, 0u};
+            if (moves[u]) buf[u] = *reinterpret_cast<const u32x4 *>(base + (size_t)s * ROW_BYTES + piece * 16);
         }
         __syncthreads();   // every read of this tile has landed
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int r = tile + u * ROWS_PER_STEP + rsub;
-            if (srcrow[u] >= 0)
-                *reinterpret_cast<uint4 *>(base + (size_t)r * ROW_BYTES + piece * 16) = buf[u];
+            if (moves[u]) *reinterpret_cast<u32x4 *>(base + (size_t)r * ROW_BYTES + piece * 16) = buf[u];
         }
     }
 
     if (!is_v) {
         if (a.pos) {
             int32_t *pos = a.pos + (size_t)seg * a.cap;
-            for (int tile = (row_start / 1024) * 1024; tile < rows_new; tile += 1024) {
+            for (int tile = (row_start / (4 * THREADS)) * (4 * THREADS); tile < rows_new; tile += 4 * THREADS) {
                 int32_t val[4];
-                int srcrow[4];
+                bool moves[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int r = tile + u * 256 + tid;
-                    srcrow[u] = -1;
+                    const int r = tile + u * THREADS + tid;
+                    int s = r;
                     if (r < rows_new) {
                         const int item = (block == 1) ? r : r / block;
-                        const int s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
-                        if (s != r) { srcrow[u] = s; val[u] = pos[s]; }
+                        s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
                     }
+                    moves[u] = (s != r);
+                    val[u] = 0;
+                    if (moves[u]) val[u] = pos[s];
                 }
                 __syncthreads();
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (srcrow[u] >= 0) pos[tile + u * 256 + tid] = val[u];
+                    if (moves[u]) pos[tile + u * THREADS + tid] = val[u];
             }
         }
         if (tid == 0) a.len[seg] = rows_new;
