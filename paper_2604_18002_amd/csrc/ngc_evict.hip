@@ -122,8 +122,12 @@ struct SelectArgs {
     int32_t *kept_out;
     int32_t *sigma_out;
     float *logp_out;
-    int32_t *seg_meta;   // [nseg][2]: kept items, rows after compaction
     int32_t *status;
+    // compaction (skipped when k == nullptr)
+    void *k;
+    void *v;
+    int32_t *pos;
+    int32_t *len_out;
     int seg0;
     int max_keep;
     int items_cap;       // ceil(cap / block): size of the code array in LDS
@@ -146,12 +150,19 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, uint64_t valid)
     return m;
 }
 
+// Slots of the small shared scratch array `misc` that outlive the selection.
+constexpr int MISC_KEPT = 35;   // items kept in this segment
+constexpr int MISC_ROWS = 36;   // rows in use after compaction
+constexpr int MISC_FIRST = 37;  // first item that changes place
+
+// Selection of one segment by the whole workgroup.  Leaves the kept count and
+// the new row count in misc[MISC_KEPT], misc[MISC_ROWS] (valid after the next
+// barrier).  Every thread of the workgroup returns at the same point.
 template <int THREADS>
-__global__ __launch_bounds__(THREADS) void select_kernel(SelectArgs a)
+__device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, unsigned char *smem_raw)
 {
     constexpr int NW = THREADS / NGC_WAVE;
     constexpr int HIST = (SEL_BINS > 256 * NW) ? SEL_BINS : 256 * NW;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
     uint32_t *code = reinterpret_cast<uint32_t *>(smem_raw);
     uint32_t *hist = code + a.items_cap;
     int *misc = reinterpret_cast<int *>(hist + HIST);            // 64 ints
@@ -160,7 +171,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(SelectArgs a)
     float *fmisc = reinterpret_cast<float *>(misc);
 
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
-    const int seg = a.seg0 + blockIdx.x;
     int l, b, h;
     seg_coords(seg, a.g, l, b, h);
     const int n = seg_rows(a.len, seg, a.g.cap, a.status);
@@ -179,8 +189,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(SelectArgs a)
 
     if (K == 0) {
         if (tid == 0) {
-            a.seg_meta[2 * seg] = 0;
-            a.seg_meta[2 * seg + 1] = 0;
+            misc[MISC_KEPT] = 0;
+            misc[MISC_ROWS] = 0;
             if (want_logp) a.logp_out[seg] = 0.f;
         }
         return;
@@ -292,8 +302,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(SelectArgs a)
     if (tid == 0) {
         const int last_item = misc[34];
         const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
-        a.seg_meta[2 * seg] = K;
-        a.seg_meta[2 * seg + 1] = (K - 1) * a.g.block + last_rows;
+        misc[MISC_KEPT] = K;
+        misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
     }
     if (!want_sort) return;
 
@@ -489,103 +499,117 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
 // In place: the row that ends at slot j comes from a slot >= j, so a
 // workgroup that walks a segment front to back, reads a whole tile into
 // registers, waits for the tile's reads (barrier) and only then writes, never
-// overwrites a row it (or a later tile) still has to read.  One workgroup per
-// (segment, K-or-V); 16-byte loads and stores; rows that stay where they are
-// are neither read nor written.
+// overwrites a row it (or a later tile) still has to read.  16-byte loads and
+// stores, one full row per ROW_BYTES/16 consecutive lanes; rows that stay
+// where they are are neither read nor written.  K and V tiles travel together
+// so that twice as many loads are in flight.
 
-struct CompactArgs {
-    void *k;
-    void *v;
-    int32_t *pos;
-    int32_t *len;
-    const int32_t *kept;
-    const int32_t *seg_meta;
-    int seg0;
-    int max_keep;
-    int cap;
-    int block;
-};
+__device__ __forceinline__ int source_row(const int32_t *kept, int r, int block)
+{
+    if (block == 1) return kept[r];
+    const int item = r / block;
+    return kept[item] * block + (r - item * block);
+}
 
-template <int ROW_BYTES, int THREADS = 256, int UNROLL = 8>
-__global__ __launch_bounds__(THREADS) void compact_kernel(CompactArgs a)
+template <int ROW_BYTES, int THREADS, int UNROLL>
+__device__ __forceinline__ void compact_kv_inplace(unsigned char *kbase, unsigned char *vbase,
+                                                   const int32_t *kept, int rows_new, int row_start, int block)
 {
     constexpr int PIECES = ROW_BYTES / 16;           // 16-byte pieces per row
     constexpr int ROWS_PER_STEP = THREADS / PIECES;  // rows covered by one load per thread
     constexpr int TILE_ROWS = ROWS_PER_STEP * UNROLL;
-    __shared__ int first_moved;
-
-    const int tid = threadIdx.x;
-    const int seg = a.seg0 + blockIdx.x;
-    const bool is_v = blockIdx.y == 1;
-    const int K = a.seg_meta[2 * seg];
-    const int rows_new = a.seg_meta[2 * seg + 1];
-    const int32_t *kept = a.kept + (size_t)seg * a.max_keep;
-    const int block = a.block;
-
-    // first item that changes place (kept is ascending and kept[j] >= j)
-    if (tid == 0) first_moved = K;
-    __syncthreads();
-    {
-        int mine = K;
-        for (int j = tid; j < K; j += THREADS)
-            if (kept[j] != j) { mine = j; break; }
-        if (mine < K) atomicMin(&first_moved, mine);
-    }
-    __syncthreads();
-    const int row_start = first_moved * block;
-
-    unsigned char *base = reinterpret_cast<unsigned char *>(is_v ? a.v : a.k) +
-                          (size_t)seg * a.cap * ROW_BYTES;
-    const int piece = tid % PIECES, rsub = tid / PIECES;
+    const int piece = threadIdx.x % PIECES, rsub = threadIdx.x / PIECES;
     for (int tile = (row_start / TILE_ROWS) * TILE_ROWS; tile < rows_new; tile += TILE_ROWS) {
-        u32x4 buf[UNROLL];
+        u32x4 kb[UNROLL], vb[UNROLL];
         bool moves[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int r = tile + u * ROWS_PER_STEP + rsub;
-            int s = r;
-            if (r < rows_new) {
-                const int item = (block == 1) ? r : r / block;
-                s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
-            }
+            const int s = (r < rows_new) ? source_row(kept, r, block) : r;
             moves[u] = (s != r);
-            buf[u] = u32x4{0u, 0u, 0u, 0u};
-            if (moves[u]) buf[u] = *reinterpret_cast<const u32x4 *>(base + (size_t)s * ROW_BYTES + piece * 16);
+            kb[u] = u32x4{0u, 0u, 0u, 0u};
+            vb[u] = u32x4{0u, 0u, 0u, 0u};
+            if (moves[u]) {
+                const size_t off = (size_t)s * ROW_BYTES + piece * 16;
+                kb[u] = *reinterpret_cast<const u32x4 *>(kbase + off);
+                vb[u] = *reinterpret_cast<const u32x4 *>(vbase + off);
+            }
         }
         __syncthreads();   // every read of this tile has landed
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int r = tile + u * ROWS_PER_STEP + rsub;
-            if (moves[u]) *reinterpret_cast<u32x4 *>(base + (size_t)r * ROW_BYTES + piece * 16) = buf[u];
-        }
-    }
-
-    if (!is_v) {
-        if (a.pos) {
-            int32_t *pos = a.pos + (size_t)seg * a.cap;
-            for (int tile = (row_start / (4 * THREADS)) * (4 * THREADS); tile < rows_new; tile += 4 * THREADS) {
-                int32_t val[4];
-                bool moves[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int r = tile + u * THREADS + tid;
-                    int s = r;
-                    if (r < rows_new) {
-                        const int item = (block == 1) ? r : r / block;
-                        s = (block == 1) ? kept[item] : kept[item] * block + (r - item * block);
-                    }
-                    moves[u] = (s != r);
-                    val[u] = 0;
-                    if (moves[u]) val[u] = pos[s];
-                }
-                __syncthreads();
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (moves[u]) pos[tile + u * THREADS + tid] = val[u];
+            if (moves[u]) {
+                const size_t off = (size_t)r * ROW_BYTES + piece * 16;
+                *reinterpret_cast<u32x4 *>(kbase + off) = kb[u];
+                *reinterpret_cast<u32x4 *>(vbase + off) = vb[u];
             }
         }
-        if (tid == 0) a.len[seg] = rows_new;
     }
+}
+
+template <int THREADS>
+__device__ __forceinline__ void compact_pos_inplace(int32_t *pos, const int32_t *kept, int rows_new,
+                                                    int row_start, int block)
+{
+    constexpr int TILE = 4 * THREADS;
+    for (int tile = (row_start / TILE) * TILE; tile < rows_new; tile += TILE) {
+        int32_t val[4];
+        bool moves[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = tile + u * THREADS + threadIdx.x;
+            const int s = (r < rows_new) ? source_row(kept, r, block) : r;
+            moves[u] = (s != r);
+            val[u] = 0;
+            if (moves[u]) val[u] = pos[s];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (moves[u]) pos[tile + u * THREADS + threadIdx.x] = val[u];
+    }
+}
+
+// One workgroup per segment: sample, score, then move the survivors.  While a
+// workgroup is in its (ALU/LDS bound) selection phase, the other workgroups of
+// the grid keep the memory system busy with their compaction phase.
+template <int THREADS, int ROW_BYTES>
+__global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    constexpr int HIST = (SEL_BINS > 256 * NW) ? SEL_BINS : 256 * NW;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    int *misc = reinterpret_cast<int *>(reinterpret_cast<uint32_t *>(smem_raw) + a.items_cap + HIST);
+    const int seg = a.seg0 + blockIdx.x;
+
+    select_segment<THREADS>(a, seg, smem_raw);
+    if (a.k == nullptr) return;   // selection only
+
+    if (threadIdx.x == 0) misc[MISC_FIRST] = 0x7FFFFFFF;
+    __syncthreads();   // publishes misc[] and this workgroup's kept_out writes
+    const int K = misc[MISC_KEPT];
+    const int rows_new = misc[MISC_ROWS];
+    const int32_t *kept = a.kept_out + (size_t)seg * a.max_keep;
+    // first item that changes place (kept is ascending and kept[j] >= j)
+    {
+        int mine = K;
+        for (int j = threadIdx.x; j < K; j += THREADS)
+            if (kept[j] != j) { mine = j; break; }
+        if (mine < K) atomicMin(&misc[MISC_FIRST], mine);
+    }
+    __syncthreads();
+    const int first = misc[MISC_FIRST];
+    if (first < K) {
+        const int row_start = first * a.g.block;
+        const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
+        compact_kv_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                  kept, rows_new, row_start, a.g.block);
+        if (a.pos)
+            compact_pos_inplace<THREADS>(a.pos + (size_t)seg * a.g.cap, kept, rows_new, row_start, a.g.block);
+    }
+    if (threadIdx.x == 0) a.len_out[seg] = rows_new;
 }
 
 // -------------------------------------------------------------- append ----
@@ -717,36 +741,29 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
 
     int32_t *status = reinterpret_cast<int32_t *>(ws);
-    int32_t *seg_meta = status + NGC_STATUS_WORDS;
+    const bool move_rows = !(p->flags & NGC_EVICT_SELECT_ONLY);
 
     SelectArgs sa;
     sa.logits = logits; sa.len = c->len; sa.keep = keep;
     sa.kept_out = kept_out; sa.sigma_out = sigma_out; sa.logp_out = logp_out;
-    sa.seg_meta = seg_meta; sa.status = status;
+    sa.status = status;
+    sa.k = move_rows ? c->k : nullptr; sa.v = c->v; sa.pos = c->pos; sa.len_out = c->len;
     sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
     sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
     sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
 
     hipStream_t st = (hipStream_t)stream;
-    if (threads == 1024) {
-        NGC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<1024>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(select_kernel<1024>, dim3(nseg), dim3(1024), lds, st, sa);
-    } else {
-        NGC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<256>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(select_kernel<256>, dim3(nseg), dim3(256), lds, st, sa);
-    }
-    NGC_HIP_CHECK(hipGetLastError());
-
-    if (!(p->flags & NGC_EVICT_SELECT_ONLY)) {
-        CompactArgs ca{c->k, c->v, c->pos, c->len, kept_out, seg_meta, seg0, max_keep, c->cap, p->block};
-        if (c->D == 128)
-            hipLaunchKernelGGL(compact_kernel<256>, dim3(nseg, 2), dim3(256), 0, st, ca);
-        else
-            hipLaunchKernelGGL(compact_kernel<128>, dim3(nseg, 2), dim3(256), 0, st, ca);
-        NGC_HIP_CHECK(hipGetLastError());
-    }
+    const void *fn;
+    if (threads == 1024)
+        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<1024, 256>)
+                           : reinterpret_cast<const void *>(&evict_kernel<1024, 128>);
+    else
+        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<256, 256>)
+                           : reinterpret_cast<const void *>(&evict_kernel<256, 128>);
+    if (lds > 64 * 1024)
+        NGC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    void *kargs[] = {&sa};
+    NGC_HIP_CHECK(hipLaunchKernel(fn, dim3(nseg), dim3(threads), kargs, lds, st));
     return NGC_OK;
 }
 
