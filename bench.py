@@ -30,6 +30,14 @@ if ROOT not in sys.path:
 METRIC = "decode-attn tokens/s + eviction-step µs over evicted cache; % HBM peak"
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic per dispatch (bytes) measured with rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE on the unmodified workload, each counter scaled by what it
+# reads for a plain 1 GiB copy (summaries under profiles/).  Keyed by
+# (config, L, B); other shapes report null.
+MEASURED_TRAFFIC = {
+    (3, 28, 128): {"decode": 19.6552e9, "evict": 36.4068e9},
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -91,43 +99,59 @@ def evict_bytes(w, n_items: np.ndarray, keep: np.ndarray, moved_rows: float, wit
     return b
 
 
-def cpu_baseline(w, lens, keep, n_after_mid):
-    """The oracle, as it stands, on one layer of the workload (bounded sample of
-    sequences): one eviction round at the steady-state size and one decode
-    attention step, scaled to a full period and to all layers."""
+def cpu_baseline(w, lens, keep, n_after_mid, budget_s=12.0):
+    """The oracle, as it stands, timed on segments of the workload until about
+    `budget_s` seconds of CPU work are spent: per segment one eviction round at
+    the steady-state size (select + log-prob + compaction) and one
+    decode-attention step at the mid-period length.  Scaled to a whole period
+    (delta token-steps, all segments)."""
     import oracle as orc
     from paper_2604_18002_amd import synth
     rng = np.random.default_rng(w.data_seed)
-    nb = min(w.B, 32)
-    t_evict = t_attn = 0.0
-    kmax = int(max(lens)) + w.delta
+    kmax = int(keep.max()) + w.delta
     kbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
     vbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
-    q = synth.queries(w, 0)
     scale = 1.0 / math.sqrt(w.D)
-    for b in range(nb):
-        for h in range(w.Hkv):
-            K = int(keep[0, b, h])
-            n = K + w.delta
-            s = synth.segment_logits(w, 0, b, h, n)
-            t0 = time.perf_counter()
-            kept, sigma = orc.evict_select(s, K, 1.0, w.gumbel_seed, 1, 0, b, h)
-            orc.logprob_suffix(s, sigma)
-            ka = orc.compact_rows(kbits[:n], kept)
-            va = orc.compact_rows(vbits[:n], kept)
-            t_evict += time.perf_counter() - t0
-            m = int(n_after_mid[0, b, h])
-            t0 = time.perf_counter()
-            orc.decode_attn(q[b, h * w.G:(h + 1) * w.G], kbits[:m], vbits[:m], scale)
-            t_attn += time.perf_counter() - t0
-    period = w.L * (t_evict + w.delta * t_attn)        # one layer measured, L layers, delta token-steps
+    t_evict = t_attn = 0.0
+    nsegs = 0
+    done = False
+    for l in range(w.L):
+        q = synth.queries(w, l)
+        for b in range(w.B):
+            for h in range(w.Hkv):
+                K = int(keep[l, b, h])
+                n = K + w.delta
+                s = synth.segment_logits(w, l, b, h, n, rnd=1)
+                t0 = time.perf_counter()
+                kept, sigma = orc.evict_select(s, K, 1.0, w.gumbel_seed, 1, l, b, h)
+                if w.with_logprob:
+                    orc.logprob_suffix(s, sigma)
+                orc.compact_rows(kbits[:n], kept)
+                orc.compact_rows(vbits[:n], kept)
+                t_evict += time.perf_counter() - t0
+                m = int(n_after_mid[l, b, h])
+                t0 = time.perf_counter()
+                orc.decode_attn(q[b, h * w.G:(h + 1) * w.G], kbits[:m], vbits[:m], scale)
+                t_attn += time.perf_counter() - t0
+                nsegs += 1
+                done = (t_evict + t_attn) >= budget_s
+                if done:
+                    break
+            if done:
+                break
+        if done:
+            break
+    total_segs = w.L * w.B * w.Hkv
+    per_seg_period = (t_evict + w.delta * t_attn) / nsegs      # seconds of CPU per segment and period
+    period = per_seg_period * total_segs
     return {
-        "value": nb * w.delta / period, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-        "sample": f"{nb} of {w.B} sequences, 1 of {w.L} layers: one eviction round (select + log-prob + "
-                  f"compaction) and one decode-attention step at mid-period length, scaled x{w.L} layers and "
-                  f"x{w.delta} token-steps; fp64 single-threaded oracle",
-        "eviction_step_us": w.L * t_evict * 1e6 * (w.B / nb),
-        "decode_attn_tokens_per_s": nb / (w.L * t_attn),
+        "value": w.B * w.delta / period, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": f"{nsegs} of {total_segs} (layer, sequence, head) segments: per segment one eviction round "
+                  f"(select + log-prob + compaction, {'budget + delta -> budget'}) and one decode-attention step at "
+                  f"mid-period length; scaled to all segments and {w.delta} token-steps per period; "
+                  f"fp64 single-threaded oracle",
+        "eviction_step_us": 1e6 * t_evict / nsegs * total_segs,
+        "decode_attn_tokens_per_s": w.B / (t_attn / nsegs * total_segs),
         "cpu_seconds": t_evict + t_attn,
     }
 
@@ -313,13 +337,15 @@ def main():
         "roofline": {
             "kernel": "decode_partial_kernel<%d>" % w.D,
             "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": attn_gbs / HBM_PEAK_GBS, "traffic": None,
+            "frac": attn_gbs / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("decode"),
             "bytes_per_launch": attn_b / n_attn, "launch_ms": attn_ms / n_attn, "launches": n_attn,
         },
         "roofline_evict": {
             "kernels": "select_kernel + compact_kernel (round 0 at peak cache)",
             "bound": "hbm", "achieved": p1_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": p1_gbs / HBM_PEAK_GBS, "traffic": None,
+            "frac": p1_gbs / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("evict"),
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
         },
         "setup_s": t_setup,
