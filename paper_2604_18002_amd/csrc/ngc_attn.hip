@@ -336,15 +336,20 @@ using namespace ngc;
 namespace {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
-constexpr int TARGET_WORKGROUPS = 4096;
+// Split only as far as needed to give every workgroup slot of the chip (256
+// CUs x 2 resident workgroups) one piece of work: measured on MI355X, fewer and
+// longer workgroups beat finer splits (partials and the merge kernel cost more
+// than the tail they save).
+constexpr int TARGET_WORKGROUPS = 512;
 constexpr int MAX_SPLITS = 64;
-constexpr int MIN_TILES_PER_SPLIT = 2 * ATT_WAVES;   // 256 rows
+constexpr int MIN_TILES_PER_SPLIT = 16;   // 512 rows
 
 int splits_for(int nseg_launch, int max_len)
 {
-    int s = (TARGET_WORKGROUPS + nseg_launch - 1) / nseg_launch;
+    const int target = TARGET_WORKGROUPS, min_tiles = MIN_TILES_PER_SPLIT;
+    int s = (target + nseg_launch - 1) / nseg_launch;
     const int tiles = (max_len + ATT_TILE - 1) / ATT_TILE;
-    int by_len = tiles / MIN_TILES_PER_SPLIT;
+    int by_len = tiles / min_tiles;
     if (by_len < 1) by_len = 1;
     if (s > by_len) s = by_len;
     if (s > MAX_SPLITS) s = MAX_SPLITS;

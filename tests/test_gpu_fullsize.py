@@ -1,0 +1,102 @@
+"""Parity at the full benchmark sizes (configs 2-4), in the launch configuration
+bench.py times (all layers in one launch): the caches are filled on the device,
+a sample of segments is generated on the host and uploaded, and exactly those
+segments are compared with the oracle after evict -> append -> attend."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2604_18002_amd import synth
+
+from _harness import host_case, keep_table, oracle_evict_segment, to_bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_segments(w, count, seed):
+    rng = np.random.default_rng(seed)
+    segs = {(0, 0, 0), (w.L - 1, w.B - 1, w.Hkv - 1)}
+    while len(segs) < count:
+        segs.add((int(rng.integers(w.L)), int(rng.integers(w.B)), int(rng.integers(w.Hkv))))
+    return sorted(segs)
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_full_size_sampled_segments(idx):
+    import torch
+    from paper_2604_18002_amd import binding as ngc
+    ngc.load_library()
+    w = synth.workload(idx)
+    segs = _sample_segments(w, 24, 100 + idx)
+    case = host_case(w, segs)
+    keep_h = keep_table(w, case.lens)
+    case.keep = keep_h
+    max_keep = int(keep_h.max())
+    print(f"[full] workload={w.name} L={w.L} B={w.B} Hkv={w.Hkv} cap={w.cap} max_keep={max_keep} "
+          f"K/V bytes={2 * w.L * w.B * w.Hkv * w.cap * w.D * 2 / 1e9:.1f} GB", flush=True)
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, w.cap)
+    synth.fill_normal_bf16_(cache.k, 1)
+    synth.fill_normal_bf16_(cache.v, 2)
+    logits = torch.empty(w.L, w.B, w.Hkv, w.cap, dtype=torch.float32, device="cuda")
+    synth.fill_logits_(logits, w, 3)
+    cache.len.copy_(torch.from_numpy(np.broadcast_to(case.lens[None, :, None], (w.L, w.B, w.Hkv)).copy()))
+    for seg in segs:
+        l, b, h = seg
+        n = case.k[seg].shape[0]
+        cache.k[l, b, h, :n] = to_bf16_tensor(case.k[seg], "cuda")
+        cache.v[l, b, h, :n] = to_bf16_tensor(case.v[seg], "cuda")
+        logits[l, b, h, :n] = torch.from_numpy(case.logits[seg]).cuda()
+    keep = torch.from_numpy(keep_h).cuda()
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.empty(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device="cuda")
+    sigma = torch.empty_like(kept)
+    logp = torch.empty(w.L, w.B, w.Hkv, dtype=torch.float32, device="cuda")
+    p = ngc.make_params(noise_scale=1.0, round=0, seed=w.gumbel_seed)
+    print("[full] evict, all layers", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    k_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    v_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    q = torch.randn(w.L, w.B, w.Hq, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty(w.L, w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    print("[full] append + decode attention, all layers", flush=True)
+    ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+    scale = 1.0 / np.sqrt(w.D)
+    ngc.ngc_decode_attn(cache, -1, q, scale, max_keep + w.delta, out, ws)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+    # lengths everywhere: budget + 1
+    assert torch.equal(cache.len.cpu(), torch.from_numpy(keep_h) + 1)
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    for seg in segs:
+        l, b, h = seg
+        okept, osig, olp, ka, va = oracle_evict_segment(case, seg, 1.0, w.gumbel_seed, 0)
+        K = okept.size
+        assert kept[l, b, h, :K].cpu().numpy().tolist() == okept.tolist(), seg
+        assert sigma[l, b, h, :K].cpu().numpy().tolist() == osig.tolist(), seg
+        assert float(logp[l, b, h]) == pytest.approx(olp, rel=1e-4), seg
+        assert bits(cache.k[l, b, h, :K]).tobytes() == ka.tobytes(), seg
+        assert bits(cache.v[l, b, h, :K]).tobytes() == va.tobytes(), seg
+        kk = np.concatenate([ka, bits(k_new[l, b, h])[None]])
+        vv = np.concatenate([va, bits(v_new[l, b, h])[None]])
+        want = orc.decode_attn(bits(q[l, b, h * w.G:(h + 1) * w.G]), kk, vv, scale)
+        got = out[l, b, h * w.G:(h + 1) * w.G].cpu().numpy()
+        assert np.abs(got - want).max() <= 2e-3, (seg, np.abs(got - want).max())
+    # property that holds at any size: kept lists are strictly ascending and within range everywhere
+    idx_ok = torch.ones((), dtype=torch.bool, device="cuda")
+    slot = torch.arange(max_keep, device="cuda")
+    valid = slot < keep.unsqueeze(-1)
+    asc = (kept[..., 1:] > kept[..., :-1]) | ~valid[..., 1:]
+    n0 = torch.from_numpy(np.broadcast_to(case.lens[None, :, None], keep_h.shape).copy()).cuda()
+    in_range = ((kept >= 0) & (kept < n0.unsqueeze(-1))) | ~valid
+    assert bool(asc.all() & in_range.all() & idx_ok)
+    # sigma is a permutation of kept in every segment
+    ssort = torch.where(valid, sigma, torch.full_like(sigma, 2 ** 30)).sort(dim=-1).values
+    ksort = torch.where(valid, kept, torch.full_like(kept, 2 ** 30))
+    assert torch.equal(ssort, ksort)
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(logp).all())
