@@ -212,8 +212,9 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def evict(rnd):
-        ngc.ngc_evict(cache, -1, logits, keep, ngc.make_params(noise_scale=1.0, round=rnd, seed=w.gumbel_seed),
+    def evict(rnd, flags=0):
+        ngc.ngc_evict(cache, -1, logits, keep,
+                      ngc.make_params(noise_scale=1.0, round=rnd, seed=w.gumbel_seed, flags=flags),
                       max_keep, kept, sigma if w.with_logprob else None, logp if w.with_logprob else None, ws)
 
     # ------------------------------------- P1: round-0 eviction at peak cache
@@ -294,6 +295,42 @@ def main():
     # sanity: lengths are back at the budget after the last round
     assert torch.equal(cache.len.cpu(), torch.from_numpy(keep_h)), "lengths drifted from the schedule"
 
+    # ---- the same rounds with the unordered (hole filling) arrangement: same sample, fewer rows moved
+    def timed_evict(rnd, flags):
+        e0, e1 = ev(), ev()
+        e0.record()
+        evict(rnd, flags)
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1)
+
+    def unordered_moved():
+        valid = slot < keep.unsqueeze(-1)
+        return float(((kept >= keep.unsqueeze(-1)) & valid).sum().item())
+
+    un_p1, un_steady = [], []
+    for rep in range(3):
+        cache.len.copy_(len0)
+        torch.cuda.synchronize()
+        un_p1.append(timed_evict(0, ngc.EVICT_UNORDERED))
+    un_p1_moved = unordered_moved()
+    for rep in range(3):
+        for t in range(w.delta):
+            ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+        torch.cuda.synchronize()
+        un_steady.append(timed_evict(rnd + rep, ngc.EVICT_UNORDERED))
+    un_steady_moved = unordered_moved()
+    un_p1_us, un_steady_us = float(np.mean(un_p1[1:])), float(np.mean(un_steady[1:]))
+    un_p1_bytes = evict_bytes(w, n_items0, keep_h, un_p1_moved, w.with_logprob, w.with_logprob)
+    un_steady_bytes = evict_bytes(w, keep_h + w.delta, keep_h, un_steady_moved, w.with_logprob, w.with_logprob)
+    unordered = {
+        "what": "same rounds with NGC_EVICT_UNORDERED (kept rows beyond slot K fill the freed slots below K)",
+        "eviction_step_us": un_p1_us, "moved_rows": un_p1_moved, "bytes_per_round": un_p1_bytes,
+        "hbm_frac": un_p1_bytes / (un_p1_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "eviction_step_us_steady": un_steady_us, "moved_rows_steady": un_steady_moved,
+        "hbm_frac_steady": un_steady_bytes / (un_steady_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+    }
+
     per_layer = None
     if args.per_layer:
         reps = 20
@@ -348,6 +385,7 @@ def main():
             "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("evict"),
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
         },
+        "eviction_unordered": unordered,
         "setup_s": t_setup,
     }
     if per_layer:

@@ -61,8 +61,9 @@ extern "C" {
 
 /* Non-owning view of a KV cache in device memory.
  *   k, v : bf16, dense [L][B][Hkv][cap][D], 16-byte aligned.  Rows [0, len) of
- *          a segment are the surviving entries in ascending order of their
- *          original position; rows >= len are unspecified.
+ *          a segment are the surviving entries (in ascending order of their
+ *          original position unless a round used NGC_EVICT_UNORDERED); rows
+ *          >= len are unspecified.
  *   len  : int32 [L][B][Hkv], rows in use per segment (ragged).
  *   pos  : optional int32 [L][B][Hkv][cap], original token index of each row
  *          (moved together with the rows), or NULL.
@@ -86,8 +87,15 @@ typedef struct ngc_cache {
  *   round        eviction round counter; with `seed` it names the draw, the
  *                same (seed, round) reproduces the same sample.
  *   flags        NGC_EVICT_SELECT_ONLY: sample (and score) but move nothing
- *                and leave `len` untouched.                                   */
+ *                and leave `len` untouched.
+ *                NGC_EVICT_UNORDERED (block == 1 only): instead of packing the
+ *                survivors in ascending order, leave the kept rows below slot
+ *                K in place and move the i-th kept row at or beyond slot K
+ *                into the i-th freed slot below K (both counted ascending).
+ *                Same surviving set, far fewer rows moved; the cache is then
+ *                no longer in order of original position (pos still names it). */
 #define NGC_EVICT_SELECT_ONLY 1u
+#define NGC_EVICT_UNORDERED   2u
 typedef struct ngc_evict_params {
     int32_t  block;
     int32_t  share_heads;

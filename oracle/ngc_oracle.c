@@ -274,6 +274,36 @@ int32_t orc_compact_i32(const int32_t *src, int32_t *dst, int32_t n_rows,
     return out;
 }
 
+/* Unordered variant ("fill the holes", single rows only): with K kept rows,
+ * slots [0, K) that lose their row (holes, ascending) receive, in order, the
+ * kept rows that sit at or beyond slot K (tails, ascending); kept rows already
+ * below K stay where they are.  Same surviving set as orc_compact_rows, other
+ * arrangement, far fewer rows moved.  Works on a copy: dst must not alias src.
+ * Returns K. */
+int32_t orc_compact_rows_unordered(const uint16_t *src, uint16_t *dst, int32_t n_rows,
+                                   int32_t row_elems, const int32_t *kept, int32_t K)
+{
+    unsigned char *is_kept = (unsigned char *)calloc((size_t)(n_rows > 0 ? n_rows : 1), 1);
+    if (!is_kept) return -1;
+    for (int32_t j = 0; j < K; ++j) is_kept[kept[j]] = 1;
+    /* rows that stay */
+    for (int32_t r = 0; r < K && r < n_rows; ++r)
+        if (is_kept[r])
+            memcpy(dst + (size_t)r * row_elems, src + (size_t)r * row_elems,
+                   sizeof(uint16_t) * (size_t)row_elems);
+    /* i-th hole <- i-th tail */
+    int32_t hole = 0;
+    for (int32_t t = K; t < n_rows; ++t) {
+        if (!is_kept[t]) continue;
+        while (is_kept[hole]) ++hole;
+        memcpy(dst + (size_t)hole * row_elems, src + (size_t)t * row_elems,
+               sizeof(uint16_t) * (size_t)row_elems);
+        ++hole;
+    }
+    free(is_kept);
+    return K;
+}
+
 /* ---------------------------------------------------------- attention --- */
 
 static double bf16_to_double(uint16_t h)

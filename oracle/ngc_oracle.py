@@ -56,6 +56,8 @@ def _L():
             fn.restype = C.c_double
         lib.orc_compact_rows.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32]
         lib.orc_compact_rows.restype = C.c_int32
+        lib.orc_compact_rows_unordered.argtypes = [u16p, u16p, C.c_int32, C.c_int32, i32p, C.c_int32]
+        lib.orc_compact_rows_unordered.restype = C.c_int32
         lib.orc_compact_i32.argtypes = [i32p, i32p, C.c_int32, C.c_int32, i32p, C.c_int32]
         lib.orc_compact_i32.restype = C.c_int32
         lib.orc_decode_attn.argtypes = [u16p, u16p, u16p, C.c_int32, C.c_int32, C.c_int32,
@@ -144,6 +146,19 @@ def compact_rows(rows_u16, kept, block: int = 1) -> np.ndarray:
     dst = np.zeros_like(src)
     n_new = _L().orc_compact_rows(_p(src, C.c_uint16), _p(dst, C.c_uint16), n, D, block,
                                   _p(kp, C.c_int32), kp.size)
+    return dst[:n_new].copy()
+
+
+def compact_rows_unordered(rows_u16, kept) -> np.ndarray:
+    """Hole-filling arrangement of the same survivors (single rows): [K, D]."""
+    src = _arr(rows_u16, np.uint16)
+    n, D = src.shape
+    kp = _arr(kept, np.int32)
+    dst = np.zeros_like(src)
+    n_new = _L().orc_compact_rows_unordered(_p(src, C.c_uint16), _p(dst, C.c_uint16), n, D,
+                                            _p(kp, C.c_int32), kp.size)
+    if n_new < 0:
+        raise MemoryError
     return dst[:n_new].copy()
 
 

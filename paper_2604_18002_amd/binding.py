@@ -28,6 +28,7 @@ STATUS_APPEND_FULL = 3
 STATUS_BAD_SIGMA = 4
 
 EVICT_SELECT_ONLY = 1
+EVICT_UNORDERED = 2
 
 EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn")

@@ -128,6 +128,7 @@ struct SelectArgs {
     void *v;
     int32_t *pos;
     int32_t *len_out;
+    int unordered;       // 1: fill the holes below K with the kept rows beyond K (block == 1 only)
     int seg0;
     int max_keep;
     int items_cap;       // ceil(cap / block): size of the code array in LDS
@@ -150,6 +151,60 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, uint64_t valid)
     return m;
 }
 
+// Unordered arrangement (single rows): kept rows below slot K stay; the i-th
+// kept row at or beyond K moves into the i-th free slot below K.  Sources and
+// destinations are disjoint, so there is no ordering to respect and no barrier.
+// `kept` is the ascending kept list in LDS.  kept[0 .. jstar) are the kept rows
+// below K; the i-th number missing from that list is i + #{p : kept[p] - p <= i}.
+template <int ROW_BYTES, int THREADS, int UNROLL>
+__device__ __forceinline__ void fill_holes_inplace(unsigned char *kbase, unsigned char *vbase, int32_t *pos,
+                                                   const uint16_t *kept, int K)
+{
+    constexpr int PIECES = ROW_BYTES / 16;
+    constexpr int ROWS_PER_STEP = THREADS / PIECES;
+    int lo = 0, hi = K;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((int)kept[mid] < K) lo = mid + 1; else hi = mid;
+    }
+    const int jstar = lo, movers = K - jstar;
+    auto hole_of = [&](int i) {
+        int a = 0, b = jstar;
+        while (a < b) {
+            const int mid = (a + b) >> 1;
+            if ((int)kept[mid] - mid <= i) a = mid + 1; else b = mid;
+        }
+        return i + a;
+    };
+    const int piece = threadIdx.x % PIECES, rsub = threadIdx.x / PIECES;
+    for (int i0 = 0; i0 < movers; i0 += ROWS_PER_STEP * UNROLL) {
+        u32x4 kb[UNROLL], vb[UNROLL];
+        int dst[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int i = i0 + u * ROWS_PER_STEP + rsub;
+            dst[u] = -1;
+            kb[u] = u32x4{0u, 0u, 0u, 0u};
+            vb[u] = u32x4{0u, 0u, 0u, 0u};
+            if (i < movers) {
+                const size_t off = (size_t)kept[jstar + i] * ROW_BYTES + piece * 16;
+                kb[u] = *reinterpret_cast<const u32x4 *>(kbase + off);
+                vb[u] = *reinterpret_cast<const u32x4 *>(vbase + off);
+                dst[u] = hole_of(i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (dst[u] >= 0) {
+                const size_t off = (size_t)dst[u] * ROW_BYTES + piece * 16;
+                *reinterpret_cast<u32x4 *>(kbase + off) = kb[u];
+                *reinterpret_cast<u32x4 *>(vbase + off) = vb[u];
+            }
+    }
+    if (pos)
+        for (int i = threadIdx.x; i < movers; i += THREADS) pos[hole_of(i)] = pos[kept[jstar + i]];
+}
+
 // Slots of the small shared scratch array `misc` that outlive the selection.
 constexpr int MISC_KEPT = 35;   // items kept in this segment
 constexpr int MISC_ROWS = 36;   // rows in use after compaction
@@ -158,7 +213,7 @@ constexpr int MISC_FIRST = 37;  // first item that changes place
 // Selection of one segment by the whole workgroup.  Leaves the kept count and
 // the new row count in misc[MISC_KEPT], misc[MISC_ROWS] (valid after the next
 // barrier).  Every thread of the workgroup returns at the same point.
-template <int THREADS>
+template <int THREADS, int ROW_BYTES>
 __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, unsigned char *smem_raw)
 {
     constexpr int NW = THREADS / NGC_WAVE;
@@ -186,6 +241,7 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     const float *row = a.logits + (size_t)seg * a.g.cap;
     const bool want_logp = a.logp_out != nullptr;
     const bool want_sort = want_logp || a.sigma_out != nullptr;
+    const bool fill_holes = a.unordered && a.k != nullptr;
 
     if (K == 0) {
         if (tid == 0) {
@@ -288,7 +344,7 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
         if (sel) {
             const int slot = gt_before + (eq_before < need ? eq_before : need);
             kept_row[slot] = t;
-            if (want_sort) idxA[slot] = (uint16_t)t;
+            if (want_sort || fill_holes) idxA[slot] = (uint16_t)t;
             if (slot == K - 1) misc[34] = t;   // highest kept index
         } else if (in && want_logp) {
             float x = row[t];
@@ -304,6 +360,13 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
         const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
         misc[MISC_KEPT] = K;
         misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
+    }
+    if (fill_holes) {
+        // idxA still holds the kept list in ascending order (the sort below permutes it)
+        const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
+        fill_holes_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                  a.pos ? a.pos + (size_t)seg * a.g.cap : nullptr, idxA, K);
     }
     if (!want_sort) return;
 
@@ -583,7 +646,7 @@ __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
     int *misc = reinterpret_cast<int *>(reinterpret_cast<uint32_t *>(smem_raw) + a.items_cap + HIST);
     const int seg = a.seg0 + blockIdx.x;
 
-    select_segment<THREADS>(a, seg, smem_raw);
+    select_segment<THREADS, ROW_BYTES>(a, seg, smem_raw);
     if (a.k == nullptr) return;   // selection only
 
     if (threadIdx.x == 0) misc[MISC_FIRST] = 0x7FFFFFFF;
@@ -591,6 +654,10 @@ __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
     const int K = misc[MISC_KEPT];
     const int rows_new = misc[MISC_ROWS];
     const int32_t *kept = a.kept_out + (size_t)seg * a.max_keep;
+    if (a.unordered) {   // rows were moved right after the kept list was known
+        if (threadIdx.x == 0) a.len_out[seg] = rows_new;
+        return;
+    }
     // first item that changes place (kept is ascending and kept[j] >= j)
     {
         int mine = K;
@@ -724,6 +791,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     int rc = check_cache(c);
     if (rc) return rc;
     if (!logits || !keep || !p || !kept_out || !ws || p->block < 1 || max_keep < 1) return NGC_EINVAL;
+    if ((p->flags & NGC_EVICT_UNORDERED) && p->block != 1) return NGC_EUNSUPPORTED;
     int seg0, nseg;
     rc = layer_range(c, layer, &seg0, &nseg);
     if (rc) return rc;
@@ -748,6 +816,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     sa.kept_out = kept_out; sa.sigma_out = sigma_out; sa.logp_out = logp_out;
     sa.status = status;
     sa.k = move_rows ? c->k : nullptr; sa.v = c->v; sa.pos = c->pos; sa.len_out = c->len;
+    sa.unordered = (p->flags & NGC_EVICT_UNORDERED) ? 1 : 0;
     sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
     sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
     sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};

@@ -350,3 +350,97 @@ def test_append_rows():
     torch.cuda.synchronize()
     assert ngc.read_status(ws)[ngc.STATUS_APPEND_FULL] == w.B * w.Hkv
     assert (cache.len.cpu().numpy() == 43).all()
+
+
+# ------------------------------------------------ unordered (hole filling) --
+
+def _run_unordered(case, rnd=0, tau=1.0):
+    import torch
+    ngc = _ngc()
+    w = case.w
+    cache, logits, keep = upload(case, with_pos=True)
+    max_keep = max(int(case.keep.max()), 1)
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.zeros(w.L, w.B, w.Hkv, dtype=torch.float32, device="cuda")
+    p = ngc.make_params(noise_scale=tau, round=rnd, seed=w.gumbel_seed, flags=ngc.EVICT_UNORDERED)
+    print(f"[evict-unordered] workload={w.name} L={w.L} B={w.B} cap={w.cap} max_keep={max_keep}", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    return cache, kept, sigma, logp, ws
+
+
+@pytest.mark.parametrize("idx,over", [(0, {}), (1, {}), (3, dict(L=2, B=4)), (4, dict(L=1, B=2))])
+def test_unordered_compaction_parity(idx, over):
+    case = host_case(synth.workload(idx, **over))
+    w = case.w
+    cache, kept, sigma, logp, ws = _run_unordered(case)
+    hk, hv = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v)
+    hlen, hpos = cache.len.cpu().numpy(), cache.pos.cpu().numpy()
+    hkept, hsig, hlp = kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy()
+    for seg in case.segs:
+        l, b, h = seg
+        okept, osig, olp, _, _ = oracle_evict_segment(case, seg, 1.0, w.gumbel_seed, 0)
+        K = okept.size
+        assert hkept[l, b, h, :K].tolist() == okept.tolist(), seg
+        assert hsig[l, b, h, :K].tolist() == osig.tolist(), seg
+        assert hlp[l, b, h] == pytest.approx(olp, rel=LOGP_RTOL), seg
+        assert hlen[l, b, h] == K
+        assert hk[l, b, h, :K].tobytes() == orc.compact_rows_unordered(case.k[seg], okept).tobytes(), seg
+        assert hv[l, b, h, :K].tobytes() == orc.compact_rows_unordered(case.v[seg], okept).tobytes(), seg
+        n = case.k[seg].shape[0]
+        pos_rows = np.arange(n, dtype=np.int32).view(np.uint16).reshape(n, 2)
+        want_pos = orc.compact_rows_unordered(pos_rows, okept).reshape(-1).view(np.int32)
+        assert hpos[l, b, h, :K].tolist() == want_pos.tolist(), seg
+    assert all(x == 0 for x in _ngc().read_status(ws))
+
+
+def test_unordered_rejects_blocks():
+    import torch
+    ngc = _ngc()
+    case = host_case(synth.workload(0))
+    cache, logits, keep = upload(case)
+    ws = ngc.allocate_workspace(cache, 256)
+    kept = torch.zeros(1, 1, 2, 256, dtype=torch.int32, device="cuda")
+    p = ngc.make_params(block=32, flags=ngc.EVICT_UNORDERED)
+    with pytest.raises(ngc.NgcError) as e:
+        ngc.ngc_evict(cache, -1, logits, keep, p, 256, kept, None, None, ws)
+    assert e.value.code == ngc.NGC_EUNSUPPORTED
+
+
+def test_ordered_and_unordered_rounds_keep_the_same_entries():
+    # three greedy rounds (tau = 0) with growth in between; scores are a fixed function of the
+    # original token, looked up through pos, so both arrangements must keep the same tokens and
+    # decode attention must agree
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, B=3, n_lo=900, n_hi=1300)
+    case = host_case(w)
+    base = torch.from_numpy(np.random.default_rng(9).standard_normal((w.L, w.B, w.Hkv, 4096)).astype(np.float32)).cuda()
+    q = to_bf16_tensor(synth.queries(w, 0, 3), "cuda")
+    outs, sets = [], []
+    for flags in (0, ngc.EVICT_UNORDERED):
+        cache, logits, keep = upload(case, with_pos=True)
+        max_keep = int(case.keep.max())
+        ws = ngc.allocate_workspace(cache, max_keep)
+        kept = torch.zeros(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device="cuda")
+        next_pos = torch.from_numpy(case.lens.astype(np.int32)).cuda()
+        for rnd in range(3):
+            logits.copy_(torch.gather(base, 3, cache.pos.long().clamp(0, 4095))[..., :w.cap])
+            print(f"[evict] flags={flags} round={rnd}", flush=True)
+            ngc.ngc_evict(cache, -1, logits, keep, ngc.make_params(noise_scale=0.0, round=rnd, flags=flags),
+                          max_keep, kept, None, None, ws)
+            for t in range(40):
+                nk, nv = synth.new_token_kv(w, 0, rnd * 40 + t)
+                ngc.ngc_cache_append(cache, 0, to_bf16_tensor(nk, "cuda"), to_bf16_tensor(nv, "cuda"), next_pos, ws)
+                next_pos = next_pos + 1
+        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+        ngc.ngc_decode_attn(cache, 0, q, 1.0 / np.sqrt(w.D), 0, out, ws)
+        torch.cuda.synchronize()
+        assert all(x == 0 for x in ngc.read_status(ws))
+        outs.append(out.cpu().numpy())
+        hlen, hpos = cache.len.cpu().numpy(), cache.pos.cpu().numpy()
+        sets.append([[sorted(hpos[0, b, h, :hlen[0, b, h]].tolist()) for h in range(w.Hkv)] for b in range(w.B)])
+    assert sets[0] == sets[1]
+    assert np.abs(outs[0] - outs[1]).max() <= 2e-5

@@ -44,6 +44,28 @@ def test_compaction_of_blocks():
     assert orc.compact_i32(np.arange(10), [1, 2], block=4).tolist() == [4, 5, 6, 7, 8, 9]
 
 
+def test_unordered_compaction_by_hand_and_as_a_set():
+    # n = 8, keep {1, 2, 5, 7}: K = 4, holes among slots 0..3 are 0 and 3, tails are 5 and 7
+    rows = (np.arange(8, dtype=np.uint16)[:, None] * 10 + np.arange(3, dtype=np.uint16)[None]).astype(np.uint16)
+    got = orc.compact_rows_unordered(rows, [1, 2, 5, 7])
+    assert got.tolist() == rows[[5, 1, 2, 7]].tolist()
+    # nothing beyond K kept: nothing moves; everything kept: nothing moves
+    assert orc.compact_rows_unordered(rows, [0, 1, 2]).tolist() == rows[:3].tolist()
+    assert orc.compact_rows_unordered(rows, np.arange(8)).tolist() == rows.tolist()
+    # same multiset of rows as the ordered compaction, rows below K that are kept do not move
+    rng = np.random.default_rng(22)
+    n, D, K = 500, 4, 180
+    big = rng.integers(0, 65536, size=(n, D), dtype=np.uint16)
+    big[:, 0] = np.arange(n)                      # make rows distinct and traceable
+    kept = np.sort(rng.permutation(n)[:K]).astype(np.int32)
+    a, b = orc.compact_rows(big, kept), orc.compact_rows_unordered(big, kept)
+    assert sorted(map(tuple, a.tolist())) == sorted(map(tuple, b.tolist()))
+    stay = kept[kept < K]
+    assert b[stay].tolist() == big[stay].tolist()
+    moved = int((b[:, 0] != np.arange(K)).sum())
+    assert moved == int((kept >= K).sum())        # exactly the tails move
+
+
 # ------------------------------------------------------------- attention ---
 
 def _dense_reference(q, k, v, scale):
