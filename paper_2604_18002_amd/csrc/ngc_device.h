@@ -134,4 +134,22 @@ __device__ __forceinline__ float block_max_f(float v, float *tmp)
     return all;
 }
 
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_max_u(uint32_t v, uint32_t *tmp)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)v, o, NGC_WAVE);
+        v = t > v ? t : v;
+    }
+    if (lane_id() == 0) tmp[wave_id()] = v;
+    __syncthreads();
+    uint32_t all = tmp[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) all = tmp[w] > all ? tmp[w] : all;
+    __syncthreads();
+    return all;
+}
+
 }  // namespace ngc

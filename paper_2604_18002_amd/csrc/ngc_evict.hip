@@ -137,13 +137,16 @@ struct SelectArgs {
     NoiseArgs na;
 };
 
-// For each lane: the set of lanes of this wave whose 8-bit digit equals its
-// own, restricted to `valid` lanes.
+constexpr int SORT_BITS = 9;                 // digit width of the sigma sort
+constexpr int SORT_BINS = 1 << SORT_BITS;
+
+// For each lane: the set of lanes of this wave whose SORT_BITS-bit digit equals
+// its own, restricted to `valid` lanes.
 __device__ __forceinline__ uint64_t match_digit(uint32_t d, uint64_t valid)
 {
     uint64_t m = valid;
 #pragma unroll
-    for (int bit = 0; bit < 8; ++bit) {
+    for (int bit = 0; bit < SORT_BITS; ++bit) {
         const bool on = (d >> bit) & 1u;
         const uint64_t bal = __ballot(on);
         m &= on ? bal : ~bal;
@@ -217,7 +220,7 @@ template <int THREADS, int ROW_BYTES>
 __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, unsigned char *smem_raw)
 {
     constexpr int NW = THREADS / NGC_WAVE;
-    constexpr int HIST = (SEL_BINS > 256 * NW) ? SEL_BINS : 256 * NW;
+    constexpr int HIST = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;
     uint32_t *code = reinterpret_cast<uint32_t *>(smem_raw);
     uint32_t *hist = code + a.items_cap;
     int *misc = reinterpret_cast<int *>(hist + HIST);            // 64 ints
@@ -254,17 +257,21 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
 
     // ---- 1. keys ----------------------------------------------------------
     float smax = -INFINITY;
+    uint32_t cmax = 0;
     for (int quad = tid; 4 * quad < N; quad += THREADS) {
         float s[4], key[4];
         keys_of_quad(row, N, quad, a.na, l, b, h, s, key);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (4 * quad + i < N) {
-                code[4 * quad + i] = ordered_code(key[i]);
+                const uint32_t c = ordered_code(key[i]);
+                code[4 * quad + i] = c;
+                cmax = c > cmax ? c : cmax;
                 smax = fmaxf(smax, s[i]);
             }
     }
     if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
+    if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
 
     // ---- 2. radix select of the K-th largest code -------------------------
     uint32_t prefix = 0, pmask = 0;
@@ -371,40 +378,46 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     if (!want_sort) return;
 
     // ---- 4. sigma: stable sort of the kept indices by descending code ------
+    // Sort key = cmax - code (ascending), which for kept items lies in
+    // [0, cmax - thr]: only the bits of that range are sorted, SORT_BITS at a time.
     const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
     const int k_begin = wv * per_wave_k;
     const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
     uint16_t *src = idxA, *dst = idxB;
     volatile uint32_t *vh = hist;
+    const uint32_t range = cmax - thr;
+    const int range_bits = range ? 32 - __clz(range) : 0;
+    const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
 #pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 8 * pass;
-        for (int i = tid; i < 256 * NW; i += THREADS) hist[i] = 0;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = SORT_BITS * pass;
+        for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
         __syncthreads();
         // per-wave digit counts over the wave's own contiguous range
         for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
             const int j = j0 + lane;
-            const bool in = j < k_end;
-            const uint32_t d = in ? ((~code[src[j]]) >> shift) & 255u : 0u;
-            const uint64_t peers = match_digit(d, __ballot(in));
-            if (in && popc_below(peers) == 0) vh[wv * 256 + d] += (uint32_t)__popcll(peers);
+            if (j < k_end) {
+                const uint32_t d = ((cmax - code[src[j]]) >> shift) & (SORT_BINS - 1);
+                atomicAdd(&hist[wv * SORT_BINS + d], 1u);
+            }
         }
         __syncthreads();
-        // exclusive scan in (digit, wave) order; thread owns 4 consecutive entries
+        // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
         {
-            int vals[4], sum = 0;
+            constexpr int PER = SORT_BINS * NW / THREADS;
+            int vals[PER], sum = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int e = tid * 4 + i;
-                vals[i] = (int)hist[(e % NW) * 256 + e / NW];
+            for (int i = 0; i < PER; ++i) {
+                const int e = tid * PER + i;
+                vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
                 sum += vals[i];
             }
             int total;
             int run = block_excl_scan_i<THREADS>(sum, misc, &total);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int e = tid * 4 + i;
-                hist[(e % NW) * 256 + e / NW] = (uint32_t)run;
+            for (int i = 0; i < PER; ++i) {
+                const int e = tid * PER + i;
+                hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
                 run += vals[i];
             }
         }
@@ -414,22 +427,22 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
             const int j = j0 + lane;
             const bool in = j < k_end;
             const uint16_t idx = in ? src[j] : (uint16_t)0;
-            const uint32_t d = in ? ((~code[idx]) >> shift) & 255u : 0u;
+            const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
             const uint64_t peers = match_digit(d, __ballot(in));
             const int rank = popc_below(peers);
             uint32_t base = 0;
-            if (in) base = vh[wv * 256 + d];
+            if (in) base = vh[wv * SORT_BINS + d];
             __builtin_amdgcn_wave_barrier();
             if (in) {
                 dst[base + rank] = idx;
-                if (rank == 0) vh[wv * 256 + d] = base + (uint32_t)__popcll(peers);
+                if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
             }
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
         uint16_t *tmp = src; src = dst; dst = tmp;
     }
-    // four passes: the sorted list is back in idxA (== src)
+    // the sorted list is in `src` (idxA or idxB, depending on the number of passes)
     if (a.sigma_out) {
         int32_t *sig_row = a.sigma_out + (size_t)seg * a.max_keep;
         for (int j = tid; j < K; j += THREADS) sig_row[j] = (int32_t)src[j];
@@ -641,7 +654,7 @@ template <int THREADS, int ROW_BYTES>
 __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
 {
     constexpr int NW = THREADS / NGC_WAVE;
-    constexpr int HIST = (SEL_BINS > 256 * NW) ? SEL_BINS : 256 * NW;
+    constexpr int HIST = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     int *misc = reinterpret_cast<int *>(reinterpret_cast<uint32_t *>(smem_raw) + a.items_cap + HIST);
     const int seg = a.seg0 + blockIdx.x;
@@ -758,7 +771,7 @@ constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
 size_t select_lds_bytes(int threads, int items_cap, int keep_cap)
 {
     const int nw = threads / 64;
-    const int hist = (SEL_BINS > 256 * nw) ? SEL_BINS : 256 * nw;
+    const int hist = (SEL_BINS > SORT_BINS * nw) ? SEL_BINS : SORT_BINS * nw;
     return (size_t)items_cap * 4 + (size_t)hist * 4 + 64 * 4 + (size_t)keep_cap * 2 * 2;
 }
 
