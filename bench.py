@@ -331,6 +331,31 @@ def main():
         "hbm_frac_steady": un_steady_bytes / (un_steady_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
     }
 
+    # ---- key scoring (the step before the eviction round): w = 5 recent queries, steady-state size
+    w_recent = 5
+    q_recent = torch.randn(w.L, w.B, w_recent, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
+    scores = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.float32, device=dev)
+    for t in range(w.delta):
+        ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+    sc_ms = []
+    for rep in range(4):
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        ngc.ngc_score_keys(cache, -1, q_recent, w_recent, scale, 0, 1, scores, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        sc_ms.append(e0.elapsed_time(e1))
+    sc_us = 1e3 * float(np.mean(sc_ms[1:]))
+    rows_scored = float((keep_h + w.delta).sum())
+    sc_bytes = rows_scored * (2 * w.D + 4) + nseg * w_recent * w.G * w.D * 2     # K once, one score per key, queries
+    scoring = {
+        "what": f"ngc_score_keys, w={w_recent}, every segment at budget + delta rows, all layers in one launch",
+        "us": sc_us, "bytes": sc_bytes, "hbm_frac": sc_bytes / (sc_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "note": "the kernel reads K twice (max/sum pass, probability pass): HBM traffic is ~2x these bytes",
+    }
+    evict(rnd + 10)      # back to the budget
+
     per_layer = None
     if args.per_layer:
         reps = 20
@@ -386,6 +411,7 @@ def main():
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
         },
         "eviction_unordered": unordered,
+        "scoring": scoring,
         "setup_s": t_setup,
     }
     if per_layer:

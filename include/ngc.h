@@ -13,6 +13,8 @@
  *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
+ *   ngc_score_keys       attention-based importance of every cached key, the
+ *                        input of the eviction policy                (Sec. 4.2)
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless a comment says "host".  The
@@ -188,6 +190,30 @@ int ngc_cache_append(const ngc_cache *c, int32_t layer, const void *k_new,
 int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
                     int32_t max_len_hint, float *out,
                     void *ws, size_t ws_bytes, void *stream);
+
+/* Key importance scores for the eviction policy (Sec. 4.2): for every segment
+ * of `layer` (-1 = all layers), with the queries of the w most recent tokens
+ * (whose keys are the last w rows of the segment),
+ *     A_{q,t}  = softmax_t( scale * <q, K[t]> )   over the rows query q can see,
+ *     psi_t    = mean of A_{q,t} over the w queries and the Hq/Hkv query heads
+ *                of the KV head,
+ * where recent query j (0 = oldest) sees rows t <= len - w + j (its own token
+ * and everything before it); NGC_SCORE_NO_CAUSAL lets every query see all rows.
+ * With block > 1 the value of item j is the mean of psi over its rows (last
+ * block possibly short); with NGC_SCORE_POOL_HEADS it is further averaged over
+ * the KV heads of the (layer, sequence) -- the paper's one score per layer and
+ * block -- and written to every head.
+ *   q_recent    bf16 [B][w][Hq][D] (or [L][B][w][Hq][D] for layer = -1), 16-byte aligned
+ *   scores_out  fp32 [L][B][Hkv][cap], item j of a segment at offset j: the
+ *               layout ngc_evict takes as logits.  Entries past the item count
+ *               are unspecified.
+ * Limit: w * (Hq/Hkv) <= 64 (NGC_EUNSUPPORTED beyond).
+ * ws needs NGC_STATUS_WORDS * 4 bytes (status only). */
+#define NGC_SCORE_NO_CAUSAL  1u
+#define NGC_SCORE_POOL_HEADS 2u
+int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent, int32_t w,
+                   float scale, uint32_t flags, int32_t block, float *scores_out,
+                   void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -32,6 +32,11 @@
  *   orc_decode_attn     softmax(q K^T / sqrt(d_h)) V over the surviving rows
  *                       (Sec. 4.2 for the scale, Sec. 4.1 for "conditioned on
  *                       the surviving entries")
+ *   orc_score_keys      importance of every cached key: attention weights of
+ *                       the w most recent queries, averaged over heads and
+ *                       queries (Sec. 4.2, "Parameterizing eviction actions")
+ *   orc_block_means     block-level scores: mean of the key scores over each
+ *                       block of b contiguous keys (Sec. 4.2, "Coarsening")
  *
  * Parity status: every function here is pinned by tests/test_oracle_*.py
  * against published test vectors, closed forms, brute force or a library
@@ -346,4 +351,54 @@ void orc_decode_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
     }
     free(x);
     free(o);
+}
+
+/* ------------------------------------------------------------ scoring --- */
+
+/* Key importance for one KV head of one sequence (Sec. 4.2).
+ *   q    [w][G][D]  queries of the w most recent tokens, G query heads each
+ *   k    [n][D]     cached keys; the w most recent tokens are rows n-w .. n-1
+ * For every query (j, g): a = softmax_t(scale * <q_{j,g}, k_t>) over the keys
+ * it can see -- with causal != 0 query j (the token at row n-w+j) sees rows
+ * t <= n-w+j, otherwise every query sees all n rows.  psi_t is the mean of
+ * a_t over the w*G queries (0 where a query cannot see t). */
+void orc_score_keys(const uint16_t *q, const uint16_t *k, int32_t n, int32_t w,
+                    int32_t G, int32_t D, double scale, int32_t causal, double *psi)
+{
+    double *x = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (int32_t t = 0; t < n; ++t) psi[t] = 0.0;
+    for (int32_t j = 0; j < w; ++j) {
+        int32_t vis = causal ? (n - w + j + 1) : n;   /* number of visible rows */
+        if (vis > n) vis = n;
+        if (vis <= 0) continue;
+        for (int32_t g = 0; g < G; ++g) {
+            const uint16_t *qr = q + ((size_t)j * G + g) * D;
+            double mx = -INFINITY;
+            for (int32_t t = 0; t < vis; ++t) {
+                double acc = 0.0;
+                for (int32_t d = 0; d < D; ++d)
+                    acc += bf16_to_double(qr[d]) * bf16_to_double(k[(size_t)t * D + d]);
+                x[t] = acc * scale;
+                if (x[t] > mx) mx = x[t];
+            }
+            double den = 0.0;
+            for (int32_t t = 0; t < vis; ++t) den += exp(x[t] - mx);
+            for (int32_t t = 0; t < vis; ++t) psi[t] += exp(x[t] - mx) / den;
+        }
+    }
+    for (int32_t t = 0; t < n; ++t) psi[t] /= (double)(w * G);
+    free(x);
+}
+
+/* s_j = mean of psi over block j (blocks of `block` consecutive keys, the
+ * last one possibly short; every key is valid). */
+void orc_block_means(const double *psi, int32_t n, int32_t block, double *s)
+{
+    int32_t N = (n + block - 1) / block;
+    for (int32_t j = 0; j < N; ++j) {
+        int32_t lo = j * block, hi = lo + block < n ? lo + block : n;
+        double acc = 0.0;
+        for (int32_t t = lo; t < hi; ++t) acc += psi[t];
+        s[j] = acc / (double)(hi - lo);
+    }
 }

@@ -63,6 +63,12 @@ def _L():
         lib.orc_decode_attn.argtypes = [u16p, u16p, u16p, C.c_int32, C.c_int32, C.c_int32,
                                         C.c_double, f32p]
         lib.orc_decode_attn.restype = None
+        f64p = C.POINTER(C.c_double)
+        lib.orc_score_keys.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_double, C.c_int32, f64p]
+        lib.orc_score_keys.restype = None
+        lib.orc_block_means.argtypes = [f64p, C.c_int32, C.c_int32, f64p]
+        lib.orc_block_means.restype = None
         _lib = lib
     return _lib
 
@@ -185,6 +191,28 @@ def decode_attn(q_u16, k_u16, v_u16, scale: float) -> np.ndarray:
     _L().orc_decode_attn(_p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16), n, G, D,
                          float(scale), _p(out, C.c_float))
     return out
+
+
+# --------------------------------------------------------------- scoring --
+
+def score_keys(q_u16, k_u16, scale: float, causal: bool = True) -> np.ndarray:
+    """q: [w, G, D], k: [n, D] (bf16 bit patterns).  Returns psi, fp64 [n]."""
+    q = _arr(q_u16, np.uint16)
+    k = _arr(k_u16, np.uint16)
+    w, G, D = q.shape
+    n = k.shape[0]
+    psi = np.zeros(max(n, 1), np.float64)
+    _L().orc_score_keys(_p(q, C.c_uint16), _p(k, C.c_uint16), n, w, G, D, float(scale), int(bool(causal)),
+                        _p(psi, C.c_double))
+    return psi[:n]
+
+
+def block_means(psi, block: int) -> np.ndarray:
+    x = _arr(psi, np.float64)
+    N = (x.size + block - 1) // block
+    s = np.zeros(max(N, 1), np.float64)
+    _L().orc_block_means(_p(x, C.c_double), x.size, block, _p(s, C.c_double))
+    return s[:N]
 
 
 # ------------------------------------------------- host-integer schedule --

@@ -18,6 +18,7 @@ _COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 _UNITS = (
     ("ngc_evict.hip", ["-ffp-contract=off"]),
     ("ngc_attn.hip", []),
+    ("ngc_score.hip", []),
 )
 
 

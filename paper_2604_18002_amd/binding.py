@@ -29,9 +29,11 @@ STATUS_BAD_SIGMA = 4
 
 EVICT_SELECT_ONLY = 1
 EVICT_UNORDERED = 2
+SCORE_NO_CAUSAL = 1
+SCORE_POOL_HEADS = 2
 
 EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
-           "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn")
+           "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys")
 
 
 class NgcError(RuntimeError):
@@ -83,6 +85,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_cache_append.restype = C.c_int
     lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, sz, vp]
     lib.ngc_decode_attn.restype = C.c_int
+    lib.ngc_score_keys.argtypes = [cp, i32, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
+    lib.ngc_score_keys.restype = C.c_int
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -199,3 +203,11 @@ def ngc_decode_attn(cache: Cache, layer: int, q, scale: float, max_len_hint: int
     v = cache.view()
     _check(load_library().ngc_decode_attn(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
                                           _ptr(ws), ws.numel(), _stream(stream)), "ngc_decode_attn")
+
+
+def ngc_score_keys(cache: Cache, layer: int, q_recent, w: int, scale: float, flags: int, block: int,
+                   scores_out, ws, stream=None):
+    v = cache.view()
+    _check(load_library().ngc_score_keys(C.byref(v), layer, _ptr(q_recent), w, scale, flags, block,
+                                         _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "ngc_score_keys")

@@ -33,14 +33,6 @@
 
 namespace ngc {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// 2^x by the hardware instruction (-inf -> 0); inputs here are <= 0 or small.
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_TILE = 32;   // rows per wave step
 

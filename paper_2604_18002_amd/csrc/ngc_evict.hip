@@ -16,8 +16,6 @@ namespace ngc {
 
 // ------------------------------------------------------------ geometry ----
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 struct SegGeom {
     int B, Hkv, cap, block;
 };
