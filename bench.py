@@ -356,6 +356,28 @@ def main():
     }
     evict(rnd + 10)      # back to the budget
 
+    # ---- gradient of the log-prob for the round just sampled (what Eq. 4 back-propagates)
+    bwd = None
+    if w.with_logprob:
+        n_items_d = (keep + w.delta).reshape(-1).contiguous()
+        grad = torch.empty_like(logits)
+        gout = torch.randn(nseg, generator=g, device=dev)
+        bw_ms = []
+        for rep in range(4):
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            ngc.ngc_subset_logprob_backward(logits, n_items_d, sigma, keep.reshape(-1), nseg, cap, max_keep, max_keep,
+                                            gout, grad, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            bw_ms.append(e0.elapsed_time(e1))
+        bw_us = 1e3 * float(np.mean(bw_ms[1:]))
+        bw_bytes = 8.0 * float((keep_h + w.delta).sum()) + 4.0 * float(keep_h.sum()) + 4.0 * nseg
+        bwd = {"what": "ngc_subset_logprob_backward for every segment of the round (n = budget + delta)",
+               "us": bw_us, "bytes": bw_bytes, "hbm_frac": bw_bytes / (bw_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del grad
+
     per_layer = None
     if args.per_layer:
         reps = 20
@@ -412,6 +434,7 @@ def main():
         },
         "eviction_unordered": unordered,
         "scoring": scoring,
+        "logprob_backward": bwd,
         "setup_s": t_setup,
     }
     if per_layer:

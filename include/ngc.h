@@ -10,6 +10,7 @@
  *                        ordered-subset log-probability, and in-place removal
  *                        of everything else                  (Sec. 4.1, 4.3, Eq. 2)
  *   ngc_subset_logprob   Eq. 2 for caller-supplied sampled actions (Sec. 4.3-4.4)
+ *   ngc_subset_logprob_backward  its gradient w.r.t. the logits (Eq. 4)
  *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
@@ -166,6 +167,22 @@ int ngc_subset_logprob(const float *logits, const int32_t *n_items,
                        const int32_t *sigma, const int32_t *keep, int32_t nseg,
                        int64_t logit_stride, int32_t sigma_stride,
                        float *logp_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Gradient of Eq. 2 with respect to the logits, as the eviction policy
+ * gradient of Eq. 4 needs it: for each segment s and item t < n_items[s]
+ *     grad[s][t] = gout[s] * d log p(sigma_s | x_s) / d x_s[t]
+ *                = gout[s] * ( 1[t in sigma_s] - sum_{j : t not in sigma_1..sigma_{j-1}}
+ *                                                 exp x[t] / sum_{u not in sigma_1..sigma_{j-1}} exp x[u] ).
+ *   gout      fp32 [nseg] upstream weights (for Eq. 4: minus the advantage over
+ *             the number of rollouts and rounds), or NULL for 1
+ *   grad_out  fp32 [nseg][logit_stride]; entries past n_items are untouched
+ *   max_keep  upper bound on keep[s] (<= 32768)
+ * Other arguments as in ngc_subset_logprob. */
+int ngc_subset_logprob_backward(const float *logits, const int32_t *n_items,
+                                const int32_t *sigma, const int32_t *keep, int32_t nseg,
+                                int64_t logit_stride, int32_t sigma_stride, int32_t max_keep,
+                                const float *gout, float *grad_out,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* Append one new row per (sequence, head) of `layer` (-1 = all layers) at row
  * len and add 1 to len (Sec. 4.1: between rounds the cache grows as usual).

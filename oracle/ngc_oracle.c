@@ -27,6 +27,7 @@
  *   orc_logprob_suffix  the same value by one reverse running sum (the
  *                       "prefix sum trick" remark after Eq. 2, in the
  *                       cancellation-free arrangement)
+ *   orc_logprob_grad_literal  d(Eq. 2)/d(logits), term by term (Eq. 4 needs it)
  *   orc_compact         permanent removal of evicted entries    (Sec. 4.1,
  *                       Eq. 7: next alive set = kept entries + new tokens)
  *   orc_decode_attn     softmax(q K^T / sqrt(d_h)) V over the surviving rows
@@ -242,6 +243,30 @@ double orc_logprob_suffix(const float *logits, int32_t n_items,
     }
     free(picked);
     return total;
+}
+
+/* Gradient of Eq. 2 with respect to every logit, term by term: the j-th term
+ * s_{sigma_j} - logsumexp(alive_j) contributes +1 at sigma_j and minus the
+ * softmax over the items still alive at step j.  O(nK).  This is what the
+ * eviction policy gradient of Eq. 4 multiplies by the advantage. */
+void orc_logprob_grad_literal(const float *logits, int32_t n_items,
+                              const int32_t *sigma, int32_t K, double *grad)
+{
+    unsigned char *gone = (unsigned char *)calloc((size_t)(n_items > 0 ? n_items : 1), 1);
+    for (int32_t t = 0; t < n_items; ++t) grad[t] = 0.0;
+    for (int32_t j = 0; j < K; ++j) {
+        double mx = -INFINITY;
+        for (int32_t t = 0; t < n_items; ++t)
+            if (!gone[t] && (double)logits[t] > mx) mx = (double)logits[t];
+        double den = 0.0;
+        for (int32_t t = 0; t < n_items; ++t)
+            if (!gone[t]) den += exp((double)logits[t] - mx);
+        for (int32_t t = 0; t < n_items; ++t)
+            if (!gone[t]) grad[t] -= exp((double)logits[t] - mx) / den;
+        grad[sigma[j]] += 1.0;
+        gone[sigma[j]] = 1;
+    }
+    free(gone);
 }
 
 /* -------------------------------------------------------- compaction ---- */

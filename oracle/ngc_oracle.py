@@ -64,6 +64,8 @@ def _L():
                                         C.c_double, f32p]
         lib.orc_decode_attn.restype = None
         f64p = C.POINTER(C.c_double)
+        lib.orc_logprob_grad_literal.argtypes = [f32p, C.c_int32, i32p, C.c_int32, f64p]
+        lib.orc_logprob_grad_literal.restype = None
         lib.orc_score_keys.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_double, C.c_int32, f64p]
         lib.orc_score_keys.restype = None
@@ -140,6 +142,15 @@ def logprob_suffix(logits, sigma) -> float:
     s = _arr(logits, np.float32)
     sg = _arr(sigma, np.int32)
     return float(_L().orc_logprob_suffix(_p(s, C.c_float), s.size, _p(sg, C.c_int32), sg.size))
+
+
+def logprob_grad(logits, sigma) -> np.ndarray:
+    """d log p(sigma | logits) / d logits, fp64 [n]."""
+    s = _arr(logits, np.float32)
+    sg = _arr(sigma, np.int32)
+    g = np.zeros(max(s.size, 1), np.float64)
+    _L().orc_logprob_grad_literal(_p(s, C.c_float), s.size, _p(sg, C.c_int32), sg.size, _p(g, C.c_double))
+    return g[:s.size]
 
 
 # ------------------------------------------------------------ compaction --

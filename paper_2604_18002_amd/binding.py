@@ -33,7 +33,8 @@ SCORE_NO_CAUSAL = 1
 SCORE_POOL_HEADS = 2
 
 EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
-           "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys")
+           "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
+           "ngc_subset_logprob_backward")
 
 
 class NgcError(RuntimeError):
@@ -85,6 +86,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_cache_append.restype = C.c_int
     lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, sz, vp]
     lib.ngc_decode_attn.restype = C.c_int
+    lib.ngc_subset_logprob_backward.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.ngc_subset_logprob_backward.restype = C.c_int
     lib.ngc_score_keys.argtypes = [cp, i32, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_score_keys.restype = C.c_int
     if path == LIB_PATH:
@@ -211,3 +214,11 @@ def ngc_score_keys(cache: Cache, layer: int, q_recent, w: int, scale: float, fla
     _check(load_library().ngc_score_keys(C.byref(v), layer, _ptr(q_recent), w, scale, flags, block,
                                          _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
            "ngc_score_keys")
+
+
+def ngc_subset_logprob_backward(logits, n_items, sigma, keep, nseg: int, logit_stride: int, sigma_stride: int,
+                                max_keep: int, gout, grad_out, ws, stream=None):
+    _check(load_library().ngc_subset_logprob_backward(_ptr(logits), _ptr(n_items), _ptr(sigma), _ptr(keep), nseg,
+                                                      logit_stride, sigma_stride, max_keep, _ptr(gout),
+                                                      _ptr(grad_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "ngc_subset_logprob_backward")

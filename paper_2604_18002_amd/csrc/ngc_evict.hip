@@ -568,6 +568,126 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
     if (tid == 0) a.logp_out[seg] = lp;
 }
 
+// ------------------------------------------ gradient of the log-prob ------
+//
+// d log p / d s_t = 1[t in sigma] - e_t * C_{r(t)},  C_r = sum_{j <= r} 1 / R_j,
+// r(t) = position of t in sigma (K if t was never picked), with e_t and R_j as
+// in the forward form.  One reverse scan gives R_j, one forward scan of 1/R_j
+// gives C_r; 1/R_j lives in LDS between the two.
+
+struct LogprobBwdArgs {
+    const float *logits;
+    const int32_t *n_items;
+    const int32_t *sigma;
+    const int32_t *keep;
+    const float *gout;     // upstream weight per segment, or nullptr for 1
+    float *grad_out;
+    int32_t *status;
+    int64_t logit_stride;
+    int sigma_stride;
+    int keep_cap;
+};
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(LogprobBwdArgs a)
+{
+    extern __shared__ float inv_r[];          // keep_cap floats
+    __shared__ uint32_t picked[2048];
+    __shared__ float fmisc[32];
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x;
+    int N = a.n_items[seg];
+    N = N < 0 ? 0 : (N > 65536 ? 65536 : N);
+    int K = a.keep[seg];
+    {
+        const int lim = N < a.keep_cap ? N : a.keep_cap;
+        if (K < 0 || K > lim) {
+            if (tid == 0) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+            K = K < 0 ? 0 : lim;
+        }
+    }
+    const float *row = a.logits + (size_t)seg * a.logit_stride;
+    float *grow = a.grad_out + (size_t)seg * a.logit_stride;
+    const int32_t *sig = a.sigma + (size_t)seg * a.sigma_stride;
+    const float g = a.gout ? a.gout[seg] : 1.0f;
+    if (K == 0) {
+        for (int t = tid; t < N; t += THREADS) grow[t] = 0.f;
+        return;
+    }
+    for (int i = tid; i < 2048; i += THREADS) picked[i] = 0;
+    __syncthreads();
+    int bad = 0;
+    for (int j = tid; j < K; j += THREADS) {
+        const int t = sig[j];
+        if (t < 0 || t >= N) { bad = 1; continue; }
+        const uint32_t bit = 1u << (t & 31);
+        if (atomicOr(&picked[t >> 5], bit) & bit) bad = 1;
+    }
+    if (bad) atomicAdd(&a.status[NGC_STATUS_BAD_SIGMA], 1);
+    float smax = -INFINITY;
+    for (int t = tid; t < N; t += THREADS) {
+        const float x = row[t];
+        if (x == x) smax = fmaxf(smax, x);
+    }
+    smax = block_max_f<THREADS>(smax, fmisc);
+    float unpicked = 0.f;
+    for (int t = tid; t < N; t += THREADS) {
+        if (picked[t >> 5] & (1u << (t & 31))) continue;
+        float x = row[t];
+        if (x != x) x = -INFINITY;
+        unpicked += expf(x - smax);
+    }
+    const float U = block_sum_f<THREADS>(unpicked, fmisc);
+    auto mass_of = [&](int j) {
+        int t = sig[j];
+        t = t < 0 ? 0 : (t >= N ? N - 1 : t);
+        const float x = row[t];
+        return (x != x) ? 0.f : expf(x - smax);
+    };
+    const int chunk = (K + THREADS - 1) / THREADS;
+    const int nchunks = (K + chunk - 1) / chunk;
+    // reverse pass: thread 0 owns the last chunk
+    {
+        const int cidx = nchunks - 1 - tid;
+        const int j_lo = cidx * chunk;
+        const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+        float mass = 0.f;
+        if (cidx >= 0)
+            for (int j = j_lo; j < j_hi; ++j) mass += mass_of(j);
+        float total;
+        const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total);
+        if (cidx >= 0) {
+            float R = U + after;
+            for (int j = j_hi - 1; j >= j_lo; --j) {
+                R += mass_of(j);
+                inv_r[j] = 1.0f / R;
+            }
+        }
+    }
+    __syncthreads();
+    // forward pass: thread i owns chunk i
+    float c_all;
+    {
+        const int j_lo = tid * chunk;
+        const int j_hi = (tid < nchunks) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : j_lo;
+        float part = 0.f;
+        for (int j = j_lo; j < j_hi; ++j) part += inv_r[j];
+        const float before = block_excl_scan_f<THREADS>(part, fmisc, &c_all);
+        float C = before;
+        for (int j = j_lo; j < j_hi; ++j) {
+            C += inv_r[j];
+            const int t = sig[j];
+            if (t >= 0 && t < N) grow[t] = g * (1.0f - mass_of(j) * C);
+        }
+    }
+    for (int t = tid; t < N; t += THREADS) {
+        if (picked[t >> 5] & (1u << (t & 31))) continue;
+        float x = row[t];
+        const float e = (x != x) ? 0.f : expf(x - smax);
+        grow[t] = -g * e * c_all;
+    }
+}
+
 // --------------------------------------------------------- compaction -----
 //
 // In place: the row that ends at slot j comes from a slot >= j, so a
@@ -860,6 +980,28 @@ extern "C" int ngc_subset_logprob(const float *logits, const int32_t *n_items,
                    logit_stride, sigma_stride};
     hipLaunchKernelGGL(subset_logprob_kernel<512>, dim3(nseg), dim3(512), 0, (hipStream_t)stream, la);
     NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_subset_logprob_backward(const float *logits, const int32_t *n_items,
+                                           const int32_t *sigma, const int32_t *keep, int32_t nseg,
+                                           int64_t logit_stride, int32_t sigma_stride, int32_t max_keep,
+                                           const float *gout, float *grad_out,
+                                           void *ws, size_t ws_bytes, void *stream)
+{
+    if (!logits || !n_items || !sigma || !keep || !grad_out || !ws) return NGC_EINVAL;
+    if (nseg < 0 || logit_stride < 0 || sigma_stride < 0 || max_keep < 1) return NGC_EINVAL;
+    if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
+    if (max_keep > 32768) return NGC_EUNSUPPORTED;
+    if (nseg == 0) return NGC_OK;
+    LogprobBwdArgs la{logits, n_items, sigma, keep, gout, grad_out, reinterpret_cast<int32_t *>(ws),
+                      logit_stride, sigma_stride, max_keep};
+    const size_t lds = (size_t)max_keep * sizeof(float);
+    const void *fn = reinterpret_cast<const void *>(&subset_logprob_backward_kernel<512>);
+    if (lds > 48 * 1024)
+        NGC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    void *kargs[] = {&la};
+    NGC_HIP_CHECK(hipLaunchKernel(fn, dim3(nseg), dim3(512), kargs, lds, (hipStream_t)stream));
     return NGC_OK;
 }
 

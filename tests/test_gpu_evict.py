@@ -444,3 +444,46 @@ def test_ordered_and_unordered_rounds_keep_the_same_entries():
         sets.append([[sorted(hpos[0, b, h, :hlen[0, b, h]].tolist()) for h in range(w.Hkv)] for b in range(w.B)])
     assert sets[0] == sets[1]
     assert np.abs(outs[0] - outs[1]).max() <= 2e-5
+
+
+# ------------------------------------------- gradient of the log-prob ------
+
+def test_subset_logprob_backward():
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(6)
+    n_items = np.array([1, 5, 64, 257, 1000, 4096, 8192], np.int32)
+    keep = np.array([1, 5, 20, 100, 333, 1366, 3277], np.int32)
+    nseg, stride, kmax = len(n_items), 8192, 3277
+    logits = np.zeros((nseg, stride), np.float32)
+    sigma = np.zeros((nseg, kmax), np.int32)
+    gout = rng.standard_normal(nseg).astype(np.float32)
+    for s in range(nseg):
+        x = rng.standard_normal(n_items[s]).astype(np.float32)
+        if s == 5:
+            out = rng.random(n_items[s]) < 0.05
+            x = np.where(out, rng.laplace(0, 4, n_items[s]), x).astype(np.float32)
+        logits[s, :n_items[s]] = x
+        _, sg = orc.evict_select(x, int(keep[s]), 1.0, 21, s, 0, 0, 0)
+        sigma[s, :keep[s]] = sg
+    d = lambda a: torch.from_numpy(a).cuda()
+    grad = torch.full((nseg, stride), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(ngc.STATUS_WORDS * 4, dtype=torch.uint8, device="cuda")
+    print("[logprob-backward]", flush=True)
+    ngc.ngc_subset_logprob_backward(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, kmax, kmax,
+                                    d(gout), grad, ws)
+    torch.cuda.synchronize()
+    got = grad.cpu().numpy()
+    for s in range(nseg):
+        n = n_items[s]
+        want = gout[s] * orc.logprob_grad(logits[s, :n], sigma[s, :keep[s]])
+        assert np.all(np.abs(got[s, :n] - want) <= 1e-4 * np.abs(want) + 2e-6), (s, np.abs(got[s, :n] - want).max())
+        assert np.isnan(got[s, n:]).all()
+        assert abs(got[s, :n].sum()) <= 1e-3 * max(1.0, np.abs(got[s, :n]).sum())
+    assert all(x == 0 for x in ngc.read_status(ws))
+    # gout = NULL means weight 1
+    ngc.ngc_subset_logprob_backward(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, kmax, kmax,
+                                    None, grad, ws)
+    torch.cuda.synchronize()
+    want = orc.logprob_grad(logits[3, :n_items[3]], sigma[3, :keep[3]])
+    assert np.abs(grad[3, :n_items[3]].cpu().numpy() - want).max() <= 1e-4

@@ -111,3 +111,39 @@ def test_full_permutation_of_everything():
     assert orc.logprob_literal(s, seq) == pytest.approx(want, rel=1e-12)
     assert orc.logprob_suffix(s, seq) == pytest.approx(want, rel=1e-12)
     assert orc.logprob_suffix(s, []) == 0.0
+
+
+# ------------------------------------------------ gradient of Eq. 2 --------
+
+def test_gradient_matches_finite_differences():
+    rng = np.random.default_rng(14)
+    n, K = 12, 5
+    s = np.round(rng.standard_normal(n) * 64) / 64            # exactly representable in fp32
+    sigma = rng.permutation(n)[:K]
+    g = orc.logprob_grad(s.astype(np.float32), sigma)
+    h = 2.0 ** -9                                             # exact step in fp32 at this magnitude
+    for t in range(n):
+        up, dn = s.copy(), s.copy()
+        up[t] += h
+        dn[t] -= h
+        fd = (orc.logprob_literal(up.astype(np.float32), sigma) -
+              orc.logprob_literal(dn.astype(np.float32), sigma)) / (2 * h)
+        assert g[t] == pytest.approx(fd, abs=2e-5)
+
+
+def test_gradient_invariants():
+    rng = np.random.default_rng(15)
+    n, K = 300, 120
+    s = (2 * rng.standard_normal(n)).astype(np.float32)
+    sigma = rng.permutation(n)[:K]
+    g = orc.logprob_grad(s, sigma)
+    assert g.sum() == pytest.approx(0.0, abs=1e-10)           # adding a constant to all logits changes nothing
+    unpicked = np.setdiff1d(np.arange(n), sigma)
+    assert (g[unpicked] < 0).all()                            # raising an unpicked logit lowers the probability
+    # K = 1: one-hot minus softmax
+    g1 = orc.logprob_grad(s, sigma[:1])
+    want = -np.exp(log_softmax(s.astype(np.float64)))
+    want[sigma[0]] += 1.0
+    assert np.abs(g1 - want).max() < 1e-14
+    # the last pick of a full permutation has zero gradient contribution beyond itself
+    assert orc.logprob_grad(s[:5], [0, 1, 2, 3, 4]).sum() == pytest.approx(0.0, abs=1e-12)
