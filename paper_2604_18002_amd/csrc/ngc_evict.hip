@@ -935,7 +935,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     int keep_cap = max_keep < items_cap ? max_keep : items_cap;
     keep_cap = (keep_cap + 7) & ~7;
     const int items_cap_al = (items_cap + 3) & ~3;
-    const int threads = items_cap > 2048 ? 1024 : 256;
+    const int threads = items_cap > 8192 ? 1024 : (items_cap > 2048 ? 512 : 256);   // measured on configs 2-4
     const size_t lds = select_lds_bytes(threads, items_cap_al, keep_cap);
     if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
 
@@ -957,6 +957,9 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     if (threads == 1024)
         fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<1024, 256>)
                            : reinterpret_cast<const void *>(&evict_kernel<1024, 128>);
+    else if (threads == 512)
+        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<512, 256>)
+                           : reinterpret_cast<const void *>(&evict_kernel<512, 128>);
     else
         fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<256, 256>)
                            : reinterpret_cast<const void *>(&evict_kernel<256, 128>);
