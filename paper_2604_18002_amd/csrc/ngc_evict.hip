@@ -725,8 +725,8 @@ __device__ __forceinline__ void compact_kv_inplace(unsigned char *kbase, unsigne
             vb[u] = u32x4{0u, 0u, 0u, 0u};
             if (moves[u]) {
                 const size_t off = (size_t)s * ROW_BYTES + piece * 16;
-                kb[u] = *reinterpret_cast<const u32x4 *>(kbase + off);
-                vb[u] = *reinterpret_cast<const u32x4 *>(vbase + off);
+                kb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kbase + off));
+                vb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vbase + off));
             }
         }
         __syncthreads();   // every read of this tile has landed
@@ -735,8 +735,8 @@ __device__ __forceinline__ void compact_kv_inplace(unsigned char *kbase, unsigne
             const int r = tile + u * ROWS_PER_STEP + rsub;
             if (moves[u]) {
                 const size_t off = (size_t)r * ROW_BYTES + piece * 16;
-                *reinterpret_cast<u32x4 *>(kbase + off) = kb[u];
-                *reinterpret_cast<u32x4 *>(vbase + off) = vb[u];
+                __builtin_nontemporal_store(kb[u], reinterpret_cast<u32x4 *>(kbase + off));
+                __builtin_nontemporal_store(vb[u], reinterpret_cast<u32x4 *>(vbase + off));
             }
         }
     }

@@ -97,7 +97,8 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
         for (int r = 0; r < K_LOADS; ++r) {
             int row = row0 + r * K_ROWS_PER_LOAD + lane / K_PIECES;
             row = row < last_row ? row : last_row;
-            kbuf[r] = *reinterpret_cast<const u32x4 *>(kseg + (size_t)row * ROW_BYTES + (lane % K_PIECES) * 16);
+            kbuf[r] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(kseg + (size_t)row * ROW_BYTES + (lane % K_PIECES) * 16));
         }
     };
     auto stage_tile = [&]() {
