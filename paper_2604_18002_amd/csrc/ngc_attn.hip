@@ -138,48 +138,42 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
 #pragma unroll
     for (int e = 0; e < 8; ++e) vrow_rel[e] = (e < 4) ? (4 * kg + e) : (16 + 4 * kg + (e - 4));
 
+    // 32-bit byte offsets inside the segment (a segment is at most cap * ROW_BYTES <= 2^31 bytes)
+    const uint32_t k_col = (uint32_t)(lane % K_PIECES) * 16u;
+    const uint32_t v_col = (uint32_t)li * (DPL * 2);
     u32x4 kbuf[K_LOADS];
-    u32x4 vbuf4[8];   // D = 128: 16 B per row; D = 64: low 8 B used
-    auto load_tile = [&](int tile) {
+    auto issue_loads = [&](int tile, u32x4 (&vb)[8]) {
         const int row0 = tile * ATT_TILE;
 #pragma unroll
         for (int r = 0; r < K_LOADS; ++r) {
             int row = row0 + r * K_ROWS_PER_LOAD + lane / K_PIECES;
             row = row < last_row ? row : last_row;
             kbuf[r] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(kseg + (size_t)row * ROW_BYTES + (lane % K_PIECES) * 16));
+                reinterpret_cast<const u32x4 *>(kseg + ((uint32_t)row * ROW_BYTES + k_col)));
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int row = row0 + vrow_rel[e];
             row = row < last_row ? row : last_row;
-            const unsigned char *p = vseg + (size_t)row * ROW_BYTES + li * (DPL * 2);
+            const unsigned char *p = vseg + ((uint32_t)row * ROW_BYTES + v_col);
             if constexpr (DPL == 8) {
-                vbuf4[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+                vb[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
             } else {
                 const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
-                vbuf4[e] = u32x4{t[0], t[1], 0u, 0u};
+                vb[e] = u32x4{t[0], t[1], 0u, 0u};
             }
         }
     };
-
-    int tile = t_lo + wv;
-    if (tile < t_hi) load_tile(tile);
-    for (; tile < t_hi; tile += ATT_WAVES) {
-        // ---- stage K through LDS, keep V in registers ---------------------
-        u32x4 vcur[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vcur[e] = vbuf4[e];
+    auto stage_k = [&]() {
 #pragma unroll
         for (int r = 0; r < K_LOADS; ++r) {
             const int rl = r * K_ROWS_PER_LOAD + lane / K_PIECES;
-            *reinterpret_cast<u32x4 *>(wlds + rl * LROW + (lane % K_PIECES) * 16) = kbuf[r];
+            *reinterpret_cast<u32x4 *>(wlds + rl * LROW + k_col) = kbuf[r];
         }
+    };
+    // one 32-row tile: K from the wave's LDS area, V from registers
+    auto compute_tile = [&](int tile, const u32x4 (&vcur)[8]) {
         const int row0 = tile * ATT_TILE;
-        if (tile + ATT_WAVES < t_hi) load_tile(tile + ATT_WAVES);   // prefetch the next tile
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- scores: two 16-row tiles ------------------------------------
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
@@ -188,7 +182,6 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qop[c], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qop[c], s1, 0, 0, 0);
         }
-        __builtin_amdgcn_wave_barrier();
         // lane (q = li, kg) now holds rows 4kg+r (s0[r]) and 16+4kg+r (s1[r])
         float x[8];
 #pragma unroll
@@ -202,19 +195,22 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16, NGC_WAVE));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NGC_WAVE));
         const float m_new = fmaxf(m_run, tmax);           // finite: a tile has a valid row
-        const float alpha = fast_exp2(m_run - m_new);         // 0 on the first tile
+        if (__ballot(m_new != m_run)) {                   // wave-uniform: the running max moved somewhere
+            const float alpha = fast_exp2(m_run - m_new); // 0 on the first tile, 1 where nothing changed
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < DPL; ++c) oacc[c] *= alpha;
+            m_run = m_new;
+        }
         float p[8], psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            p[e] = fast_exp2(x[e] - m_new);
+            p[e] = fast_exp2(x[e] - m_run);
             psum += p[e];
         }
-        l_run = l_run * alpha + psum;   // lane-local part; lane groups are summed at the end
-        m_run = m_new;
-#pragma unroll
-        for (int c = 0; c < DPL; ++c) oacc[c] *= alpha;
+        l_run += psum;   // lane-local part; lane groups are summed at the end
 
-        // ---- P as bf16 head + bf16 remainder (B operands) -----------------
+        // P as bf16 head + bf16 remainder (B operands)
         uint32_t ph[4], pl[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
@@ -227,7 +223,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
         const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
         const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
 
-        // ---- O^T += V^T P --------------------------------------------------
+        // O^T += V^T P
 #pragma unroll
         for (int c = 0; c < DPL; ++c) {
             uint32_t va[4];
@@ -242,6 +238,32 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
             oacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi, oacc[c], 0, 0, 0);
             oacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo, oacc[c], 0, 0, 0);
         }
+    };
+
+    // Software pipeline, unrolled by two so that the V registers of the tile in
+    // flight and of the tile being computed are distinct (no copies): the loads
+    // of the next tile are issued before the current tile's math and are only
+    // waited for at the top of the next step.  The prefetch is unconditional (a
+    // tile past the end only re-reads the last row, which every load clamps to)
+    // so that the number of loads in flight is the same on every path and the
+    // wait for the current tile's data does not also wait for the prefetch.
+    u32x4 v_a[8], v_b[8];
+    int tile = t_lo + wv;
+    issue_loads(tile, v_a);
+    while (tile < t_hi) {
+        stage_k();
+        issue_loads(tile + ATT_WAVES, v_b);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_tile(tile, v_a);
+        __builtin_amdgcn_sched_barrier(0);
+        tile += ATT_WAVES;
+        if (tile >= t_hi) break;
+        stage_k();
+        issue_loads(tile + ATT_WAVES, v_a);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_tile(tile, v_b);
+        __builtin_amdgcn_sched_barrier(0);
+        tile += ATT_WAVES;
     }
 
     // ---- merge the waves of this workgroup ----------------------------------
