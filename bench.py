@@ -378,6 +378,37 @@ def main():
                "us": bw_us, "bytes": bw_bytes, "hbm_frac": bw_bytes / (bw_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
         del grad
 
+    # ---- config 4, other reading: one budget per sequence pooled over its KV heads
+    pooled = None
+    if w.per_head_budget and w.Hkv * cap <= 65536:
+        ws_p = torch.zeros(ngc.ngc_workspace_bytes(cache, cap) + 4 * nseg * cap, dtype=torch.uint8, device=dev)
+        kept_p = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.int32, device=dev)
+        sigma_p = torch.empty_like(kept_p)
+        pl_ms = []
+        for rep in range(3):
+            cache.len.copy_(len0)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            ngc.ngc_evict(cache, -1, logits, keep,
+                          ngc.make_params(noise_scale=1.0, round=0, seed=w.gumbel_seed, flags=ngc.EVICT_POOL_HEADS),
+                          cap, kept_p, sigma_p, logp, ws_p)
+            e1.record()
+            torch.cuda.synchronize()
+            pl_ms.append(e0.elapsed_time(e1))
+        lens_p = cache.len.cpu().numpy()
+        slot_p = torch.arange(cap, device=dev, dtype=torch.int32)
+        moved_p = float(((kept_p != slot_p) & (slot_p < cache.len.unsqueeze(-1))).sum().item())
+        pl_us = 1e3 * float(np.mean(pl_ms[1:]))
+        pl_bytes = evict_bytes(w, n_items0, lens_p, moved_p, True, True)
+        pooled = {"what": "round 0 with NGC_EVICT_POOL_HEADS: one top-K per (layer, sequence) over all heads' rows",
+                  "eviction_step_us": pl_us, "bytes_per_round": pl_bytes,
+                  "hbm_frac": pl_bytes / (pl_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                  "rows_kept_per_head_min_max": [int(lens_p.min()), int(lens_p.max())]}
+        assert all(x == 0 for x in ngc.read_status(ws_p)), "pooled run: status words not clean"
+        del ws_p, kept_p, sigma_p
+        cache.len.copy_(keep)       # back to the schedule's state
+
     per_layer = None
     if args.per_layer:
         reps = 20
@@ -435,6 +466,7 @@ def main():
         "eviction_unordered": unordered,
         "scoring": scoring,
         "logprob_backward": bwd,
+        "eviction_pooled_heads": pooled,
         "setup_s": t_setup,
     }
     if per_layer:

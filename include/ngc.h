@@ -96,9 +96,23 @@ typedef struct ngc_cache {
  *                K in place and move the i-th kept row at or beyond slot K
  *                into the i-th freed slot below K (both counted ascending).
  *                Same surviving set, far fewer rows moved; the cache is then
- *                no longer in order of original position (pos still names it). */
+ *                no longer in order of original position (pos still names it).
+ *                NGC_EVICT_POOL_HEADS (block == 1, Hkv * cap <= 65536): one
+ *                selection per (layer, sequence) over the rows of all its KV
+ *                heads; the budget is the sum of the heads' keep entries and
+ *                every head keeps however many of its rows make the pooled
+ *                top-K (item order for ties and for sigma: head, then row; the
+ *                noise of a row is the one the per-head mode draws for it).
+ *                kept_out then holds each head's own kept rows (ascending;
+ *                max_keep must cover the largest share), len the per-head
+ *                counts; sigma_out holds the pooled sequence, coded as
+ *                head * cap + row, in the Hkv rows of the (layer, sequence)
+ *                back to back; logp_out holds its log-probability in the entry
+ *                of head 0 and 0 in the others.  The workspace must be
+ *                ngc_workspace_bytes() + 4 * L * B * Hkv * cap bytes. */
 #define NGC_EVICT_SELECT_ONLY 1u
 #define NGC_EVICT_UNORDERED   2u
+#define NGC_EVICT_POOL_HEADS  4u
 typedef struct ngc_evict_params {
     int32_t  block;
     int32_t  share_heads;

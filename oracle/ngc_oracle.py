@@ -130,6 +130,23 @@ def evict_select(logits, K: int, tau: float, seed: int, rnd: int, l: int, b: int
     return select(perturbed_keys(logits, tau, seed, rnd, l, b, hsel), K)
 
 
+def evict_select_pooled(logits_per_head, K_total: int, tau: float, seed: int, rnd: int, l: int, b: int):
+    """One selection over the items of all KV heads of a (layer, sequence): the
+    heads' items are laid end to end in (head, row) order, every item keeps the
+    noise it would draw in its own head, and the K_total largest keys win.
+    Returns (kept rows per head, sigma as a list of (head, row), concatenated
+    logits, sigma as indices into the concatenation)."""
+    keys = [perturbed_keys(s, tau, seed, rnd, l, b, h) for h, s in enumerate(logits_per_head)]
+    sizes = [k.size for k in keys]
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    kept, sigma = select(np.concatenate(keys) if keys else np.zeros(0, np.float32), K_total)
+    head_of = np.searchsorted(offs, kept, side="right") - 1
+    kept_per_head = [(kept[head_of == h] - offs[h]).astype(np.int32) for h in range(len(keys))]
+    sh = np.searchsorted(offs, sigma, side="right") - 1
+    sigma_pairs = [(int(h), int(i - offs[h])) for h, i in zip(sh, sigma)]
+    return kept_per_head, sigma_pairs, np.concatenate([_arr(s, np.float32) for s in logits_per_head]), sigma
+
+
 # ------------------------------------------------------------- log-prob ---
 
 def logprob_literal(logits, sigma) -> float:

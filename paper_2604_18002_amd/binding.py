@@ -29,6 +29,7 @@ STATUS_BAD_SIGMA = 4
 
 EVICT_SELECT_ONLY = 1
 EVICT_UNORDERED = 2
+EVICT_POOL_HEADS = 4
 SCORE_NO_CAUSAL = 1
 SCORE_POOL_HEADS = 2
 

@@ -131,6 +131,7 @@ struct SelectArgs {
     int max_keep;
     int items_cap;       // ceil(cap / block): size of the code array in LDS
     int keep_cap;        // size of each index buffer in LDS
+    uint32_t *pool_codes; // pooled mode: key codes of every item, Hkv * cap per (layer, sequence)
     SegGeom g;
     NoiseArgs na;
 };
@@ -765,6 +766,337 @@ __device__ __forceinline__ void compact_pos_inplace(int32_t *pos, const int32_t 
     }
 }
 
+// ------------------------------------------------- pooled-heads mode ------
+//
+// One selection problem per (layer, sequence): the items of all its KV heads
+// compete for one budget, so heads whose logits are larger keep more rows.
+// Item order (for ties and for the sampled sequence) is (head, row); the noise
+// of item (head, row) is the one the per-head mode draws for it.  Up to
+// Hkv * cap = 65536 items: their key codes live in a workspace in global
+// memory (L2-resident while the workgroup works on them), the index buffers of
+// the sort stay in LDS.  Steps as in select_segment.
+
+constexpr int POOL_THREADS = 1024;
+constexpr int POOL_MAX_HEADS = 16;
+// misc slots of the pooled kernel
+constexpr int PM_N = 40;      // rows per head        [40, 56)
+constexpr int PM_OFF = 56;    // item offset per head [56, 73)
+constexpr int PM_BASE = 73;   // kept slots before each head [73, 90)
+
+template <int ROW_BYTES>
+__global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a)
+{
+    constexpr int THREADS = POOL_THREADS;
+    constexpr int NW = THREADS / NGC_WAVE;
+    constexpr int HIST = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint32_t *hist = reinterpret_cast<uint32_t *>(smem_raw);
+    int *misc = reinterpret_cast<int *>(hist + HIST);   // 128 ints
+    uint16_t *idxA = reinterpret_cast<uint16_t *>(misc + 128);
+    uint16_t *idxB = idxA + a.keep_cap;
+    float *fmisc = reinterpret_cast<float *>(misc);
+
+    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const int Hkv = a.g.Hkv, cap = a.g.cap;
+    const int lb = a.seg0 / Hkv + blockIdx.x;     // layer * B + sequence
+    const int l = lb / a.g.B, b = lb - l * a.g.B;
+    const int seg_first = lb * Hkv;
+    uint32_t *code = a.pool_codes + (size_t)lb * Hkv * cap;
+
+    // ---- 0. geometry of the pooled item space ------------------------------
+    if (tid == 0) {
+        int off = 0, ktot = 0;
+        for (int h = 0; h < Hkv; ++h) {
+            int n = a.len[seg_first + h];
+            if (n < 0 || n > cap) {
+                atomicAdd(&a.status[NGC_STATUS_LEN_CLAMPED], 1);
+                n = n < 0 ? 0 : cap;
+            }
+            int kh = a.keep[seg_first + h];
+            if (kh < 0) { atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1); kh = 0; }
+            misc[PM_N + h] = n;
+            misc[PM_OFF + h] = off;
+            off += n;
+            ktot += kh;
+        }
+        misc[PM_OFF + Hkv] = off;
+        int lim = off < a.keep_cap ? off : a.keep_cap;
+        if (ktot > lim) {
+            atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+            ktot = lim;
+        }
+        misc[MISC_KEPT] = ktot;
+    }
+    __syncthreads();
+    const int N = misc[PM_OFF + Hkv];
+    const int K = misc[MISC_KEPT];
+    const bool want_logp = a.logp_out != nullptr;
+    const bool want_sort = want_logp || a.sigma_out != nullptr;
+    auto head_of = [&](int i) {
+        int h = 0;
+        while (h + 1 < Hkv && i >= misc[PM_OFF + h + 1]) ++h;
+        return h;
+    };
+    if (K == 0) {
+        if (tid < Hkv) {
+            if (a.k) a.len_out[seg_first + tid] = 0;
+            if (want_logp) a.logp_out[seg_first + tid] = 0.f;
+        }
+        return;
+    }
+
+    // ---- 1. keys (and the first histogram of the radix select) -------------
+    for (int i = tid; i < SEL_BINS; i += THREADS) hist[i] = 0;
+    __syncthreads();
+    float smax = -INFINITY;
+    uint32_t cmax = 0;
+    for (int h = 0; h < Hkv; ++h) {
+        const int n = misc[PM_N + h], off = misc[PM_OFF + h];
+        const float *row = a.logits + (size_t)(seg_first + h) * cap;
+        for (int quad = tid; 4 * quad < n; quad += THREADS) {
+            float s[4], key[4];
+            keys_of_quad(row, n, quad, a.na, l, b, h, s, key);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (4 * quad + i < n) {
+                    const uint32_t c = ordered_code(key[i]);
+                    code[off + 4 * quad + i] = c;
+                    atomicAdd(&hist[c >> 21], 1u);
+                    cmax = c > cmax ? c : cmax;
+                    smax = fmaxf(smax, s[i]);
+                }
+        }
+    }
+    if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);
+    if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
+
+    // ---- 2. radix select ---------------------------------------------------
+    uint32_t prefix = 0, pmask = 0;
+    int need = K;
+    {
+        const int shifts[3] = {21, 10, 0};
+        const int widths[3] = {11, 11, 10};
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = shifts[pass], nb = 1 << widths[pass];
+            if (pass > 0) {
+                for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+                __syncthreads();
+                for (int t = tid; t < N; t += THREADS) {
+                    const uint32_t u = code[t];
+                    if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
+                }
+            }
+            __syncthreads();   // pass 0: also publishes the codes written in step 1
+            const int per = (nb + THREADS - 1) / THREADS;
+            int mine = 0;
+            for (int i = 0; i < per; ++i) {
+                const int p = tid * per + i;
+                if (p < nb) mine += (int)hist[nb - 1 - p];
+            }
+            int total;
+            int above = block_excl_scan_i<THREADS>(mine, misc, &total);
+            if (above < need && need <= above + mine) {
+                for (int i = 0; i < per; ++i) {
+                    const int p = tid * per + i;
+                    const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
+                    if (need <= above + c) {
+                        misc[32] = nb - 1 - p;
+                        misc[33] = above;
+                        break;
+                    }
+                    above += c;
+                }
+            }
+            __syncthreads();
+            const uint32_t digit = (uint32_t)misc[32];
+            need -= misc[33];
+            prefix |= digit << shift;
+            pmask |= (uint32_t)(nb - 1) << shift;
+            __syncthreads();
+        }
+    }
+    const uint32_t thr = prefix;
+
+    // ---- 3. kept items, ascending in (head, row) order ----------------------
+    const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+    const int w_begin = wv * per_wave;
+    const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
+    {
+        int gt = 0, eq = 0;
+        for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
+            const int t = t0 + lane;
+            const uint32_t u = (t < w_end) ? code[t] : 0u;
+            gt += __popcll(__ballot(t < w_end && u > thr));
+            eq += __popcll(__ballot(t < w_end && u == thr));
+        }
+        if (lane == 0) { misc[wv] = gt; misc[16 + wv] = eq; }
+    }
+    __syncthreads();
+    int gt_base = 0, eq_base = 0;
+    for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
+    float unpicked = 0.f;
+    for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
+        const int t = t0 + lane;
+        const bool in = t < w_end;
+        const uint32_t u = in ? code[t] : 0u;
+        const bool is_gt = in && u > thr, is_eq = in && u == thr;
+        const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
+        const int gt_before = gt_base + popc_below(bgt);
+        const int eq_before = eq_base + popc_below(beq);
+        const bool sel = is_gt || (is_eq && eq_before < need);
+        if (sel) {
+            idxA[gt_before + (eq_before < need ? eq_before : need)] = (uint16_t)t;
+        } else if (in && want_logp) {
+            const int h = head_of(t);
+            float x = a.logits[(size_t)(seg_first + h) * cap + (t - misc[PM_OFF + h])];
+            if (x != x) x = -INFINITY;
+            unpicked += expf(x - smax);
+        }
+        gt_base += __popcll(bgt);
+        eq_base += __popcll(beq);
+    }
+    __syncthreads();
+    // kept slots before each head: first slot whose item lies at or beyond the head's offset
+    if (tid <= Hkv) {
+        const int target = misc[PM_OFF + tid];
+        int lo = 0, hi = K;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((int)idxA[mid] < target) lo = mid + 1; else hi = mid;
+        }
+        misc[PM_BASE + tid] = lo;
+    }
+    __syncthreads();
+    for (int j = tid; j < K; j += THREADS) {
+        const int i = idxA[j];
+        const int h = head_of(i);
+        const int slot = j - misc[PM_BASE + h];
+        if (slot < a.max_keep) a.kept_out[(size_t)(seg_first + h) * a.max_keep + slot] = i - misc[PM_OFF + h];
+    }
+    if (tid < Hkv && misc[PM_BASE + tid + 1] - misc[PM_BASE + tid] > a.max_keep)
+        atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+
+    if (want_sort) {
+        // ---- 4. sigma ------------------------------------------------------
+        const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+        const int k_begin = wv * per_wave_k;
+        const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
+        uint16_t *src = idxA, *dst = idxB;
+        volatile uint32_t *vh = hist;
+        const uint32_t range = cmax - thr;
+        const int range_bits = range ? 32 - __clz(range) : 0;
+        const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
+        __syncthreads();   // kept_out loop above still reads idxA
+#pragma unroll 1
+        for (int pass = 0; pass < passes; ++pass) {
+            const int shift = SORT_BITS * pass;
+            for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
+            __syncthreads();
+            for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+                const int j = j0 + lane;
+                if (j < k_end) {
+                    const uint32_t d = ((cmax - code[src[j]]) >> shift) & (SORT_BINS - 1);
+                    atomicAdd(&hist[wv * SORT_BINS + d], 1u);
+                }
+            }
+            __syncthreads();
+            {
+                constexpr int PER = SORT_BINS * NW / THREADS;
+                int vals[PER], sum = 0;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    const int e = tid * PER + i;
+                    vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
+                    sum += vals[i];
+                }
+                int total;
+                int run = block_excl_scan_i<THREADS>(sum, misc, &total);
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    const int e = tid * PER + i;
+                    hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
+                    run += vals[i];
+                }
+            }
+            __syncthreads();
+            for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+                const int j = j0 + lane;
+                const bool in = j < k_end;
+                const uint16_t idx = in ? src[j] : (uint16_t)0;
+                const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
+                const uint64_t peers = match_digit(d, __ballot(in));
+                const int rank = popc_below(peers);
+                uint32_t base = 0;
+                if (in) base = vh[wv * SORT_BINS + d];
+                __builtin_amdgcn_wave_barrier();
+                if (in) {
+                    dst[base + rank] = idx;
+                    if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            __syncthreads();
+            uint16_t *tmp = src; src = dst; dst = tmp;
+        }
+        auto logit_of_item = [&](int i) {
+            const int h = head_of(i);
+            const float x = a.logits[(size_t)(seg_first + h) * cap + (i - misc[PM_OFF + h])];
+            return (x != x) ? -INFINITY : x;
+        };
+        if (a.sigma_out) {
+            // the pooled sequence occupies the Hkv rows of this (layer, sequence) back to back
+            int32_t *sig_row = a.sigma_out + (size_t)seg_first * a.max_keep;
+            const int room = Hkv * a.max_keep;
+            for (int j = tid; j < K && j < room; j += THREADS) {
+                const int i = src[j];
+                const int h = head_of(i);
+                sig_row[j] = h * cap + (i - misc[PM_OFF + h]);
+            }
+        }
+        if (want_logp) {
+            // ---- 5. log-probability of the pooled sequence -------------------
+            const float U = block_sum_f<THREADS>(unpicked, fmisc);
+            const int chunk = (K + THREADS - 1) / THREADS;
+            const int nchunks = (K + chunk - 1) / chunk;
+            const int cidx = nchunks - 1 - tid;
+            const int j_lo = cidx * chunk;
+            const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+            float mass = 0.f;
+            if (cidx >= 0)
+                for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of_item(src[j]) - smax);
+            float total_mass;
+            const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
+            float acc = 0.f;
+            if (cidx >= 0) {
+                float R = U + after;
+                for (int j = j_hi - 1; j >= j_lo; --j) {
+                    const float d = logit_of_item(src[j]) - smax;
+                    R += expf(d);
+                    acc += d - logf(R);
+                }
+            }
+            const float lp = block_sum_f<THREADS>(acc, fmisc);
+            if (tid < Hkv) a.logp_out[seg_first + tid] = (tid == 0) ? lp : 0.f;
+        }
+    }
+    if (a.k == nullptr) return;
+
+    // ---- 6. per-head compaction ---------------------------------------------
+    __syncthreads();   // kept_out of this workgroup is complete and visible
+    for (int h = 0; h < Hkv; ++h) {
+        int Kh = misc[PM_BASE + h + 1] - misc[PM_BASE + h];
+        Kh = Kh < a.max_keep ? Kh : a.max_keep;
+        const size_t seg_off = (size_t)(seg_first + h) * cap * ROW_BYTES;
+        const int32_t *kept = a.kept_out + (size_t)(seg_first + h) * a.max_keep;
+        compact_kv_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                  kept, Kh, 0, 1);
+        if (a.pos) compact_pos_inplace<THREADS>(a.pos + (size_t)(seg_first + h) * cap, kept, Kh, 0, 1);
+        if (tid == 0) a.len_out[seg_first + h] = Kh;
+    }
+}
+
 // One workgroup per segment: sample, score, then move the survivors.  While a
 // workgroup is in its (ALU/LDS bound) selection phase, the other workgroups of
 // the grid keep the memory system busy with their compaction phase.
@@ -930,6 +1262,44 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     if (ws_bytes < STATUS_BYTES + (size_t)nseg_total * 8) return NGC_ENOSPC;
     if (!aligned16(ws)) return NGC_EINVAL;
 
+    if (p->flags & NGC_EVICT_POOL_HEADS) {
+        // one selection per (layer, sequence) over the items of all its heads
+        if (p->block != 1 || (p->flags & NGC_EVICT_UNORDERED)) return NGC_EUNSUPPORTED;
+        if (c->Hkv > POOL_MAX_HEADS || (long long)c->Hkv * c->cap > 65536) return NGC_EUNSUPPORTED;
+        const size_t codes_off = ngc_workspace_bytes(c, max_keep);
+        const size_t codes_bytes = (size_t)c->L * c->B * c->Hkv * c->cap * sizeof(uint32_t);
+        if (ws_bytes < codes_off + codes_bytes) return NGC_ENOSPC;
+        long long kc = (long long)c->Hkv * max_keep;
+        if (kc > (long long)c->Hkv * c->cap) kc = (long long)c->Hkv * c->cap;
+        int keep_cap = (int)((kc + 7) & ~7LL);
+        const int hist = (SEL_BINS > SORT_BINS * (POOL_THREADS / 64)) ? SEL_BINS : SORT_BINS * (POOL_THREADS / 64);
+        size_t lds = (size_t)hist * 4 + 128 * 4 + (size_t)keep_cap * 2 * 2;
+        if (lds > 160 * 1024) {
+            // the index buffers do not fit: allow as many kept items as LDS holds
+            keep_cap = (int)(((160 * 1024 - (size_t)hist * 4 - 128 * 4) / 4) & ~7u);
+            lds = (size_t)hist * 4 + 128 * 4 + (size_t)keep_cap * 2 * 2;
+        }
+        SelectArgs sa;
+        sa.logits = logits; sa.len = c->len; sa.keep = keep;
+        sa.kept_out = kept_out; sa.sigma_out = sigma_out; sa.logp_out = logp_out;
+        sa.status = reinterpret_cast<int32_t *>(ws);
+        const bool move = !(p->flags & NGC_EVICT_SELECT_ONLY);
+        sa.k = move ? c->k : nullptr; sa.v = c->v; sa.pos = c->pos; sa.len_out = c->len;
+        sa.unordered = 0;
+        sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = 0; sa.keep_cap = keep_cap;
+        sa.pool_codes = reinterpret_cast<uint32_t *>(reinterpret_cast<unsigned char *>(ws) + codes_off);
+        sa.g = SegGeom{c->B, c->Hkv, c->cap, 1};
+        sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
+        const void *fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_pooled_kernel<256>)
+                                       : reinterpret_cast<const void *>(&evict_pooled_kernel<128>);
+        if (lds > 64 * 1024)
+            NGC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        void *kargs[] = {&sa};
+        NGC_HIP_CHECK(hipLaunchKernel(fn, dim3(nseg / c->Hkv), dim3(POOL_THREADS), kargs, lds,
+                                      (hipStream_t)stream));
+        return NGC_OK;
+    }
+
     const int items_cap = (c->cap + p->block - 1) / p->block;
     if (items_cap > 16384) return NGC_EUNSUPPORTED;
     int keep_cap = max_keep < items_cap ? max_keep : items_cap;
@@ -948,6 +1318,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     sa.status = status;
     sa.k = move_rows ? c->k : nullptr; sa.v = c->v; sa.pos = c->pos; sa.len_out = c->len;
     sa.unordered = (p->flags & NGC_EVICT_UNORDERED) ? 1 : 0;
+    sa.pool_codes = nullptr;
     sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
     sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
     sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};

@@ -487,3 +487,57 @@ def test_subset_logprob_backward():
     torch.cuda.synchronize()
     want = orc.logprob_grad(logits[3, :n_items[3]], sigma[3, :keep[3]])
     assert np.abs(grad[3, :n_items[3]].cpu().numpy() - want).max() <= 1e-4
+
+
+# ----------------------------------------------------- pooled over heads ---
+
+@pytest.mark.parametrize("idx,over,sel_only", [
+    (4, dict(L=1, B=2), False),                       # 4 heads x 16384 rows, heavy-tailed logits
+    (1, dict(L=2, B=3), False),                       # ragged, 2 heads
+    (3, dict(L=1, B=2, n_lo=700, n_hi=3000), True),   # selection only
+])
+def test_pooled_heads_eviction(idx, over, sel_only):
+    import torch
+    ngc = _ngc()
+    w = synth.workload(idx, **over)
+    case = host_case(w)
+    cache, logits, keep = upload(case, with_pos=True)
+    # a head may keep far more than its even share: give the lists the full capacity
+    max_keep = w.cap
+    nbytes = ngc.ngc_workspace_bytes(cache, max_keep) + 4 * w.L * w.B * w.Hkv * w.cap
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.full((w.L, w.B, w.Hkv), float("nan"), dtype=torch.float32, device="cuda")
+    flags = ngc.EVICT_POOL_HEADS | (ngc.EVICT_SELECT_ONLY if sel_only else 0)
+    p = ngc.make_params(noise_scale=1.0, round=2, seed=w.gumbel_seed, flags=flags)
+    print(f"[evict-pooled] workload={w.name} L={w.L} B={w.B} Hkv={w.Hkv} cap={w.cap}", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+    hk, hv = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v)
+    hlen, hpos = cache.len.cpu().numpy(), cache.pos.cpu().numpy()
+    hkept, hsig, hlp = kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy()
+    shares = set()
+    for l in range(w.L):
+        for b in range(w.B):
+            heads = [case.logits[(l, b, h)] for h in range(w.Hkv)]
+            K_total = int(case.keep[l, b].sum())
+            okept, osig, cat, osig_idx = orc.evict_select_pooled(heads, K_total, 1.0, w.gumbel_seed, 2, l, b)
+            olp = oracle_logprob(cat, osig_idx)
+            got_sig = hsig[l, b].reshape(-1)[:K_total]
+            assert got_sig.tolist() == [h * w.cap + t for h, t in osig], (l, b)
+            assert hlp[l, b, 0] == pytest.approx(olp, rel=LOGP_RTOL), (l, b)
+            assert (hlp[l, b, 1:] == 0).all()
+            for h in range(w.Hkv):
+                Kh = okept[h].size
+                shares.add(Kh)
+                assert hkept[l, b, h, :Kh].tolist() == okept[h].tolist(), (l, b, h)
+                if sel_only:
+                    assert hlen[l, b, h] == case.lens[b]
+                    continue
+                assert hlen[l, b, h] == Kh
+                assert hk[l, b, h, :Kh].tobytes() == orc.compact_rows(case.k[(l, b, h)], okept[h]).tobytes()
+                assert hv[l, b, h, :Kh].tobytes() == orc.compact_rows(case.v[(l, b, h)], okept[h]).tobytes()
+                assert hpos[l, b, h, :Kh].tolist() == okept[h].tolist()
+    assert len(shares) > 1          # the heads really keep different numbers of rows

@@ -216,3 +216,23 @@ def test_noise_scale_flattens_the_choice():
     first = sum(int(orc.evict_select(s, 1, 50.0, 5, r, 0, 0, 0)[1][0] == 0) for r in range(N)) / N
     p = math.exp(3 / 50.0) / (math.exp(3 / 50.0) + 3)
     assert first == pytest.approx(p, abs=0.015)
+
+
+# ------------------------------------------------------ pooled over heads ---
+
+def test_pooled_selection_is_one_topk_over_all_heads():
+    rng = np.random.default_rng(6)
+    heads = [rng.standard_normal(n).astype(np.float32) for n in (50, 80, 65)]
+    heads[1][:10] += 4.0                                  # one head clearly more important
+    kept, sigma, cat, sig_idx = orc.evict_select_pooled(heads, 60, 0.0, 1, 0, 0, 0)
+    order = np.argsort(-cat.astype(np.float64), kind="stable")[:60]      # library top-k over the concatenation
+    assert sig_idx.tolist() == order.tolist()
+    offs = [0, 50, 130]
+    want = [sorted(int(i - offs[h]) for i in order if offs[h] <= i < offs[h] + len(heads[h])) for h in range(3)]
+    assert [k.tolist() for k in kept] == want
+    assert sum(k.size for k in kept) == 60 and kept[1].size > kept[0].size
+    assert sigma[0] == (1, int(np.argmax(heads[1])))
+    # with noise: every item keeps the noise of its own head, so a single head pooled alone is the per-head sample
+    k1, s1, _, _ = orc.evict_select_pooled([heads[0]], 20, 1.0, 9, 2, 3, 4)
+    k0, s0 = orc.evict_select(heads[0], 20, 1.0, 9, 2, 3, 4, 0)
+    assert k1[0].tolist() == k0.tolist() and [t for _, t in s1] == s0.tolist()
