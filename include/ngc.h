@@ -216,10 +216,13 @@ int ngc_cache_append(const ngc_cache *c, int32_t layer, const void *k_new,
  *   scale          usually 1 / sqrt(D)
  *   max_len_hint   an upper bound on len the caller knows (0 = use cap); it
  *                  only steers how the work is split, never the result.
+ *   lse_out        optional fp32 [B][Hq] (or [L][B][Hq]): log sum_j exp(scale *
+ *                  <q, K[j]>) per query head (natural log; -inf for n == 0), or
+ *                  NULL.  ngc_score_keys can reuse it.
  * n == 0 gives zeros (and is counted).  Scores, softmax and accumulation are
  * fp32.  ws must hold ngc_workspace_bytes(). */
 int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
-                    int32_t max_len_hint, float *out,
+                    int32_t max_len_hint, float *out, float *lse_out,
                     void *ws, size_t ws_bytes, void *stream);
 
 /* Key importance scores for the eviction policy (Sec. 4.2): for every segment
@@ -235,6 +238,10 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
  * the KV heads of the (layer, sequence) -- the paper's one score per layer and
  * block -- and written to every head.
  *   q_recent    bf16 [B][w][Hq][D] (or [L][B][w][Hq][D] for layer = -1), 16-byte aligned
+ *   lse_recent  optional fp32 [B][w][Hq] (or [L][B][w][Hq]): the log-sum-exp of
+ *               each recent query over the rows it can see, as ngc_decode_attn
+ *               returned it when that token was decoded (causal reading only).
+ *               With it the keys are read once instead of twice.  NULL = compute.
  *   scores_out  fp32 [L][B][Hkv][cap], item j of a segment at offset j: the
  *               layout ngc_evict takes as logits.  Entries past the item count
  *               are unspecified.
@@ -242,7 +249,8 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
  * ws needs NGC_STATUS_WORDS * 4 bytes (status only). */
 #define NGC_SCORE_NO_CAUSAL  1u
 #define NGC_SCORE_POOL_HEADS 2u
-int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent, int32_t w,
+int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
+                   const float *lse_recent, int32_t w,
                    float scale, uint32_t flags, int32_t block, float *scores_out,
                    void *ws, size_t ws_bytes, void *stream);
 

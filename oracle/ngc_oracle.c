@@ -378,6 +378,27 @@ void orc_decode_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
     free(o);
 }
 
+/* log sum_j exp(scale * <q_g, k_j>) for every query head g (natural log,
+ * -inf for n == 0): the normaliser of the attention above. */
+void orc_decode_lse(const uint16_t *q, const uint16_t *k, int32_t n, int32_t G,
+                    int32_t D, double scale, double *lse)
+{
+    for (int32_t g = 0; g < G; ++g) {
+        double mx = -INFINITY, den = 0.0;
+        double *x = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        for (int32_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int32_t d = 0; d < D; ++d)
+                acc += bf16_to_double(q[(size_t)g * D + d]) * bf16_to_double(k[(size_t)j * D + d]);
+            x[j] = acc * scale;
+            if (x[j] > mx) mx = x[j];
+        }
+        for (int32_t j = 0; j < n; ++j) den += exp(x[j] - mx);
+        lse[g] = (n > 0) ? mx + log(den) : -INFINITY;
+        free(x);
+    }
+}
+
 /* ------------------------------------------------------------ scoring --- */
 
 /* Key importance for one KV head of one sequence (Sec. 4.2).

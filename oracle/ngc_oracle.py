@@ -66,6 +66,8 @@ def _L():
         f64p = C.POINTER(C.c_double)
         lib.orc_logprob_grad_literal.argtypes = [f32p, C.c_int32, i32p, C.c_int32, f64p]
         lib.orc_logprob_grad_literal.restype = None
+        lib.orc_decode_lse.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_double, f64p]
+        lib.orc_decode_lse.restype = None
         lib.orc_score_keys.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_double, C.c_int32, f64p]
         lib.orc_score_keys.restype = None
@@ -218,6 +220,16 @@ def decode_attn(q_u16, k_u16, v_u16, scale: float) -> np.ndarray:
     out = np.zeros((G, D), np.float32)
     _L().orc_decode_attn(_p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16), n, G, D,
                          float(scale), _p(out, C.c_float))
+    return out
+
+
+def decode_lse(q_u16, k_u16, scale: float) -> np.ndarray:
+    """Log-sum-exp of the scaled scores per query head: fp64 [G]."""
+    q = _arr(q_u16, np.uint16)
+    k = _arr(k_u16, np.uint16)
+    G, D = q.shape
+    out = np.zeros(G, np.float64)
+    _L().orc_decode_lse(_p(q, C.c_uint16), _p(k, C.c_uint16), k.shape[0], G, D, float(scale), _p(out, C.c_double))
     return out
 
 

@@ -85,11 +85,11 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_subset_logprob.restype = C.c_int
     lib.ngc_cache_append.argtypes = [cp, i32, vp, vp, vp, vp, sz, vp]
     lib.ngc_cache_append.restype = C.c_int
-    lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, vp, sz, vp]
     lib.ngc_decode_attn.restype = C.c_int
     lib.ngc_subset_logprob_backward.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, sz, vp]
     lib.ngc_subset_logprob_backward.restype = C.c_int
-    lib.ngc_score_keys.argtypes = [cp, i32, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
+    lib.ngc_score_keys.argtypes = [cp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_score_keys.restype = C.c_int
     if path == LIB_PATH:
         _lib = lib
@@ -203,16 +203,17 @@ def ngc_cache_append(cache: Cache, layer: int, k_new, v_new, new_pos, ws, stream
                                            _ptr(ws), ws.numel(), _stream(stream)), "ngc_cache_append")
 
 
-def ngc_decode_attn(cache: Cache, layer: int, q, scale: float, max_len_hint: int, out, ws, stream=None):
+def ngc_decode_attn(cache: Cache, layer: int, q, scale: float, max_len_hint: int, out, ws, stream=None,
+                    lse_out=None):
     v = cache.view()
     _check(load_library().ngc_decode_attn(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
-                                          _ptr(ws), ws.numel(), _stream(stream)), "ngc_decode_attn")
+                                          _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)), "ngc_decode_attn")
 
 
 def ngc_score_keys(cache: Cache, layer: int, q_recent, w: int, scale: float, flags: int, block: int,
-                   scores_out, ws, stream=None):
+                   scores_out, ws, stream=None, lse_recent=None):
     v = cache.view()
-    _check(load_library().ngc_score_keys(C.byref(v), layer, _ptr(q_recent), w, scale, flags, block,
+    _check(load_library().ngc_score_keys(C.byref(v), layer, _ptr(q_recent), _ptr(lse_recent), w, scale, flags, block,
                                          _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
            "ngc_score_keys")
 

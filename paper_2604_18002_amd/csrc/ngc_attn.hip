@@ -44,6 +44,7 @@ struct AttnArgs {
     const int32_t *len;
     const unsigned char *q;
     float *out;
+    float *lse_out;   // optional: log-sum-exp of the scaled scores per query head, natural log
     float *part_o;    // [nseg_launch][S][G][D]
     float *part_ml;   // [nseg_launch][S][G][2]
     int32_t *status;
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
 
     if (n == 0) {
         if (split == 0) {
+            if (a.lse_out && threadIdx.x < G) a.lse_out[((size_t)lb * a.Hkv + h) * G + threadIdx.x] = -INFINITY;
             for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) out_seg[i] = 0.f;
             if (threadIdx.x == 0) atomicAdd(&a.status[NGC_STATUS_EMPTY_ATTN], 1);
         }
@@ -310,6 +312,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
         ml[0] = m_all;
         ml[1] = l_all;
     }
+    if (direct && a.lse_out && wv == 0 && kg == 0 && li < G)
+        a.lse_out[((size_t)lb * a.Hkv + h) * G + li] = (m_all + __log2f(l_all)) * 0.6931471805599453f;
 }
 
 // Merge of the split partials: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
@@ -341,6 +345,8 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(AttnArgs a)
             den += pml[(s * G + qi) * 2 + 1] * w;
         }
         out_seg[i] = num / den;
+        if (a.lse_out && i == qi * D)
+            a.lse_out[((size_t)lb * a.Hkv + h) * G + qi] = (M + __log2f(den)) * 0.6931471805599453f;
     }
 }
 
@@ -420,7 +426,7 @@ extern "C" size_t ngc_workspace_bytes(const ngc_cache *c, int32_t max_keep)
 }
 
 extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
-                               int32_t max_len_hint, float *out,
+                               int32_t max_len_hint, float *out, float *lse_out,
                                void *ws, size_t ws_bytes, void *stream)
 {
     if (!c || !c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
@@ -445,6 +451,7 @@ extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q,
     aa.len = c->len;
     aa.q = reinterpret_cast<const unsigned char *>(q);
     aa.out = out;
+    aa.lse_out = lse_out;
     aa.part_o = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off);
     aa.part_ml = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off +
                                            partial_o_bytes(c, nseg, S));

@@ -27,6 +27,7 @@ struct ScoreArgs {
     const unsigned char *k;
     const int32_t *len;
     const unsigned char *q;   // bf16 [lb][w][Hq][D]
+    const float *lse;         // optional fp32 [lb][w][Hq]: log-sum-exp of every query's scaled scores
     float *psi_out;           // fp32 [seg][cap], one value per key
     int32_t *status;
     int seg0, lb0;
@@ -110,6 +111,20 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
     };
 
     // ------------------------------------------------ pass 1: max and sum ---
+    // (skipped when the caller hands over the log-sum-exp that decode attention
+    // already computed for these very queries: then K is read only once)
+    if (a.lse != nullptr) {
+        for (int r = threadIdx.x; r < QT * 16; r += SC_WAVES * 64) {
+            float m2 = -INFINITY;
+            if (r < R) {
+                const int j = r / G, g = r - j * G;
+                m2 = a.lse[((size_t)lb * w + j) * Hq + (size_t)h * G + g] * 1.4426950408889634f;
+            }
+            fin_m[r] = m2;
+            fin_il[r] = (m2 > -INFINITY) ? 1.0f : 0.f;
+        }
+        __syncthreads();
+    } else {
     float m_run[QT], l_run[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
@@ -183,6 +198,7 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
         fin_il[r] = (L > 0.f) ? 1.0f / L : 0.f;
     }
     __syncthreads();
+    }
 
     // ------------------------------------- pass 2: probabilities per key ---
     // lane (key = li, kg) holds query rows qt*16 + 4kg + r
@@ -306,7 +322,8 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ReduceArgs a)
 
 using namespace ngc;
 
-extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent, int32_t w,
+extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
+                              const float *lse_recent, int32_t w,
                               float scale, uint32_t flags, int32_t block, float *scores_out,
                               void *ws, size_t ws_bytes, void *stream)
 {
@@ -317,6 +334,7 @@ extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_r
     if (c->Hq % c->Hkv != 0 || w < 1 || block < 1 || !(scale == scale)) return NGC_EINVAL;
     if (layer < -1 || layer >= c->L) return NGC_EINVAL;
     if (ws_bytes < NGC_STATUS_WORDS * sizeof(int32_t)) return NGC_ENOSPC;
+    if (lse_recent && (flags & NGC_SCORE_NO_CAUSAL)) return NGC_EINVAL;   // decode's lse is the causal one
     const int G = c->Hq / c->Hkv;
     const int R = w * G;
     if (R > 64) return NGC_EUNSUPPORTED;
@@ -329,6 +347,7 @@ extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_r
     sa.k = reinterpret_cast<const unsigned char *>(c->k);
     sa.len = c->len;
     sa.q = reinterpret_cast<const unsigned char *>(q_recent);
+    sa.lse = lse_recent;
     sa.psi_out = scores_out;
     sa.status = reinterpret_cast<int32_t *>(ws);
     sa.seg0 = seg0;

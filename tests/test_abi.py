@@ -58,7 +58,7 @@ def test_host_side_argument_checks_need_no_gpu(lib):
     p = binding.make_params()
     # null cache pointers are rejected before anything touches a device
     assert lib.ngc_evict(C.byref(c), -1, None, None, C.byref(p), 1, None, None, None, None, 0, None) == binding.NGC_EINVAL
-    assert lib.ngc_decode_attn(C.byref(c), 0, None, 0.125, 0, None, None, 0, None) == binding.NGC_EINVAL
+    assert lib.ngc_decode_attn(C.byref(c), 0, None, 0.125, 0, None, None, None, 0, None) == binding.NGC_EINVAL
     assert lib.ngc_subset_logprob(None, None, None, None, 1, 1, 1, None, None, 0, None) == binding.NGC_EINVAL
     assert lib.ngc_workspace_bytes(C.byref(c), 256) >= binding.STATUS_WORDS * 4 + 2 * 2 * 4
 

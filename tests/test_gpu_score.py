@@ -132,3 +132,54 @@ def test_scores_feed_the_eviction_step():
         thr = psi[order[K - 1]]
         unsure = {int(t) for t in np.flatnonzero(np.abs(psi - thr) <= 2 * RTOL * thr)}
         assert (got ^ want) <= unsure, (seg, margin)
+
+
+def test_decode_lse_and_single_pass_scoring():
+    """Decode w tokens (append + attend, keeping each step's log-sum-exp), then score with those
+    normalisers handed over: same scores as the two-pass kernel and as the oracle."""
+    import torch
+    ngc = _ngc()
+    wl = synth.workload(3, L=2, B=3, n_lo=300, n_hi=900)
+    case = host_case(wl)
+    cache, _, _ = upload(case, cap=wl.cap + 8)
+    w_ = 5
+    ws = ngc.allocate_workspace(cache, 1)
+    scale = 1.0 / np.sqrt(wl.D)
+    qs, lses, new_k = [], [], []
+    for j in range(w_):
+        nk = np.stack([synth.new_token_kv(wl, l, j)[0] for l in range(wl.L)])
+        nv = np.stack([synth.new_token_kv(wl, l, j)[1] for l in range(wl.L)])
+        q = np.stack([synth.queries(wl, l, 200 + j) for l in range(wl.L)])          # [L,B,Hq,D]
+        out = torch.zeros(wl.L, wl.B, wl.Hq, wl.D, dtype=torch.float32, device="cuda")
+        lse = torch.zeros(wl.L, wl.B, wl.Hq, dtype=torch.float32, device="cuda")
+        print(f"[decode+lse] step {j}", flush=True)
+        ngc.ngc_cache_append(cache, -1, to_bf16_tensor(nk, "cuda"), to_bf16_tensor(nv, "cuda"), None, ws)
+        ngc.ngc_decode_attn(cache, -1, to_bf16_tensor(q, "cuda"), scale, 0, out, ws, lse_out=lse)
+        qs.append(q); lses.append(lse); new_k.append(nk)
+    torch.cuda.synchronize()
+    q_recent = np.stack(qs, axis=2)                                                  # [L,B,w,Hq,D]
+    lse_recent = torch.stack(lses, dim=2).contiguous()                               # [L,B,w,Hq]
+    cap = cache.k.shape[3]
+    s_two = torch.zeros(wl.L, wl.B, wl.Hkv, cap, dtype=torch.float32, device="cuda")
+    s_one = torch.zeros_like(s_two)
+    print("[score] two passes, then one pass with decode's lse", flush=True)
+    ngc.ngc_score_keys(cache, -1, to_bf16_tensor(q_recent, "cuda"), w_, scale, 0, 1, s_two, ws)
+    ngc.ngc_score_keys(cache, -1, to_bf16_tensor(q_recent, "cuda"), w_, scale, 0, 1, s_one, ws, lse_recent=lse_recent)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+    h_two, h_one, h_lse = s_two.cpu().numpy(), s_one.cpu().numpy(), lse_recent.cpu().numpy()
+    G = wl.G
+    for (l, b, h) in case.segs:
+        kk = np.concatenate([case.k[(l, b, h)]] + [new_k[j][l, b, h][None] for j in range(w_)])
+        n = kk.shape[0]
+        want = orc.score_keys(q_recent[l, b, :, h * G:(h + 1) * G], kk, scale, True)
+        for got in (h_two[l, b, h, :n], h_one[l, b, h, :n]):
+            assert np.all(np.abs(got - want) <= RTOL * np.abs(want) + ATOL), ((l, b, h), np.abs(got - want).max())
+        for j in range(w_):
+            vis = n - w_ + j + 1
+            want_lse = orc.decode_lse(q_recent[l, b, j, h * G:(h + 1) * G], kk[:vis], scale)
+            assert np.abs(h_lse[l, b, j, h * G:(h + 1) * G] - want_lse).max() <= 2e-5
+    # the normalisers belong to the causal reading only
+    with pytest.raises(ngc.NgcError):
+        ngc.ngc_score_keys(cache, -1, to_bf16_tensor(q_recent, "cuda"), w_, scale, ngc.SCORE_NO_CAUSAL, 1, s_one, ws,
+                           lse_recent=lse_recent)

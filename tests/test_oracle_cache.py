@@ -177,3 +177,15 @@ def test_paper_example_half_eviction():
     # eviction rate 1/2 with cadence 256: the steady state before a round is 512
     assert orc.steady_state(256, 1, 2) == 512
     assert orc.trajectory_fraction(256, 256, 1, 2, 30)[-1] == 512
+
+
+def test_decode_lse_is_library_logsumexp():
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(35)
+    G, D, n = 5, 64, 123
+    q, k = _rand_bf16(rng, (G, D)), _rand_bf16(rng, (n, D))
+    qf = synth.bf16_bits_to_f32(q).astype(np.float64)
+    kf = synth.bf16_bits_to_f32(k).astype(np.float64)
+    want = logsumexp(qf @ kf.T * 0.125, axis=1)
+    assert np.abs(orc.decode_lse(q, k, 0.125) - want).max() < 1e-12
+    assert np.isneginf(orc.decode_lse(q, k[:0], 0.125)).all()
