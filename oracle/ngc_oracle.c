@@ -33,6 +33,9 @@
  *   orc_decode_attn     softmax(q K^T / sqrt(d_h)) V over the surviving rows
  *                       (Sec. 4.2 for the scale, Sec. 4.1 for "conditioned on
  *                       the surviving entries")
+ *   orc_replay_attn     attention of a whole trajectory under the replay mask:
+ *                       query i sees key j iff j <= i and j had not been evicted
+ *                       when token i was generated (Sec. 4.5, Appendix A.3)
  *   orc_score_keys      importance of every cached key: attention weights of
  *                       the w most recent queries, averaged over heads and
  *                       queries (Sec. 4.2, "Parameterizing eviction actions")
@@ -447,4 +450,44 @@ void orc_block_means(const double *psi, int32_t n, int32_t block, double *s)
         for (int32_t t = lo; t < hi; ++t) acc += psi[t];
         s[j] = acc / (double)(hi - lo);
     }
+}
+
+/* ------------------------------------------------------------- replay --- */
+
+/* One KV head of one sequence, all T positions at once.  death[j] is the first
+ * query position that can no longer see key j (T or more if j is never
+ * evicted); visibility is  j <= i < death[j]  (Sec. 4.5: the mask replicates
+ * the visibility pattern that the eviction decisions induced).
+ *   q [T][G][D], k, v [T][D]  ->  out [T][G][D] (fp32). */
+void orc_replay_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                     const int32_t *death, int32_t T, int32_t G, int32_t D,
+                     double scale, float *out)
+{
+    double *x = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1));
+    double *o = (double *)malloc(sizeof(double) * (size_t)D);
+    for (int32_t i = 0; i < T; ++i)
+        for (int32_t g = 0; g < G; ++g) {
+            const uint16_t *qr = q + ((size_t)i * G + g) * D;
+            double mx = -INFINITY;
+            for (int32_t j = 0; j <= i; ++j) {
+                if (death[j] <= i) continue;
+                double acc = 0.0;
+                for (int32_t d = 0; d < D; ++d)
+                    acc += bf16_to_double(qr[d]) * bf16_to_double(k[(size_t)j * D + d]);
+                x[j] = acc * scale;
+                if (x[j] > mx) mx = x[j];
+            }
+            double den = 0.0;
+            for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
+            for (int32_t j = 0; j <= i; ++j) {
+                if (death[j] <= i) continue;
+                double p = exp(x[j] - mx);
+                den += p;
+                for (int32_t d = 0; d < D; ++d) o[d] += p * bf16_to_double(v[(size_t)j * D + d]);
+            }
+            for (int32_t d = 0; d < D; ++d)
+                out[((size_t)i * G + g) * D + d] = (den > 0.0) ? (float)(o[d] / den) : 0.0f;
+        }
+    free(x);
+    free(o);
 }

@@ -68,6 +68,8 @@ def _L():
         lib.orc_logprob_grad_literal.restype = None
         lib.orc_decode_lse.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_double, f64p]
         lib.orc_decode_lse.restype = None
+        lib.orc_replay_attn.argtypes = [u16p, u16p, u16p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_double, f32p]
+        lib.orc_replay_attn.restype = None
         lib.orc_score_keys.argtypes = [u16p, u16p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_double, C.c_int32, f64p]
         lib.orc_score_keys.restype = None
@@ -253,6 +255,52 @@ def block_means(psi, block: int) -> np.ndarray:
     s = np.zeros(max(N, 1), np.float64)
     _L().orc_block_means(_p(x, C.c_double), x.size, block, _p(s, C.c_double))
     return s[:N]
+
+
+# ---------------------------------------------------------------- replay --
+
+def replay_death(T: int, boundaries, decisions) -> np.ndarray:
+    """Turn per-round retention decisions into one number per token (Appendix
+    A.3): round r fires when `boundaries[r]` tokens exist; `decisions[r]` is a
+    0/1 vector over the tokens alive at that moment (ascending); a token that a
+    round drops is invisible to every query from position boundaries[r] on.
+    Returns death[T]: first query position that cannot see the token (T if
+    it survives to the end)."""
+    death = np.full(T, T, np.int32)
+    alive = []
+    nxt = 0
+    for bnd, dec in zip(boundaries, decisions):
+        alive.extend(range(nxt, bnd))
+        nxt = bnd
+        dec = np.asarray(dec).astype(bool)
+        assert dec.size == len(alive), "one decision per alive token"
+        for tok, keep in zip(alive, dec):
+            if not keep:
+                death[tok] = bnd
+        alive = [tok for tok, keep in zip(alive, dec) if keep]
+    return death
+
+
+def replay_mask(death) -> np.ndarray:
+    """Dense replay mask: M[i, j] = (j <= i < death[j])."""
+    d = np.asarray(death)
+    T = d.size
+    i = np.arange(T)[:, None]
+    j = np.arange(T)[None, :]
+    return (j <= i) & (i < d[None, :])
+
+
+def replay_attn(q_u16, k_u16, v_u16, death, scale: float) -> np.ndarray:
+    """q: [T, G, D], k, v: [T, D], death: [T].  Returns fp32 [T, G, D]."""
+    q = _arr(q_u16, np.uint16)
+    k = _arr(k_u16, np.uint16)
+    v = _arr(v_u16, np.uint16)
+    dd = _arr(death, np.int32)
+    T, G, D = q.shape
+    out = np.zeros((T, G, D), np.float32)
+    _L().orc_replay_attn(_p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16), _p(dd, C.c_int32), T, G, D,
+                         float(scale), _p(out, C.c_float))
+    return out
 
 
 # ------------------------------------------------- host-integer schedule --
