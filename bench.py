@@ -427,6 +427,48 @@ def main():
         del ws_p, kept_p, sigma_p
         cache.len.copy_(keep)       # back to the schedule's state
 
+    # ---- replay attention (training forward under the replay mask), one layer, paper-like rounds
+    def replay_case(block):
+        Bt, T = 8, 4096
+        rs = np.random.default_rng(w.data_seed + block)
+        death_h = np.full((Bt, T), T, np.int32)
+        for bb in range(Bt):
+            alive = np.zeros(0, np.int64)
+            for bnd in range(w.delta, T, w.delta):
+                alive = np.concatenate([alive, np.arange(bnd - w.delta, bnd)])
+                nb = (alive.size + block - 1) // block
+                keep_b = rs.random(nb) < (w.keep_num / w.keep_den) ** (w.delta / max(1.0, alive.size / 2))
+                keep_t = np.repeat(keep_b, block)[:alive.size]
+                death_h[bb, alive[~keep_t]] = bnd
+                alive = alive[keep_t]
+        qT = torch.randn(Bt, T, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
+        kT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+        vT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+        oT = torch.empty(Bt, T, w.Hq, w.D, dtype=torch.float32, device=dev)
+        dT = torch.from_numpy(death_h).to(dev)
+        wsT = torch.zeros(ngc.ngc_replay_workspace_bytes(Bt, T, w.Hkv), dtype=torch.uint8, device=dev)
+        ms = []
+        for rep in range(4):
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            ngc.ngc_replay_attn(qT, kT, vT, dT, Bt, T, w.Hq, w.Hkv, w.D, False, scale, oT, wsT)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        t_ms = float(np.mean(ms[1:]))
+        ii = np.arange(T)
+        visible = sum(int(((ii[:, None] >= ii[None, :]) & (ii[:, None] < death_h[bb][None, :])).sum()) for bb in range(Bt))
+        flops = 4.0 * w.D * visible * w.Hq
+        causal = 4.0 * w.D * (T * (T + 1) / 2) * w.Hq * Bt
+        return {"block": block, "B": Bt, "T": T, "ms": t_ms, "visible_pairs_frac_of_causal": flops / causal,
+                "algorithmic_tflops": flops / (t_ms * 1e-3) / 1e12,
+                "mfma_frac": flops / (t_ms * 1e-3) / 1e12 / 2500.0,
+                "causal_equivalent_tflops": causal / (t_ms * 1e-3) / 1e12}
+
+    replay = {"what": "ngc_replay_attn, one layer, rounds every delta tokens, random survivors; bound: bf16 MFMA 2.5 PFLOP/s",
+              "per_token_eviction": replay_case(1), "block32_eviction": replay_case(32)}
+
     per_layer = None
     if args.per_layer:
         reps = 20
@@ -485,6 +527,7 @@ def main():
         "scoring": scoring,
         "logprob_backward": bwd,
         "eviction_pooled_heads": pooled,
+        "replay_attn": replay,
         "setup_s": t_setup,
     }
     if per_layer:

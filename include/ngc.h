@@ -14,6 +14,7 @@
  *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
+ *   ngc_replay_attn      training-time attention under the replay mask (Sec. 4.5)
  *   ngc_score_keys       attention-based importance of every cached key, the
  *                        input of the eviction policy                (Sec. 4.2)
  *
@@ -253,6 +254,27 @@ int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
                    const float *lse_recent, int32_t w,
                    float scale, uint32_t flags, int32_t block, float *scores_out,
                    void *ws, size_t ws_bytes, void *stream);
+
+/* Replay attention for the training forward pass (Sec. 4.5, Appendix A.3): one
+ * layer, every position of every trajectory at once, each query seeing exactly
+ * the keys that were in the cache when its token was generated:
+ *     out[b][i][h][:] = sum_j softmax_j( scale * <q[b][i][h], k[b][j][h/G]> ) v[b][j][h/G][:]
+ *     over the j with  j <= i < death[b][.][j],
+ * where death[..][j] is the first query position that no longer sees key j (the
+ * position at which the round that evicted it fired; >= T if it was never
+ * evicted).  This replaces the dense B x T x T boolean mask of the paper by one
+ * int per key.
+ *   q      bf16 [B][T][Hq][D], 16-byte aligned
+ *   k, v   bf16 [B][T][Hkv][D]
+ *   death  int32 [B][Hkv][T] if death_per_head != 0, else [B][T] (one set of
+ *          decisions per layer, shared by its KV heads)
+ *   out    fp32 [B][T][Hq][D]
+ * D is 64 or 128.  ws must hold ngc_replay_workspace_bytes(B, T, Hkv). */
+size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv);
+int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *death,
+                    int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                    int32_t death_per_head, float scale, float *out,
+                    void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

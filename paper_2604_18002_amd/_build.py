@@ -19,6 +19,7 @@ _UNITS = (
     ("ngc_evict.hip", ["-ffp-contract=off"]),
     ("ngc_attn.hip", []),
     ("ngc_score.hip", []),
+    ("ngc_replay.hip", []),
 )
 
 

@@ -35,7 +35,7 @@ SCORE_POOL_HEADS = 2
 
 EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
-           "ngc_subset_logprob_backward")
+           "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes")
 
 
 class NgcError(RuntimeError):
@@ -89,6 +89,10 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_decode_attn.restype = C.c_int
     lib.ngc_subset_logprob_backward.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, sz, vp]
     lib.ngc_subset_logprob_backward.restype = C.c_int
+    lib.ngc_replay_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.ngc_replay_workspace_bytes.restype = sz
+    lib.ngc_replay_attn.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    lib.ngc_replay_attn.restype = C.c_int
     lib.ngc_score_keys.argtypes = [cp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_score_keys.restype = C.c_int
     if path == LIB_PATH:
@@ -223,4 +227,15 @@ def ngc_subset_logprob_backward(logits, n_items, sigma, keep, nseg: int, logit_s
     _check(load_library().ngc_subset_logprob_backward(_ptr(logits), _ptr(n_items), _ptr(sigma), _ptr(keep), nseg,
                                                       logit_stride, sigma_stride, max_keep, _ptr(gout),
                                                       _ptr(grad_out), _ptr(ws), ws.numel(), _stream(stream)),
-           "ngc_subset_logprob_backward")
+           "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes")
+
+
+def ngc_replay_workspace_bytes(B: int, T: int, Hkv: int) -> int:
+    return int(load_library().ngc_replay_workspace_bytes(B, T, Hkv))
+
+
+def ngc_replay_attn(q, k, v, death, B: int, T: int, Hq: int, Hkv: int, D: int, death_per_head: bool,
+                    scale: float, out, ws, stream=None):
+    _check(load_library().ngc_replay_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(death), B, T, Hq, Hkv, D,
+                                          1 if death_per_head else 0, scale, _ptr(out), _ptr(ws), ws.numel(),
+                                          _stream(stream)), "ngc_replay_attn")

@@ -1,0 +1,326 @@
+// Replay attention for the training forward pass (Sec. 4.5 and Appendix A.3 of
+// the paper): all T positions of a trajectory at once, query i seeing key j iff
+// j <= i and j had not been evicted when token i was generated.
+//
+// Instead of the paper's dense T x T boolean mask per layer, visibility is one
+// int per key: death[j] = first query position that no longer sees key j, so
+// visible(i, j) = (j <= i < death[j]).  That also gives whole-tile skipping: a
+// tile of 32 keys whose largest death is not above the first query of a
+// workgroup is never loaded (with block-level eviction, whole tiles die).
+//
+// Flash-attention forward on the matrix cores, same operand scheme as the
+// decode kernel (S^T = K Q^T, O^T = V^T P, query on lane%16, P as bf16 head +
+// remainder).  A workgroup = 4 waves x 32 query positions of one query head;
+// K/V tiles of 32 keys are loaded cooperatively into double-buffered LDS and
+// shared by the 4 waves.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/ngc.h"
+#include "ngc_device.h"
+
+namespace ngc {
+
+constexpr int RP_WAVES = 4;
+constexpr int RP_QW = 32;                    // query positions per wave
+constexpr int RP_QT = RP_WAVES * RP_QW;      // query positions per workgroup
+constexpr int RP_KT = 32;                    // keys per tile
+
+struct ReplayArgs {
+    const unsigned char *q;    // bf16 [B][T][Hq][D]
+    const unsigned char *k;    // bf16 [B][T][Hkv][D]
+    const unsigned char *v;
+    const int32_t *death;      // [B][Hd][T]
+    int32_t *tile_maxdeath;    // [B][Hd][ceil(T/32)]
+    float *out;                // fp32 [B][T][Hq][D]
+    int B, T, Hq, Hkv, Hd;     // Hd = Hkv (a death row per KV head) or 1 (shared by the heads)
+    float scale_log2e;
+};
+
+__global__ __launch_bounds__(256) void replay_tile_maxdeath_kernel(ReplayArgs a)
+{
+    const int row = blockIdx.x;                       // b * Hd + hd
+    const int ntiles = (a.T + RP_KT - 1) / RP_KT;
+    const int32_t *d = a.death + (size_t)row * a.T;
+    for (int t = threadIdx.x; t < ntiles; t += 256) {
+        int m = 0;
+        for (int j = t * RP_KT; j < (t + 1) * RP_KT && j < a.T; ++j) m = d[j] > m ? d[j] : m;
+        a.tile_maxdeath[(size_t)row * ntiles + t] = m;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a)
+{
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int DPL = D / 16;
+    constexpr int KCH = D / 32;
+    constexpr int LROW = ROW_BYTES + 16;
+    constexpr int TILE_LDS = RP_KT * LROW;
+    constexpr int PIECES = ROW_BYTES / 16;                 // 16-byte pieces per row
+    constexpr int LOADS = RP_KT * PIECES / (RP_WAVES * 64); // per thread, per tensor
+
+    __shared__ __align__(16) unsigned char lds_k[2][TILE_LDS];
+    __shared__ __align__(16) unsigned char lds_v[2][TILE_LDS];
+    __shared__ __align__(16) int32_t lds_death[2][RP_KT];
+
+    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const int li = lane & 15, kg = lane >> 4;
+    const int T = a.T;
+    const int nqt = (T + RP_QT - 1) / RP_QT;
+    const int qt = nqt - 1 - blockIdx.x;                   // heaviest query tiles first
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int G = a.Hq / a.Hkv;
+    const int hkv = head / G;
+    const int hd = a.Hd == 1 ? 0 : hkv;
+    const int i0 = qt * RP_QT;
+    const int ntiles = (T + RP_KT - 1) / RP_KT;
+    const int32_t *death = a.death + ((size_t)b * a.Hd + hd) * T;
+    const int32_t *tmax = a.tile_maxdeath + ((size_t)b * a.Hd + hd) * ntiles;
+    const size_t kv_row = (size_t)a.Hkv * ROW_BYTES;       // bytes between consecutive tokens
+    const unsigned char *kbase = a.k + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
+    const unsigned char *vbase = a.v + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
+
+    // ---- query operands: two tiles of 16 positions per wave ------------------
+    int qpos[2];
+    bf16x8 qop[2][KCH];
+#pragma unroll
+    for (int qa = 0; qa < 2; ++qa) {
+        qpos[qa] = i0 + wv * RP_QW + qa * 16 + li;
+        const int p = qpos[qa] < T ? qpos[qa] : T - 1;
+        const unsigned char *qrow = a.q + (((size_t)b * T + p) * a.Hq + head) * ROW_BYTES;
+#pragma unroll
+        for (int c = 0; c < KCH; ++c)
+            qop[qa][c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qrow + c * 64 + kg * 16));
+    }
+
+    f32x4 oacc[2][DPL];
+    float m_run[2], l_run[2];
+#pragma unroll
+    for (int qa = 0; qa < 2; ++qa) {
+        m_run[qa] = -INFINITY;
+        l_run[qa] = 0.f;
+#pragma unroll
+        for (int c = 0; c < DPL; ++c) oacc[qa][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    int vrow_rel[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vrow_rel[e] = (e < 4) ? (4 * kg + e) : (16 + 4 * kg + (e - 4));
+
+    // tiles this workgroup needs: keys not after its last query, not all dead before its first
+    const int last_pos = (i0 + RP_QT - 1 < T - 1) ? i0 + RP_QT - 1 : T - 1;
+    const int t_end = last_pos / RP_KT + 1;
+    auto next_tile = [&](int t) {
+        while (t < t_end && tmax[t] <= i0) ++t;
+        return t;
+    };
+
+    u32x4 kreg[LOADS], vreg[LOADS];
+    int dreg = 0;
+    auto load_tile = [&](int t) {
+        const int j0 = t * RP_KT;
+#pragma unroll
+        for (int r = 0; r < LOADS; ++r) {
+            const int piece_id = r * (RP_WAVES * 64) + tid;
+            int row = j0 + piece_id / PIECES;
+            row = row < T ? row : T - 1;
+            const size_t off = (size_t)row * kv_row + (piece_id % PIECES) * 16;
+            kreg[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
+            vreg[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
+        }
+        if (tid < RP_KT) dreg = (j0 + tid < T) ? death[j0 + tid] : 0;
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < LOADS; ++r) {
+            const int piece_id = r * (RP_WAVES * 64) + tid;
+            const int off = (piece_id / PIECES) * LROW + (piece_id % PIECES) * 16;
+            *reinterpret_cast<u32x4 *>(lds_k[buf] + off) = kreg[r];
+            *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = vreg[r];
+        }
+        if (tid < RP_KT) lds_death[buf][tid] = dreg;
+    };
+
+    int t = next_tile(0);
+    int buf = 0;
+    if (t < t_end) {
+        load_tile(t);
+        store_tile(0);
+    }
+    __syncthreads();
+    while (t < t_end) {
+        const int tn = next_tile(t + 1);
+        if (tn < t_end) load_tile(tn);                    // prefetch into registers
+
+        // ---- this tile, from LDS ---------------------------------------------
+        const int j0 = t * RP_KT;
+        const unsigned char *lk = lds_k[buf], *lv = lds_v[buf];
+        const bool wave_needs = (j0 <= i0 + wv * RP_QW + RP_QW - 1);   // not entirely in this wave's future
+        if (wave_needs) {
+            bf16x8 kop[2][KCH];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int c = 0; c < KCH; ++c)
+                    kop[mt][c] = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const u32x4 *>(lk + (mt * 16 + li) * LROW + c * 64 + kg * 16));
+            int dk[8];
+            {
+                const int4 d0 = *reinterpret_cast<const int4 *>(&lds_death[buf][4 * kg]);
+                const int4 d1 = *reinterpret_cast<const int4 *>(&lds_death[buf][16 + 4 * kg]);
+                dk[0] = d0.x; dk[1] = d0.y; dk[2] = d0.z; dk[3] = d0.w;
+                dk[4] = d1.x; dk[5] = d1.y; dk[6] = d1.z; dk[7] = d1.w;
+            }
+            u32x4 vcur[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if constexpr (DPL == 8) {
+                    vcur[e] = *reinterpret_cast<const u32x4 *>(lv + vrow_rel[e] * LROW + li * 16);
+                } else {
+                    const u32x2 tt = *reinterpret_cast<const u32x2 *>(lv + vrow_rel[e] * LROW + li * 8);
+                    vcur[e] = u32x4{tt[0], tt[1], 0u, 0u};
+                }
+            }
+            bf16x8 p_hi[2], p_lo[2];
+#pragma unroll
+            for (int qa = 0; qa < 2; ++qa) {
+                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) {
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][c], qop[qa][c], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][c], qop[qa][c], s1, 0, 0, 0);
+                }
+                float x[8];
+                const int qp = qpos[qa];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + vrow_rel[e];
+                    const float sc = (e < 4) ? s0[e] : s1[e - 4];
+                    x[e] = (j <= qp && qp < dk[e]) ? sc * a.scale_log2e : -INFINITY;
+                }
+                float tmx = x[0];
+#pragma unroll
+                for (int e = 1; e < 8; ++e) tmx = fmaxf(tmx, x[e]);
+                tmx = fmaxf(tmx, __shfl_xor(tmx, 16, NGC_WAVE));
+                tmx = fmaxf(tmx, __shfl_xor(tmx, 32, NGC_WAVE));
+                const float m_new = fmaxf(m_run[qa], tmx);
+                if (__ballot(m_new != m_run[qa])) {
+                    // m_new is finite wherever it changed; exp2(-inf - finite) = 0 on a first visible tile
+                    const float alpha = (m_new == m_run[qa]) ? 1.0f : fast_exp2(m_run[qa] - m_new);
+                    l_run[qa] *= alpha;
+#pragma unroll
+                    for (int c = 0; c < DPL; ++c) oacc[qa][c] *= alpha;
+                    m_run[qa] = m_new;
+                }
+                float p[8], psum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = (x[e] == -INFINITY) ? 0.f : fast_exp2(x[e] - m_run[qa]);
+                    psum += p[e];
+                }
+                l_run[qa] += psum;
+                uint32_t ph[4], pl[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const uint32_t b0 = __float_as_uint(p[2 * e2]), b1 = __float_as_uint(p[2 * e2 + 1]);
+                    const float r0 = p[2 * e2] - __uint_as_float(b0 & 0xFFFF0000u);
+                    const float r1 = p[2 * e2 + 1] - __uint_as_float(b1 & 0xFFFF0000u);
+                    ph[e2] = (b0 >> 16) | (b1 & 0xFFFF0000u);
+                    pl[e2] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+                }
+                p_hi[qa] = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
+                p_lo[qa] = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
+            }
+#pragma unroll
+            for (int c = 0; c < DPL; ++c) {
+                uint32_t va[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const uint32_t w0 = vcur[2 * e2][c >> 1];
+                    const uint32_t w1 = vcur[2 * e2 + 1][c >> 1];
+                    va[e2] = (c & 1) ? ((w0 >> 16) | (w1 & 0xFFFF0000u)) : ((w0 & 0xFFFFu) | (w1 << 16));
+                }
+                const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{va[0], va[1], va[2], va[3]});
+#pragma unroll
+                for (int qa = 0; qa < 2; ++qa) {
+                    oacc[qa][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi[qa], oacc[qa][c], 0, 0, 0);
+                    oacc[qa][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo[qa], oacc[qa][c], 0, 0, 0);
+                }
+            }
+        }
+        // ---- hand over to the prefetched tile -----------------------------------
+        if (tn < t_end) store_tile(buf ^ 1);              // the other buffer: nobody reads it now
+        __syncthreads();
+        buf ^= 1;
+        t = tn;
+    }
+
+    // ---- normalise and write -------------------------------------------------
+#pragma unroll
+    for (int qa = 0; qa < 2; ++qa) {
+        float l = l_run[qa];
+        l += __shfl_xor(l, 16, NGC_WAVE);
+        l += __shfl_xor(l, 32, NGC_WAVE);
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        if (qpos[qa] < T) {
+            float *orow = a.out + (((size_t)b * T + qpos[qa]) * a.Hq + head) * D;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // lane (q = li, kg), register (c, r) holds d = DPL * (4kg + r) + c
+                float *dst = orow + DPL * (4 * kg + r);
+#pragma unroll
+                for (int c = 0; c < DPL; c += 4)
+                    *reinterpret_cast<float4 *>(dst + c) =
+                        make_float4(oacc[qa][c][r] * inv, oacc[qa][c + 1][r] * inv, oacc[qa][c + 2][r] * inv,
+                                    oacc[qa][c + 3][r] * inv);
+            }
+        }
+    }
+}
+
+}  // namespace ngc
+
+using namespace ngc;
+
+extern "C" size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv)
+{
+    if (B <= 0 || T <= 0 || Hkv <= 0) return 0;
+    return NGC_STATUS_WORDS * sizeof(int32_t) + (size_t)B * Hkv * ((T + RP_KT - 1) / RP_KT) * sizeof(int32_t);
+}
+
+extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *death,
+                               int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                               int32_t death_per_head, float scale, float *out,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    if (!q || !k || !v || !death || !out || !ws) return NGC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ws)) & 15u)
+        return NGC_EINVAL;
+    if (B <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return NGC_EINVAL;
+    if (D != 64 && D != 128) return NGC_EINVAL;
+    if (!(scale == scale)) return NGC_EINVAL;
+    if (B > 65535 || Hq > 65535) return NGC_EUNSUPPORTED;
+    if (ws_bytes < ngc_replay_workspace_bytes(B, T, Hkv)) return NGC_ENOSPC;
+    ReplayArgs ra;
+    ra.q = reinterpret_cast<const unsigned char *>(q);
+    ra.k = reinterpret_cast<const unsigned char *>(k);
+    ra.v = reinterpret_cast<const unsigned char *>(v);
+    ra.death = death;
+    ra.tile_maxdeath = reinterpret_cast<int32_t *>(ws) + NGC_STATUS_WORDS;
+    ra.out = out;
+    ra.B = B; ra.T = T; ra.Hq = Hq; ra.Hkv = Hkv; ra.Hd = death_per_head ? Hkv : 1;
+    ra.scale_log2e = scale * 1.4426950408889634f;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(replay_tile_maxdeath_kernel, dim3(B * ra.Hd), dim3(256), 0, st, ra);
+    NGC_HIP_CHECK(hipGetLastError());
+    const int nqt = (T + RP_QT - 1) / RP_QT;
+    if (D == 128)
+        hipLaunchKernelGGL(replay_attn_kernel<128>, dim3(nqt, Hq, B), dim3(RP_WAVES * 64), 0, st, ra);
+    else
+        hipLaunchKernelGGL(replay_attn_kernel<64>, dim3(nqt, Hq, B), dim3(RP_WAVES * 64), 0, st, ra);
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
