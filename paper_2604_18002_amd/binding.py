@@ -227,7 +227,7 @@ def ngc_subset_logprob_backward(logits, n_items, sigma, keep, nseg: int, logit_s
     _check(load_library().ngc_subset_logprob_backward(_ptr(logits), _ptr(n_items), _ptr(sigma), _ptr(keep), nseg,
                                                       logit_stride, sigma_stride, max_keep, _ptr(gout),
                                                       _ptr(grad_out), _ptr(ws), ws.numel(), _stream(stream)),
-           "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes")
+           "ngc_subset_logprob_backward")
 
 
 def ngc_replay_workspace_bytes(B: int, T: int, Hkv: int) -> int:

@@ -4,9 +4,12 @@
 //
 // Instead of the paper's dense T x T boolean mask per layer, visibility is one
 // int per key: death[j] = first query position that no longer sees key j, so
-// visible(i, j) = (j <= i < death[j]).  That also gives whole-tile skipping: a
-// tile of 32 keys whose largest death is not above the first query of a
-// workgroup is never loaded (with block-level eviction, whole tiles die).
+// visible(i, j) = (j <= i < death[j]).  A small first kernel compacts, for every
+// tile of 128 query positions, the list of keys that at least one of its
+// queries can see (j not after its last query, death[j] after its first); the
+// attention kernel then only ever loads those rows: the work follows the
+// retained cache, not the T x T triangle.  The lists are shared by all query
+// heads that share the decisions.
 //
 // Flash-attention forward on the matrix cores, same operand scheme as the
 // decode kernel (S^T = K Q^T, O^T = V^T P, query on lane%16, P as bf16 head +
@@ -32,26 +35,49 @@ struct ReplayArgs {
     const unsigned char *k;    // bf16 [B][T][Hkv][D]
     const unsigned char *v;
     const int32_t *death;      // [B][Hd][T]
-    int32_t *tile_maxdeath;    // [B][Hd][ceil(T/32)]
+    uint16_t *klist;           // [B*Hd][nqt][T] visible keys per query tile, ascending
+    int32_t *kcount;           // [B*Hd][nqt]
     float *out;                // fp32 [B][T][Hq][D]
     int B, T, Hq, Hkv, Hd;     // Hd = Hkv (a death row per KV head) or 1 (shared by the heads)
     float scale_log2e;
 };
 
-__global__ __launch_bounds__(256) void replay_tile_maxdeath_kernel(ReplayArgs a)
+// Ordered compaction (ballot + prefix over the 4 waves), 256 keys per step.
+__global__ __launch_bounds__(RP_WAVES * 64) void replay_lists_kernel(ReplayArgs a)
 {
-    const int row = blockIdx.x;                       // b * Hd + hd
-    const int ntiles = (a.T + RP_KT - 1) / RP_KT;
-    const int32_t *d = a.death + (size_t)row * a.T;
-    for (int t = threadIdx.x; t < ntiles; t += 256) {
-        int m = 0;
-        for (int j = t * RP_KT; j < (t + 1) * RP_KT && j < a.T; ++j) m = d[j] > m ? d[j] : m;
-        a.tile_maxdeath[(size_t)row * ntiles + t] = m;
+    __shared__ int wave_cnt[RP_WAVES];
+    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const int T = a.T;
+    const int nqt = (T + RP_QT - 1) / RP_QT;
+    const int qt = blockIdx.x, row = blockIdx.y;          // row = b * Hd + hd
+    const int i0 = qt * RP_QT;
+    const int last_pos = (i0 + RP_QT - 1 < T - 1) ? i0 + RP_QT - 1 : T - 1;
+    const int32_t *death = a.death + (size_t)row * T;
+    uint16_t *klist = a.klist + ((size_t)row * nqt + qt) * T;
+    int n_list = 0;
+    for (int j0 = 0; j0 <= last_pos; j0 += RP_WAVES * 64) {
+        const int j = j0 + tid;
+        const bool pred = j <= last_pos && death[j] > i0;
+        const uint64_t bal = __ballot(pred);
+        if (lane == 0) wave_cnt[wv] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int x = 0; x < RP_WAVES; ++x) {
+            const int c = wave_cnt[x];
+            if (x < wv) before += c;
+            total += c;
+        }
+        if (pred) klist[n_list + before + popc_below(bal)] = (uint16_t)j;
+        n_list += total;
+        __syncthreads();
     }
+    if (tid == 0) a.kcount[(size_t)row * nqt + qt] = n_list;
 }
 
 template <int D>
-__global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a)
+__global__ __launch_bounds__(RP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void replay_attn_kernel(ReplayArgs a)
 {
     constexpr int ROW_BYTES = D * 2;
     constexpr int DPL = D / 16;
@@ -64,6 +90,7 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
     __shared__ __align__(16) unsigned char lds_k[2][TILE_LDS];
     __shared__ __align__(16) unsigned char lds_v[2][TILE_LDS];
     __shared__ __align__(16) int32_t lds_death[2][RP_KT];
+    __shared__ __align__(16) int32_t lds_kidx[2][RP_KT];
 
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const int li = lane & 15, kg = lane >> 4;
@@ -75,9 +102,7 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
     const int hkv = head / G;
     const int hd = a.Hd == 1 ? 0 : hkv;
     const int i0 = qt * RP_QT;
-    const int ntiles = (T + RP_KT - 1) / RP_KT;
     const int32_t *death = a.death + ((size_t)b * a.Hd + hd) * T;
-    const int32_t *tmax = a.tile_maxdeath + ((size_t)b * a.Hd + hd) * ntiles;
     const size_t kv_row = (size_t)a.Hkv * ROW_BYTES;       // bytes between consecutive tokens
     const unsigned char *kbase = a.k + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
     const unsigned char *vbase = a.v + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
@@ -109,28 +134,30 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
 #pragma unroll
     for (int e = 0; e < 8; ++e) vrow_rel[e] = (e < 4) ? (4 * kg + e) : (16 + 4 * kg + (e - 4));
 
-    // tiles this workgroup needs: keys not after its last query, not all dead before its first
-    const int last_pos = (i0 + RP_QT - 1 < T - 1) ? i0 + RP_QT - 1 : T - 1;
-    const int t_end = last_pos / RP_KT + 1;
-    auto next_tile = [&](int t) {
-        while (t < t_end && tmax[t] <= i0) ++t;
-        return t;
-    };
+    // keys this workgroup needs (list built by replay_lists_kernel)
+    const uint16_t *klist = a.klist + (((size_t)b * a.Hd + hd) * nqt + qt) * T;
+    const int n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
+    const int t_end = (n_list + RP_KT - 1) / RP_KT;
+    auto next_tile = [&](int t) { return t; };
 
     u32x4 kreg[LOADS], vreg[LOADS];
-    int dreg = 0;
+    int dreg = 0, ireg = 0;
     auto load_tile = [&](int t) {
-        const int j0 = t * RP_KT;
+        const int s0 = t * RP_KT;
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
-            int row = j0 + piece_id / PIECES;
-            row = row < T ? row : T - 1;
-            const size_t off = (size_t)row * kv_row + (piece_id % PIECES) * 16;
+            int slot = s0 + piece_id / PIECES;
+            slot = slot < n_list ? slot : n_list - 1;
+            const size_t off = (size_t)klist[slot] * kv_row + (piece_id % PIECES) * 16;
             kreg[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
             vreg[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
         }
-        if (tid < RP_KT) dreg = (j0 + tid < T) ? death[j0 + tid] : 0;
+        if (tid < RP_KT) {
+            const bool ok = s0 + tid < n_list;
+            ireg = ok ? (int)klist[s0 + tid] : 0x7FFFFFFF;   // a key no query comes after
+            dreg = ok ? death[ireg] : 0;
+        }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
@@ -140,7 +167,7 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
             *reinterpret_cast<u32x4 *>(lds_k[buf] + off) = kreg[r];
             *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = vreg[r];
         }
-        if (tid < RP_KT) lds_death[buf][tid] = dreg;
+        if (tid < RP_KT) { lds_death[buf][tid] = dreg; lds_kidx[buf][tid] = ireg; }
     };
 
     int t = next_tile(0);
@@ -155,9 +182,9 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
         if (tn < t_end) load_tile(tn);                    // prefetch into registers
 
         // ---- this tile, from LDS ---------------------------------------------
-        const int j0 = t * RP_KT;
         const unsigned char *lk = lds_k[buf], *lv = lds_v[buf];
-        const bool wave_needs = (j0 <= i0 + wv * RP_QW + RP_QW - 1);   // not entirely in this wave's future
+        // the list ascends: if its first key of this tile is after this wave's last query, so are all
+        const bool wave_needs = (lds_kidx[buf][0] <= i0 + wv * RP_QW + RP_QW - 1);
         if (wave_needs) {
             bf16x8 kop[2][KCH];
 #pragma unroll
@@ -166,22 +193,16 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
                 for (int c = 0; c < KCH; ++c)
                     kop[mt][c] = __builtin_bit_cast(
                         bf16x8, *reinterpret_cast<const u32x4 *>(lk + (mt * 16 + li) * LROW + c * 64 + kg * 16));
-            int dk[8];
+            int dk[8], jk[8];
             {
                 const int4 d0 = *reinterpret_cast<const int4 *>(&lds_death[buf][4 * kg]);
                 const int4 d1 = *reinterpret_cast<const int4 *>(&lds_death[buf][16 + 4 * kg]);
                 dk[0] = d0.x; dk[1] = d0.y; dk[2] = d0.z; dk[3] = d0.w;
                 dk[4] = d1.x; dk[5] = d1.y; dk[6] = d1.z; dk[7] = d1.w;
-            }
-            u32x4 vcur[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if constexpr (DPL == 8) {
-                    vcur[e] = *reinterpret_cast<const u32x4 *>(lv + vrow_rel[e] * LROW + li * 16);
-                } else {
-                    const u32x2 tt = *reinterpret_cast<const u32x2 *>(lv + vrow_rel[e] * LROW + li * 8);
-                    vcur[e] = u32x4{tt[0], tt[1], 0u, 0u};
-                }
+                const int4 j0v = *reinterpret_cast<const int4 *>(&lds_kidx[buf][4 * kg]);
+                const int4 j1v = *reinterpret_cast<const int4 *>(&lds_kidx[buf][16 + 4 * kg]);
+                jk[0] = j0v.x; jk[1] = j0v.y; jk[2] = j0v.z; jk[3] = j0v.w;
+                jk[4] = j1v.x; jk[5] = j1v.y; jk[6] = j1v.z; jk[7] = j1v.w;
             }
             bf16x8 p_hi[2], p_lo[2];
 #pragma unroll
@@ -196,9 +217,8 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
                 const int qp = qpos[qa];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const int j = j0 + vrow_rel[e];
                     const float sc = (e < 4) ? s0[e] : s1[e - 4];
-                    x[e] = (j <= qp && qp < dk[e]) ? sc * a.scale_log2e : -INFINITY;
+                    x[e] = (jk[e] <= qp && qp < dk[e]) ? sc * a.scale_log2e : -INFINITY;
                 }
                 float tmx = x[0];
 #pragma unroll
@@ -232,6 +252,18 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_attn_kernel(ReplayArgs a
                 }
                 p_hi[qa] = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
                 p_lo[qa] = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
+            }
+            // V only now: its registers must not be live together with the K operands
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 vcur[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if constexpr (DPL == 8) {
+                    vcur[e] = *reinterpret_cast<const u32x4 *>(lv + vrow_rel[e] * LROW + li * 16);
+                } else {
+                    const u32x2 tt = *reinterpret_cast<const u32x2 *>(lv + vrow_rel[e] * LROW + li * 8);
+                    vcur[e] = u32x4{tt[0], tt[1], 0u, 0u};
+                }
             }
 #pragma unroll
             for (int c = 0; c < DPL; ++c) {
@@ -287,7 +319,10 @@ using namespace ngc;
 extern "C" size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv)
 {
     if (B <= 0 || T <= 0 || Hkv <= 0) return 0;
-    return NGC_STATUS_WORDS * sizeof(int32_t) + (size_t)B * Hkv * ((T + RP_KT - 1) / RP_KT) * sizeof(int32_t);
+    const size_t nqt = (size_t)(T + RP_QT - 1) / RP_QT;
+    size_t lists = (size_t)B * Hkv * nqt * T * sizeof(uint16_t);
+    lists = (lists + 255) & ~(size_t)255;
+    return 256 + lists + (size_t)B * Hkv * nqt * sizeof(int32_t);
 }
 
 extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *death,
@@ -303,20 +338,24 @@ extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, cons
     if (D != 64 && D != 128) return NGC_EINVAL;
     if (!(scale == scale)) return NGC_EINVAL;
     if (B > 65535 || Hq > 65535) return NGC_EUNSUPPORTED;
+    if (T > 65535) return NGC_EUNSUPPORTED;   // 16-bit key lists
     if (ws_bytes < ngc_replay_workspace_bytes(B, T, Hkv)) return NGC_ENOSPC;
     ReplayArgs ra;
     ra.q = reinterpret_cast<const unsigned char *>(q);
     ra.k = reinterpret_cast<const unsigned char *>(k);
     ra.v = reinterpret_cast<const unsigned char *>(v);
     ra.death = death;
-    ra.tile_maxdeath = reinterpret_cast<int32_t *>(ws) + NGC_STATUS_WORDS;
     ra.out = out;
     ra.B = B; ra.T = T; ra.Hq = Hq; ra.Hkv = Hkv; ra.Hd = death_per_head ? Hkv : 1;
     ra.scale_log2e = scale * 1.4426950408889634f;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(replay_tile_maxdeath_kernel, dim3(B * ra.Hd), dim3(256), 0, st, ra);
-    NGC_HIP_CHECK(hipGetLastError());
     const int nqt = (T + RP_QT - 1) / RP_QT;
+    size_t lists = (size_t)B * ra.Hd * nqt * T * sizeof(uint16_t);
+    lists = (lists + 255) & ~(size_t)255;
+    ra.klist = reinterpret_cast<uint16_t *>(reinterpret_cast<unsigned char *>(ws) + 256);
+    ra.kcount = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) + 256 + lists);
+    hipLaunchKernelGGL(replay_lists_kernel, dim3(nqt, B * ra.Hd), dim3(RP_WAVES * 64), 0, st, ra);
+    NGC_HIP_CHECK(hipGetLastError());
     if (D == 128)
         hipLaunchKernelGGL(replay_attn_kernel<128>, dim3(nqt, Hq, B), dim3(RP_WAVES * 64), 0, st, ra);
     else
