@@ -461,10 +461,21 @@ def main():
         visible = sum(int(((ii[:, None] >= ii[None, :]) & (ii[:, None] < death_h[bb][None, :])).sum()) for bb in range(Bt))
         flops = 4.0 * w.D * visible * w.Hq
         causal = 4.0 * w.D * (T * (T + 1) / 2) * w.Hq * Bt
+        # what the kernel issues: per tile of 128 queries, the keys visible to any of them, rounded up to 32,
+        # times 128 query rows, times 6 D flops per pair (QK, PV with P in two bf16 parts)
+        issued_pairs = 0
+        for bb in range(Bt):
+            for i0 in range(0, T, 128):
+                last = min(i0 + 127, T - 1)
+                n_list = int((death_h[bb][:last + 1] > i0).sum())
+                issued_pairs += ((n_list + 31) // 32) * 32 * 128
+        issued = 6.0 * w.D * issued_pairs * w.Hq
         return {"block": block, "B": Bt, "T": T, "ms": t_ms, "visible_pairs_frac_of_causal": flops / causal,
                 "algorithmic_tflops": flops / (t_ms * 1e-3) / 1e12,
                 "mfma_frac": flops / (t_ms * 1e-3) / 1e12 / 2500.0,
-                "causal_equivalent_tflops": causal / (t_ms * 1e-3) / 1e12}
+                "causal_equivalent_tflops": causal / (t_ms * 1e-3) / 1e12,
+                "issued_mfma_tflops": issued / (t_ms * 1e-3) / 1e12,
+                "issued_mfma_frac": issued / (t_ms * 1e-3) / 1e12 / 2500.0}
 
     replay = {"what": "ngc_replay_attn, one layer, rounds every delta tokens, random survivors; bound: bf16 MFMA 2.5 PFLOP/s",
               "per_token_eviction": replay_case(1), "block32_eviction": replay_case(32)}
@@ -483,6 +494,32 @@ def main():
         ms = e0.elapsed_time(e1) / reps
         per_layer = {"ms_per_token_step": ms, "tokens_per_s": w.B / (ms * 1e-3),
                      "hbm_frac": attn_bytes(w, rows_after, nseg) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        # the same L launches captured once in a HIP graph and replayed (no per-launch host work)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for l in range(w.L):
+                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        eager = out.clone()
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph):
+            for l in range(w.L):
+                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+        out.zero_()
+        gph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "graph replay differs from the eager launches"
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            gph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        gms = e0.elapsed_time(e1) / reps
+        per_layer["hip_graph_ms_per_token_step"] = gms
+        per_layer["hip_graph_hbm_frac"] = attn_bytes(w, rows_after, nseg) / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     line = {
         "metric": METRIC,

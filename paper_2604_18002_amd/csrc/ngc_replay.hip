@@ -138,49 +138,42 @@ void replay_attn_kernel(ReplayArgs a)
     const uint16_t *klist = a.klist + (((size_t)b * a.Hd + hd) * nqt + qt) * T;
     const int n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
     const int t_end = (n_list + RP_KT - 1) / RP_KT;
-    auto next_tile = [&](int t) { return t; };
 
-    u32x4 kreg[LOADS], vreg[LOADS];
-    int dreg = 0, ireg = 0;
-    auto load_tile = [&](int t) {
-        const int s0 = t * RP_KT;
+    // one tile in registers on its way from global memory to LDS
+    struct Stage {
+        u32x4 k[LOADS], v[LOADS];
+        int d, i;
+    };
+    auto load_tile = [&](int t, Stage &st) {
+        const int s0 = t * RP_KT;           // past the end every slot clamps to the last key: harmless re-reads
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
             int slot = s0 + piece_id / PIECES;
             slot = slot < n_list ? slot : n_list - 1;
             const size_t off = (size_t)klist[slot] * kv_row + (piece_id % PIECES) * 16;
-            kreg[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
-            vreg[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
+            st.k[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
+            st.v[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
         }
-        if (tid < RP_KT) {
-            const bool ok = s0 + tid < n_list;
-            ireg = ok ? (int)klist[s0 + tid] : 0x7FFFFFFF;   // a key no query comes after
-            dreg = ok ? death[ireg] : 0;
+        st.d = 0;
+        st.i = 0x7FFFFFFF;                  // a key no query comes after
+        if (tid < RP_KT && s0 + tid < n_list) {
+            st.i = (int)klist[s0 + tid];
+            st.d = death[st.i];
         }
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](int buf, const Stage &st) {
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
             const int off = (piece_id / PIECES) * LROW + (piece_id % PIECES) * 16;
-            *reinterpret_cast<u32x4 *>(lds_k[buf] + off) = kreg[r];
-            *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = vreg[r];
+            *reinterpret_cast<u32x4 *>(lds_k[buf] + off) = st.k[r];
+            *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = st.v[r];
         }
-        if (tid < RP_KT) { lds_death[buf][tid] = dreg; lds_kidx[buf][tid] = ireg; }
+        if (tid < RP_KT) { lds_death[buf][tid] = st.d; lds_kidx[buf][tid] = st.i; }
     };
 
-    int t = next_tile(0);
-    int buf = 0;
-    if (t < t_end) {
-        load_tile(t);
-        store_tile(0);
-    }
-    __syncthreads();
-    while (t < t_end) {
-        const int tn = next_tile(t + 1);
-        if (tn < t_end) load_tile(tn);                    // prefetch into registers
-
+    auto compute_tile = [&](int buf) {
         // ---- this tile, from LDS ---------------------------------------------
         const unsigned char *lk = lds_k[buf], *lv = lds_v[buf];
         // the list ascends: if its first key of this tile is after this wave's last query, so are all
@@ -282,11 +275,35 @@ void replay_attn_kernel(ReplayArgs a)
                 }
             }
         }
-        // ---- hand over to the prefetched tile -----------------------------------
-        if (tn < t_end) store_tile(buf ^ 1);              // the other buffer: nobody reads it now
+    };
+
+    // Three tiles are in play: tile t is computed from LDS, tile t+1 sits in registers (loaded one
+    // step ago, stored to the other LDS buffer after the math), tile t+2 is being loaded.  Unrolled by
+    // two so that the two register stages swap roles without copies; every load is unconditional so the
+    // number of loads in flight is the same on every path.
+    Stage st_a, st_b;
+    load_tile(0, st_a);
+    store_tile(0, st_a);
+    load_tile(1, st_a);
+    __syncthreads();
+    int t = 0, buf = 0;
+    while (t < t_end) {
+        load_tile(t + 2, st_b);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_tile(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        store_tile(buf ^ 1, st_a);
         __syncthreads();
         buf ^= 1;
-        t = tn;
+        if (++t >= t_end) break;
+        load_tile(t + 2, st_a);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_tile(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        store_tile(buf ^ 1, st_b);
+        __syncthreads();
+        buf ^= 1;
+        ++t;
     }
 
     // ---- normalise and write -------------------------------------------------
