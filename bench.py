@@ -44,7 +44,7 @@ MEASURED_TRAFFIC = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default 3: 7B-shaped)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")

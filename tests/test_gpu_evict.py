@@ -541,3 +541,38 @@ def test_pooled_heads_eviction(idx, over, sel_only):
                 assert hv[l, b, h, :Kh].tobytes() == orc.compact_rows(case.v[(l, b, h)], okept[h]).tobytes()
                 assert hpos[l, b, h, :Kh].tolist() == okept[h].tolist()
     assert len(shares) > 1          # the heads really keep different numbers of rows
+
+
+# ------------------------------------------------------- odd geometries ----
+
+@pytest.mark.parametrize("idx,over,kw", [
+    (0, dict(B=2, n_lo=9000, n_hi=10001), {}),                     # D = 64 rows with the 1024-thread kernel, odd capacity
+    (1, dict(B=3, n_lo=700, n_hi=1001), {}),                       # capacity not a multiple of 4
+    (1, dict(B=2, Hq=2, Hkv=2, n_lo=2049, n_hi=2500), {}),         # just above the 256-thread limit, G = 1
+    (3, dict(L=1, B=2, n_lo=8190, n_hi=8193), dict(tau=0.5)),      # straddles the 512/1024-thread switch
+])
+def test_odd_geometries(idx, over, kw):
+    case = host_case(synth.workload(idx, **over))
+    tau = kw.get("tau", 1.0)
+    cache, kept, sigma, logp, ws = _run_evict(case, tau=tau, rnd=1)
+    _check_against_oracle(case, cache, kept, sigma, logp, tau, 1)
+    assert all(x == 0 for x in _ngc().read_status(ws))
+
+
+def test_max_keep_larger_than_capacity_and_tiny_segments():
+    import torch
+    ngc = _ngc()
+    w = synth.workload(0, B=4, n_lo=1, n_hi=5, fixed_keep=None)
+    case = host_case(w)
+    case.keep[:] = np.minimum(case.keep, 3)
+    cache, logits, keep = upload(case)
+    max_keep = 64                                                    # far more room than any segment needs
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.zeros(w.L, w.B, w.Hkv, dtype=torch.float32, device="cuda")
+    print("[evict] tiny segments, roomy lists", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, ngc.make_params(seed=w.gumbel_seed), max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
+    assert all(x == 0 for x in ngc.read_status(ws))
