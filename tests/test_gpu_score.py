@@ -183,3 +183,71 @@ def test_decode_lse_and_single_pass_scoring():
     with pytest.raises(ngc.NgcError):
         ngc.ngc_score_keys(cache, -1, to_bf16_tensor(q_recent, "cuda"), w_, scale, ngc.SCORE_NO_CAUSAL, 1, s_one, ws,
                            lse_recent=lse_recent)
+
+
+def test_paper_granularity_one_decision_per_layer():
+    """Scores pooled over heads and blocks of 32 -> eviction with blocks of 32 and one noise draw per
+    (layer, sequence): every KV head of a layer keeps exactly the same blocks (Sec. 4.2, 4.4).
+    The kernel's scores are checked against the oracle's within tolerance; the selection is checked
+    bit for bit on the oracle's own scores (so no oracle input comes from the GPU)."""
+    import torch
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=3, n_lo=900, n_hi=2048)
+    case = host_case(wl)
+    block, w_ = 32, 5
+    q = np.stack([_recent_queries(w_, wl, l) for l in range(wl.L)])
+    items = (case.lens + block - 1) // block
+    keep_items = np.maximum(1, (items + 1) // 2).astype(np.int32)                       # keep half of the blocks
+    max_keep = int(keep_items.max())
+    scale = 1.0 / np.sqrt(wl.D)
+    # oracle scores: per head psi -> block means -> mean over heads, rounded to fp32 once
+    oscores = np.zeros((wl.L, wl.B, wl.Hkv, wl.cap), np.float32)
+    for l in range(wl.L):
+        for b in range(wl.B):
+            per_head = [orc.block_means(orc.score_keys(q[l, b, :, h * wl.G:(h + 1) * wl.G], case.k[(l, b, h)], scale, True),
+                                        block) for h in range(wl.Hkv)]
+            oscores[l, b, :, :per_head[0].size] = np.mean(per_head, axis=0).astype(np.float32)
+
+    def run(score_source):
+        cache, _, _ = upload(case, with_pos=True)
+        keep = torch.from_numpy(np.broadcast_to(keep_items[None, :, None], (wl.L, wl.B, wl.Hkv)).copy()).cuda()
+        ws = ngc.allocate_workspace(cache, max_keep)
+        kept = torch.full((wl.L, wl.B, wl.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+        sigma = torch.full_like(kept, -1)
+        logp = torch.zeros(wl.L, wl.B, wl.Hkv, dtype=torch.float32, device="cuda")
+        if score_source is None:
+            scores = torch.zeros(wl.L, wl.B, wl.Hkv, wl.cap, dtype=torch.float32, device="cuda")
+            ngc.ngc_score_keys(cache, -1, to_bf16_tensor(q, "cuda"), w_, scale, ngc.SCORE_POOL_HEADS, block, scores, ws)
+        else:
+            scores = torch.from_numpy(score_source).cuda()
+        p = ngc.make_params(block=block, share_heads=1, noise_scale=1.0, round=0, seed=wl.gumbel_seed)
+        ngc.ngc_evict(cache, -1, scores, keep, p, max_keep, kept, sigma, logp, ws)
+        torch.cuda.synchronize()
+        assert all(x == 0 for x in ngc.read_status(ws))
+        return (scores.cpu().numpy(), kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy(),
+                cache.len.cpu().numpy(), cache.pos.cpu().numpy())
+
+    print("[paper granularity] score(pool, block 32) -> evict(block 32, shared noise)", flush=True)
+    gs, hk, hs, hl, hlen, hpos = run(None)
+    for l in range(wl.L):
+        for b in range(wl.B):
+            n_items, K = int(items[b]), int(keep_items[b])
+            want = oscores[l, b, 0, :n_items]
+            for h in range(wl.Hkv):
+                assert np.all(np.abs(gs[l, b, h, :n_items] - want) <= RTOL * np.abs(want) + ATOL)
+            for h in range(1, wl.Hkv):                     # one decision per layer
+                assert hk[l, b, h, :K].tolist() == hk[l, b, 0, :K].tolist()
+                assert hs[l, b, h, :K].tolist() == hs[l, b, 0, :K].tolist()
+                assert hl[l, b, h] == hl[l, b, 0] and hlen[l, b, h] == hlen[l, b, 0]
+    print("[paper granularity] evict on the oracle's scores", flush=True)
+    _, hk, hs, hl, hlen, hpos = run(oscores)
+    for l in range(wl.L):
+        for b in range(wl.B):
+            n_items, K, n = int(items[b]), int(keep_items[b]), int(case.lens[b])
+            okept, osig = orc.evict_select(oscores[l, b, 0, :n_items], K, 1.0, wl.gumbel_seed, 0, l, b, 0xFFFF)
+            want_pos = orc.compact_i32(np.arange(n, dtype=np.int32), okept, block)
+            for h in range(wl.Hkv):
+                assert hk[l, b, h, :K].tolist() == okept.tolist()
+                assert hs[l, b, h, :K].tolist() == osig.tolist()
+                assert hpos[l, b, h, :want_pos.size].tolist() == want_pos.tolist()
+                assert hlen[l, b, h] == want_pos.size
