@@ -5,3 +5,4 @@ and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
 imports it and it never imports the product package.
 """
 from .ngc_oracle import *  # noqa: F401,F403
+from .paged import PagedCache  # noqa: F401
