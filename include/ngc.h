@@ -17,6 +17,9 @@
  *   ngc_replay_attn      training-time attention under the replay mask (Sec. 4.5)
  *   ngc_score_keys       attention-based importance of every cached key, the
  *                        input of the eviction policy                (Sec. 4.2)
+ *   ngc_paged_*          the same path over a paged cache, where the blocks of
+ *                        Sec. 4.2 are pages and eviction edits a page table
+ *                        instead of moving rows
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless a comment says "host".  The
@@ -62,6 +65,8 @@ extern "C" {
 #define NGC_STATUS_EMPTY_ATTN    2  /* decode attention over an empty segment: zeros        */
 #define NGC_STATUS_APPEND_FULL   3  /* append to a full segment: skipped                    */
 #define NGC_STATUS_BAD_SIGMA     4  /* ngc_subset_logprob: index out of range or repeated   */
+#define NGC_STATUS_POOL_BOUNDS   5  /* paged cache: free stack would overflow, or a page id
+                                       in a table is outside the pool: ignored              */
 
 /* Non-owning view of a KV cache in device memory.
  *   k, v : bf16, dense [L][B][Hkv][cap][D], 16-byte aligned.  Rows [0, len) of
@@ -275,6 +280,87 @@ int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *
                     int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,
                     int32_t death_per_head, float scale, float *out,
                     void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Paged layout.  Sec. 4.2 evicts whole blocks of consecutive tokens and notes
+ * that such blocks suit paged caches; here a block IS a page: eviction permutes
+ * a segment's page table and hands the evicted pages back to a pool shared by
+ * all segments, and no K/V row moves.
+ *
+ *   k_pool, v_pool  bf16 [num_pages][page_rows][D], 16-byte aligned
+ *   pos_pool        optional int32 [num_pages][page_rows], or NULL
+ *   table           int32 [L][B][Hkv][max_pages]: physical page of every logical
+ *                   page of a segment.  Entries [0, ceil(len / page_rows)) are in
+ *                   use; row r of a segment is row r % page_rows of page
+ *                   table[r / page_rows].  Other entries are unspecified.
+ *   len             int32 [L][B][Hkv] rows in use; only the last page in use
+ *                   may be partly filled.
+ *   free_stack      int32 [num_pages]: entries [0, *free_count) are the pages no
+ *                   segment owns.  The caller initialises it (all pages, in any
+ *                   order) together with free_count.
+ *   page_rows       power of two, >= 32.  max_pages <= 16384.
+ * Every page id is in exactly one place: one table (among the entries in use)
+ * or the free stack.  The order of pool operations is fixed, so that the same
+ * calls always produce the same tables:
+ *   release (ngc_paged_evict)  segments in ascending id, the evicted pages of a
+ *           segment in ascending logical index, each pushed on top of the stack;
+ *   grant   (ngc_paged_append) the segments that need a page, in ascending id,
+ *           take pages from the top of the stack downwards.                    */
+typedef struct ngc_paged_cache {
+    void    *k_pool;
+    void    *v_pool;
+    int32_t *pos_pool;
+    int32_t *table;
+    int32_t *len;
+    int32_t *free_stack;
+    int32_t *free_count;
+    int32_t  L, B, Hkv, Hq, D, page_rows, max_pages, num_pages;
+} ngc_paged_cache;
+
+/* Bytes of workspace that make every ngc_paged_* call succeed. */
+size_t ngc_paged_workspace_bytes(const ngc_paged_cache *pc);
+
+/* One eviction round over pages (Sec. 4.1-4.3 with block = page_rows): the
+ * items of a segment are its ceil(len / page_rows) logical pages.  Sampling,
+ * kept_out, sigma_out, logp_out, keep, max_keep and the clamping rules are those
+ * of ngc_evict (p->block must equal page_rows; of p->flags only
+ * NGC_EVICT_SELECT_ONLY is allowed).
+ *   logits        fp32, item j of segment s at logits[s * logit_stride + j]
+ *                 (logit_stride >= max_pages; ngc_paged_score_keys writes with
+ *                 stride max_pages * page_rows)
+ * Unless NGC_EVICT_SELECT_ONLY: the table of every segment becomes
+ *     [ old[kept_0], .., old[kept_{K-1}], evicted entries ascending, rest as before ],
+ * len becomes page_rows * (K - 1) + rows of the last kept page (short only when
+ * that is the segment's last page), and the evicted pages are released (order
+ * above).  No K/V byte is read or written. */
+int ngc_paged_evict(const ngc_paged_cache *pc, int32_t layer, const float *logits,
+                    int64_t logit_stride, const int32_t *keep, const ngc_evict_params *p,
+                    int32_t max_keep, int32_t *kept_out, int32_t *sigma_out, float *logp_out,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* Append one row per (sequence, head) of `layer` (-1 = all layers), arguments as
+ * in ngc_cache_append.  A segment whose len is a multiple of page_rows first
+ * gets a page (order above; table entry -1 when the pool is empty).  A segment
+ * at capacity (max_pages * page_rows rows) or without a page is skipped and
+ * counted in NGC_STATUS_APPEND_FULL. */
+int ngc_paged_append(const ngc_paged_cache *pc, int32_t layer, const void *k_new,
+                     const void *v_new, const int32_t *new_pos,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ngc_decode_attn over the paged layout: same arguments, same result as for a
+ * contiguous cache holding the same logical rows. */
+int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
+                          int32_t max_len_hint, float *out, float *lse_out,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* ngc_score_keys over the paged layout.  scores_out: fp32
+ * [L][B][Hkv][max_pages * page_rows]; with block == page_rows entry j of a
+ * segment is the score of its logical page j (pass logit_stride = max_pages *
+ * page_rows to ngc_paged_evict); block == 1 gives one score per row. */
+int ngc_paged_score_keys(const ngc_paged_cache *pc, int32_t layer, const void *q_recent,
+                         const float *lse_recent, int32_t w,
+                         float scale, uint32_t flags, int32_t block, float *scores_out,
+                         void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -13,10 +13,11 @@ _COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
            # packed fp32 instructions stay off on the test machines
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-# (source, extra flags).  The eviction unit holds the exactly specified noise
+# (source, extra flags).  The eviction units hold the exactly specified noise
 # arithmetic: no contraction there.
 _UNITS = (
     ("ngc_evict.hip", ["-ffp-contract=off"]),
+    ("ngc_paged.hip", ["-ffp-contract=off"]),
     ("ngc_attn.hip", []),
     ("ngc_score.hip", []),
     ("ngc_replay.hip", []),

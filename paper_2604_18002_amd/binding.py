@@ -26,6 +26,7 @@ STATUS_LEN_CLAMPED = 1
 STATUS_EMPTY_ATTN = 2
 STATUS_APPEND_FULL = 3
 STATUS_BAD_SIGMA = 4
+STATUS_POOL_BOUNDS = 5
 
 EVICT_SELECT_ONLY = 1
 EVICT_UNORDERED = 2
@@ -35,7 +36,9 @@ SCORE_POOL_HEADS = 2
 
 EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_keys", "ngc_evict",
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
-           "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes")
+           "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
+           "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
+           "ngc_paged_score_keys")
 
 
 class NgcError(RuntimeError):
@@ -48,6 +51,14 @@ class ngc_cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_void_p), ("pos", C.c_void_p),
                 ("L", C.c_int32), ("B", C.c_int32), ("Hkv", C.c_int32), ("Hq", C.c_int32),
                 ("D", C.c_int32), ("cap", C.c_int32)]
+
+
+class ngc_paged_cache(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("pos_pool", C.c_void_p),
+                ("table", C.c_void_p), ("len", C.c_void_p), ("free_stack", C.c_void_p),
+                ("free_count", C.c_void_p),
+                ("L", C.c_int32), ("B", C.c_int32), ("Hkv", C.c_int32), ("Hq", C.c_int32), ("D", C.c_int32),
+                ("page_rows", C.c_int32), ("max_pages", C.c_int32), ("num_pages", C.c_int32)]
 
 
 class ngc_evict_params(C.Structure):
@@ -95,6 +106,17 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_replay_attn.restype = C.c_int
     lib.ngc_score_keys.argtypes = [cp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_score_keys.restype = C.c_int
+    gp = C.POINTER(ngc_paged_cache)
+    lib.ngc_paged_workspace_bytes.argtypes = [gp]
+    lib.ngc_paged_workspace_bytes.restype = sz
+    lib.ngc_paged_evict.argtypes = [gp, i32, vp, i64, vp, pp, i32, vp, vp, vp, vp, sz, vp]
+    lib.ngc_paged_evict.restype = C.c_int
+    lib.ngc_paged_append.argtypes = [gp, i32, vp, vp, vp, vp, sz, vp]
+    lib.ngc_paged_append.restype = C.c_int
+    lib.ngc_paged_decode_attn.argtypes = [gp, i32, vp, f32, i32, vp, vp, vp, sz, vp]
+    lib.ngc_paged_decode_attn.restype = C.c_int
+    lib.ngc_paged_score_keys.argtypes = [gp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
+    lib.ngc_paged_score_keys.restype = C.c_int
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -239,3 +261,92 @@ def ngc_replay_attn(q, k, v, death, B: int, T: int, Hq: int, Hkv: int, D: int, d
     _check(load_library().ngc_replay_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(death), B, T, Hq, Hkv, D,
                                           1 if death_per_head else 0, scale, _ptr(out), _ptr(ws), ws.numel(),
                                           _stream(stream)), "ngc_replay_attn")
+
+
+# ------------------------------------------------------------- paged layout ---
+
+@dataclass
+class PagedCache:
+    """Device buffers of a paged KV cache (torch tensors as plain memory).
+
+    k_pool, v_pool: bf16 [num_pages, page_rows, D]; pos_pool: int32 [num_pages, page_rows] or None;
+    table: int32 [L, B, Hkv, max_pages]; len: int32 [L, B, Hkv]; free_stack: int32 [num_pages];
+    free_count: int32 [1]."""
+    k_pool: object
+    v_pool: object
+    pos_pool: object
+    table: object
+    len: object
+    free_stack: object
+    free_count: object
+    Hq: int
+
+    @property
+    def page_rows(self) -> int:
+        return self.k_pool.shape[1]
+
+    @property
+    def cap(self) -> int:
+        return self.table.shape[3] * self.k_pool.shape[1]
+
+    def view(self) -> ngc_paged_cache:
+        num_pages, P, D = self.k_pool.shape
+        L, B, Hkv, max_pages = self.table.shape
+        for t in (self.k_pool, self.v_pool, self.table, self.len, self.free_stack, self.free_count):
+            assert t.is_contiguous()
+        return ngc_paged_cache(_ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.pos_pool), _ptr(self.table),
+                               _ptr(self.len), _ptr(self.free_stack), _ptr(self.free_count),
+                               L, B, Hkv, self.Hq, D, P, max_pages, num_pages)
+
+    @staticmethod
+    def allocate(L, B, Hkv, Hq, D, page_rows, max_pages, num_pages, device="cuda", with_pos=False) -> "PagedCache":
+        """An empty cache: every page on the free stack (page 0 on top)."""
+        import torch
+        k = torch.zeros(num_pages, page_rows, D, dtype=torch.bfloat16, device=device)
+        v = torch.zeros_like(k)
+        pos = torch.zeros(num_pages, page_rows, dtype=torch.int32, device=device) if with_pos else None
+        table = torch.full((L, B, Hkv, max_pages), -1, dtype=torch.int32, device=device)
+        ln = torch.zeros(L, B, Hkv, dtype=torch.int32, device=device)
+        stack = torch.arange(num_pages - 1, -1, -1, dtype=torch.int32, device=device)
+        count = torch.full((1,), num_pages, dtype=torch.int32, device=device)
+        return PagedCache(k, v, pos, table, ln, stack, count, Hq)
+
+
+def ngc_paged_workspace_bytes(pc: PagedCache) -> int:
+    v = pc.view()
+    return int(load_library().ngc_paged_workspace_bytes(C.byref(v)))
+
+
+def allocate_paged_workspace(pc: PagedCache):
+    import torch
+    return torch.zeros(ngc_paged_workspace_bytes(pc), dtype=torch.uint8, device=pc.k_pool.device)
+
+
+def ngc_paged_evict(pc: PagedCache, layer: int, logits, logit_stride: int, keep, params: ngc_evict_params,
+                    max_keep: int, kept_out, sigma_out, logp_out, ws, stream=None):
+    v = pc.view()
+    _check(load_library().ngc_paged_evict(C.byref(v), layer, _ptr(logits), logit_stride, _ptr(keep),
+                                          C.byref(params), max_keep, _ptr(kept_out), _ptr(sigma_out),
+                                          _ptr(logp_out), _ptr(ws), ws.numel(), _stream(stream)), "ngc_paged_evict")
+
+
+def ngc_paged_append(pc: PagedCache, layer: int, k_new, v_new, new_pos, ws, stream=None):
+    v = pc.view()
+    _check(load_library().ngc_paged_append(C.byref(v), layer, _ptr(k_new), _ptr(v_new), _ptr(new_pos),
+                                           _ptr(ws), ws.numel(), _stream(stream)), "ngc_paged_append")
+
+
+def ngc_paged_decode_attn(pc: PagedCache, layer: int, q, scale: float, max_len_hint: int, out, ws, stream=None,
+                          lse_out=None):
+    v = pc.view()
+    _check(load_library().ngc_paged_decode_attn(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
+                                                _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "ngc_paged_decode_attn")
+
+
+def ngc_paged_score_keys(pc: PagedCache, layer: int, q_recent, w: int, scale: float, flags: int, block: int,
+                         scores_out, ws, stream=None, lse_recent=None):
+    v = pc.view()
+    _check(load_library().ngc_paged_score_keys(C.byref(v), layer, _ptr(q_recent), _ptr(lse_recent), w, scale, flags,
+                                               block, _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "ngc_paged_score_keys")

@@ -26,6 +26,11 @@
 //
 // Long segments are split over several workgroups (flash-decode); each writes
 // an unnormalised partial (max, sum, O) and a second kernel merges them.
+//
+// Paged layout (PAGED = true): a 32-row tile never straddles a page (pages hold
+// a power-of-two number of rows >= 32), so only the tile's base address changes:
+// it comes from the segment's page table.  Table entries are fetched two tiles
+// ahead of their use so that the lookup never sits in front of the K/V loads.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -53,6 +58,11 @@ struct AttnArgs {
     int S;            // splits per segment
     int G, Hkv, cap;
     float scale_log2e;
+    // paged layout only: k, v are the pools
+    const int32_t *table;   // [seg][max_pages]
+    int max_pages;
+    int num_pages;
+    int tpp_shift;          // log2(tiles per page)
 };
 
 // Tiles [t_lo, t_hi) of split s when `tiles` tiles are cut into at most S
@@ -65,7 +75,7 @@ __device__ __forceinline__ void split_range(int tiles, int S, int s, int &t_lo, 
     t_hi = t_lo + per < tiles ? t_lo + per : tiles;
 }
 
-template <int D>
+template <int D, bool PAGED>
 __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs a)
 {
     constexpr int ROW_BYTES = D * 2;
@@ -111,8 +121,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     split_range(tiles, a.S, split, t_lo, t_hi, s_eff);
     if (t_lo >= t_hi) return;   // whole workgroup: nothing to do for this split
 
-    const unsigned char *kseg = a.k + (size_t)seg * a.cap * ROW_BYTES;
-    const unsigned char *vseg = a.v + (size_t)seg * a.cap * ROW_BYTES;
+    const unsigned char *kseg = PAGED ? a.k : a.k + (size_t)seg * a.cap * ROW_BYTES;
+    const unsigned char *vseg = PAGED ? a.v : a.v + (size_t)seg * a.cap * ROW_BYTES;
+    // paged: byte offset of a tile inside the pools (wave-uniform)
+    const int32_t *tab = PAGED ? a.table + (size_t)seg * a.max_pages : nullptr;
+    const int wv_u = __builtin_amdgcn_readfirstlane(wv);
+    auto tile_base = [&](int tile) -> size_t {
+        const int tc = tile < tiles ? tile : tiles - 1;   // a prefetch past the end re-reads the last tile
+        int page = tab[tc >> a.tpp_shift];
+        page = (page < 0 || page >= a.num_pages) ? 0 : page;   // never leave the pool
+        return ((size_t)page << a.tpp_shift) * (ATT_TILE * ROW_BYTES) +
+               (size_t)(tc & ((1 << a.tpp_shift) - 1)) * (ATT_TILE * ROW_BYTES);
+    };
 
     // B operand of the first product: Q[q = li][32c + 8kg .. +7], zero for q >= G
     bf16x8 qop[KCH];
@@ -144,20 +164,28 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     const uint32_t k_col = (uint32_t)(lane % K_PIECES) * 16u;
     const uint32_t v_col = (uint32_t)li * (DPL * 2);
     u32x4 kbuf[K_LOADS];
-    auto issue_loads = [&](int tile, u32x4 (&vb)[8]) {
+    // `base`: paged layout only, tile_base() of the tile
+    auto issue_loads = [&](int tile, size_t base, u32x4 (&vb)[8]) {
         const int row0 = tile * ATT_TILE;
+        const unsigned char *kt = kseg, *vt = vseg;
+        int first = 0;            // row number that offset 0 of kt / vt holds
+        if constexpr (PAGED) {
+            kt = kseg + base;
+            vt = vseg + base;
+            first = (tile < tiles ? tile : tiles - 1) * ATT_TILE;
+        }
 #pragma unroll
         for (int r = 0; r < K_LOADS; ++r) {
             int row = row0 + r * K_ROWS_PER_LOAD + lane / K_PIECES;
             row = row < last_row ? row : last_row;
             kbuf[r] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(kseg + ((uint32_t)row * ROW_BYTES + k_col)));
+                reinterpret_cast<const u32x4 *>(kt + ((uint32_t)(row - first) * ROW_BYTES + k_col)));
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int row = row0 + vrow_rel[e];
             row = row < last_row ? row : last_row;
-            const unsigned char *p = vseg + ((uint32_t)row * ROW_BYTES + v_col);
+            const unsigned char *p = vt + ((uint32_t)(row - first) * ROW_BYTES + v_col);
             if constexpr (DPL == 8) {
                 vb[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
             } else {
@@ -250,18 +278,27 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     // so that the number of loads in flight is the same on every path and the
     // wait for the current tile's data does not also wait for the prefetch.
     u32x4 v_a[8], v_b[8];
-    int tile = t_lo + wv;
-    issue_loads(tile, v_a);
+    int tile = t_lo + (PAGED ? wv_u : wv);
+    size_t base1 = 0, base2 = 0;   // paged: bases of the next tile and of the one after it
+    if constexpr (PAGED) {
+        base1 = tile_base(tile + ATT_WAVES);
+        base2 = tile_base(tile + 2 * ATT_WAVES);
+        issue_loads(tile, tile_base(tile), v_a);
+    } else {
+        issue_loads(tile, 0, v_a);
+    }
     while (tile < t_hi) {
         stage_k();
-        issue_loads(tile + ATT_WAVES, v_b);
+        issue_loads(tile + ATT_WAVES, base1, v_b);
+        if constexpr (PAGED) { base1 = base2; base2 = tile_base(tile + 3 * ATT_WAVES); }
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(tile, v_a);
         __builtin_amdgcn_sched_barrier(0);
         tile += ATT_WAVES;
         if (tile >= t_hi) break;
         stage_k();
-        issue_loads(tile + ATT_WAVES, v_a);
+        issue_loads(tile + ATT_WAVES, base1, v_a);
+        if constexpr (PAGED) { base1 = base2; base2 = tile_base(tile + 3 * ATT_WAVES); }
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(tile, v_b);
         __builtin_amdgcn_sched_barrier(0);
@@ -425,11 +462,13 @@ extern "C" size_t ngc_workspace_bytes(const ngc_cache *c, int32_t max_keep)
     return attn_offset(c) + (one > all ? one : all);
 }
 
-extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
-                               int32_t max_len_hint, float *out, float *lse_out,
-                               void *ws, size_t ws_bytes, void *stream)
+namespace {
+// Shared by both layouts.  `c` carries the logical geometry (for the paged
+// layout: cap = max_pages * page_rows, k / v = the pools).
+int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
+                  int32_t max_len_hint, float *out, float *lse_out, void *ws, size_t ws_bytes, void *stream)
 {
-    if (!c || !c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
+    if (!c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
     if (!aligned16(c->k) || !aligned16(c->v) || !aligned16(q) || !aligned16(out) || !aligned16(ws)) return NGC_EINVAL;
     if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
     if (c->D != 64 && c->D != 128) return NGC_EINVAL;
@@ -460,12 +499,22 @@ extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q,
     aa.lb0 = layer < 0 ? 0 : layer * c->B;
     aa.S = S; aa.G = c->Hq / c->Hkv; aa.Hkv = c->Hkv; aa.cap = c->cap;
     aa.scale_log2e = scale * 1.4426950408889634f;
+    aa.table = nullptr; aa.max_pages = 0; aa.num_pages = 0; aa.tpp_shift = 0;
+    if (pc) {
+        aa.table = pc->table; aa.max_pages = pc->max_pages; aa.num_pages = pc->num_pages;
+        int tpp = pc->page_rows / ATT_TILE, sh = 0;
+        while ((1 << sh) < tpp) ++sh;
+        aa.tpp_shift = sh;
+    }
     hipStream_t st = (hipStream_t)stream;
-
-    if (c->D == 128)
-        hipLaunchKernelGGL(decode_partial_kernel<128>, dim3(nseg * S), dim3(ATT_WAVES * 64), 0, st, aa);
-    else
-        hipLaunchKernelGGL(decode_partial_kernel<64>, dim3(nseg * S), dim3(ATT_WAVES * 64), 0, st, aa);
+    const dim3 grid(nseg * S), block(ATT_WAVES * 64);
+    if (pc) {
+        if (c->D == 128) hipLaunchKernelGGL((decode_partial_kernel<128, true>), grid, block, 0, st, aa);
+        else             hipLaunchKernelGGL((decode_partial_kernel<64, true>), grid, block, 0, st, aa);
+    } else {
+        if (c->D == 128) hipLaunchKernelGGL((decode_partial_kernel<128, false>), grid, block, 0, st, aa);
+        else             hipLaunchKernelGGL((decode_partial_kernel<64, false>), grid, block, 0, st, aa);
+    }
     NGC_HIP_CHECK(hipGetLastError());
     if (S > 1) {
         if (c->D == 128)
@@ -475,4 +524,28 @@ extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q,
         NGC_HIP_CHECK(hipGetLastError());
     }
     return NGC_OK;
+}
+}  // namespace
+
+extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scale,
+                               int32_t max_len_hint, float *out, float *lse_out,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    if (!c) return NGC_EINVAL;
+    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, ws, ws_bytes, stream);
+}
+
+extern "C" int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
+                                     int32_t max_len_hint, float *out, float *lse_out,
+                                     void *ws, size_t ws_bytes, void *stream)
+{
+    if (!pc || !pc->table) return NGC_EINVAL;
+    if (pc->page_rows < ATT_TILE || (pc->page_rows & (pc->page_rows - 1)) != 0) return NGC_EINVAL;
+    if (pc->max_pages <= 0 || pc->num_pages <= 0) return NGC_EINVAL;
+    if ((long long)pc->max_pages * pc->page_rows > 0x7FFFFFFFLL / 256) return NGC_EUNSUPPORTED;
+    ngc_cache c{};
+    c.k = pc->k_pool; c.v = pc->v_pool; c.len = pc->len; c.pos = nullptr;
+    c.L = pc->L; c.B = pc->B; c.Hkv = pc->Hkv; c.Hq = pc->Hq; c.D = pc->D;
+    c.cap = pc->max_pages * pc->page_rows;
+    return launch_decode(&c, pc, layer, q, scale, max_len_hint, out, lse_out, ws, ws_bytes, stream);
 }

@@ -2,8 +2,8 @@
 // selection with its ordered-subset log-probability, in-place compaction of
 // the surviving K/V rows, and the row append used between rounds.
 //
-// Compiled with -ffp-contract=off: the noise arithmetic is an exact operation
-// sequence (see ngc_noise.h).
+// The selection itself lives in ngc_select.h.  Compiled with -ffp-contract=off:
+// the noise arithmetic is an exact operation sequence (see ngc_noise.h).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -11,66 +11,9 @@
 #include "../../include/ngc.h"
 #include "ngc_device.h"
 #include "ngc_noise.h"
+#include "ngc_select.h"
 
 namespace ngc {
-
-// ------------------------------------------------------------ geometry ----
-
-struct SegGeom {
-    int B, Hkv, cap, block;
-};
-
-__device__ __forceinline__ void seg_coords(int seg, const SegGeom &g, int &l, int &b, int &h)
-{
-    h = seg % g.Hkv;
-    const int lb = seg / g.Hkv;
-    b = lb % g.B;
-    l = lb / g.B;
-}
-
-// Rows in use of a segment, clamped to [0, cap]; counts a clamp.
-__device__ __forceinline__ int seg_rows(const int32_t *len, int seg, int cap, int32_t *status)
-{
-    int n = len[seg];
-    if (n < 0 || n > cap) {
-        if (threadIdx.x == 0) atomicAdd(&status[NGC_STATUS_LEN_CLAMPED], 1);
-        n = n < 0 ? 0 : cap;
-    }
-    return n;
-}
-
-// ------------------------------------------------------ perturbed keys ----
-
-struct NoiseArgs {
-    uint64_t seed;
-    uint32_t round;
-    float tau;
-    int share_heads;
-};
-
-// Keys of items 4*quad .. 4*quad+3 (those below n_items), one Philox call.
-__device__ __forceinline__ void keys_of_quad(const float *row, int n_items, int quad,
-                                             const NoiseArgs &na, int l, int b, int h,
-                                             float s[4], float key[4])
-{
-    const int t0 = 4 * quad;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float x = (t0 + i < n_items) ? row[t0 + i] : -INFINITY;
-        if (x != x) x = -INFINITY;   // NaN logits count as masked
-        s[i] = x;
-    }
-    if (na.tau == 0.0f) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) key[i] = s[i];
-        return;
-    }
-    uint32_t w[4];
-    item_words(na.seed, na.round, (uint32_t)l, (uint32_t)b,
-               na.share_heads ? 0xFFFFu : (uint32_t)h, (uint32_t)quad, w);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) key[i] = perturb(s[i], na.tau, w[i]);
-}
 
 __global__ __launch_bounds__(256) void perturbed_keys_kernel(
     const float *__restrict__ logits, const int32_t *__restrict__ len, float *__restrict__ keys_out,
@@ -90,395 +33,6 @@ __global__ __launch_bounds__(256) void perturbed_keys_kernel(
         for (int i = 0; i < 4; ++i)
             if (4 * quad + i < n_items) out[4 * quad + i] = key[i];
     }
-}
-
-// ------------------------------------------------------------- select -----
-//
-// One workgroup per segment.  LDS holds the order-preserving code of every
-// perturbed key (4 B per item), two index buffers for the sort of the kept
-// items (2 B per kept item each) and a histogram area.
-//
-//   1. keys:    4 items per thread per step, one Philox call per 4 items.
-//   2. select:  the K-th largest code by a 3-pass radix select (11+11+10 bits)
-//               over LDS histograms.
-//   3. kept:    each wave owns a contiguous range of items; ballots and lane
-//               prefix counts give every kept item its ascending output slot.
-//               Items equal to the threshold are taken lowest index first.
-//   4. sigma:   stable LSD radix sort (4 x 8 bits) of the kept indices by
-//               descending code; stability plus the ascending start order is
-//               the index tie-break.
-//   5. logp:    Eq. 2 in the reverse-running-sum form: U = mass never picked,
-//               R_j = U + sum_{i>=j} e_sigma_i built from the last pick
-//               backwards; log p = sum_j (s_sigma_j - m) - sum_j log R_j.
-
-constexpr int SEL_BINS = 2048;
-
-struct SelectArgs {
-    const float *logits;
-    const int32_t *len;
-    const int32_t *keep;
-    int32_t *kept_out;
-    int32_t *sigma_out;
-    float *logp_out;
-    int32_t *status;
-    // compaction (skipped when k == nullptr)
-    void *k;
-    void *v;
-    int32_t *pos;
-    int32_t *len_out;
-    int unordered;       // 1: fill the holes below K with the kept rows beyond K (block == 1 only)
-    int seg0;
-    int max_keep;
-    int items_cap;       // ceil(cap / block): size of the code array in LDS
-    int keep_cap;        // size of each index buffer in LDS
-    uint32_t *pool_codes; // pooled mode: key codes of every item, Hkv * cap per (layer, sequence)
-    SegGeom g;
-    NoiseArgs na;
-};
-
-constexpr int SORT_BITS = 9;                 // digit width of the sigma sort
-constexpr int SORT_BINS = 1 << SORT_BITS;
-
-// For each lane: the set of lanes of this wave whose SORT_BITS-bit digit equals
-// its own, restricted to `valid` lanes.
-__device__ __forceinline__ uint64_t match_digit(uint32_t d, uint64_t valid)
-{
-    uint64_t m = valid;
-#pragma unroll
-    for (int bit = 0; bit < SORT_BITS; ++bit) {
-        const bool on = (d >> bit) & 1u;
-        const uint64_t bal = __ballot(on);
-        m &= on ? bal : ~bal;
-    }
-    return m;
-}
-
-// Unordered arrangement (single rows): kept rows below slot K stay; the i-th
-// kept row at or beyond K moves into the i-th free slot below K.  Sources and
-// destinations are disjoint, so there is no ordering to respect and no barrier.
-// `kept` is the ascending kept list in LDS.  kept[0 .. jstar) are the kept rows
-// below K; the i-th number missing from that list is i + #{p : kept[p] - p <= i}.
-template <int ROW_BYTES, int THREADS, int UNROLL>
-__device__ __forceinline__ void fill_holes_inplace(unsigned char *kbase, unsigned char *vbase, int32_t *pos,
-                                                   const uint16_t *kept, int K)
-{
-    constexpr int PIECES = ROW_BYTES / 16;
-    constexpr int ROWS_PER_STEP = THREADS / PIECES;
-    int lo = 0, hi = K;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if ((int)kept[mid] < K) lo = mid + 1; else hi = mid;
-    }
-    const int jstar = lo, movers = K - jstar;
-    auto hole_of = [&](int i) {
-        int a = 0, b = jstar;
-        while (a < b) {
-            const int mid = (a + b) >> 1;
-            if ((int)kept[mid] - mid <= i) a = mid + 1; else b = mid;
-        }
-        return i + a;
-    };
-    const int piece = threadIdx.x % PIECES, rsub = threadIdx.x / PIECES;
-    for (int i0 = 0; i0 < movers; i0 += ROWS_PER_STEP * UNROLL) {
-        u32x4 kb[UNROLL], vb[UNROLL];
-        int dst[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int i = i0 + u * ROWS_PER_STEP + rsub;
-            dst[u] = -1;
-            kb[u] = u32x4{0u, 0u, 0u, 0u};
-            vb[u] = u32x4{0u, 0u, 0u, 0u};
-            if (i < movers) {
-                const size_t off = (size_t)kept[jstar + i] * ROW_BYTES + piece * 16;
-                kb[u] = *reinterpret_cast<const u32x4 *>(kbase + off);
-                vb[u] = *reinterpret_cast<const u32x4 *>(vbase + off);
-                dst[u] = hole_of(i);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            if (dst[u] >= 0) {
-                const size_t off = (size_t)dst[u] * ROW_BYTES + piece * 16;
-                *reinterpret_cast<u32x4 *>(kbase + off) = kb[u];
-                *reinterpret_cast<u32x4 *>(vbase + off) = vb[u];
-            }
-    }
-    if (pos)
-        for (int i = threadIdx.x; i < movers; i += THREADS) pos[hole_of(i)] = pos[kept[jstar + i]];
-}
-
-// Slots of the small shared scratch array `misc` that outlive the selection.
-constexpr int MISC_KEPT = 35;   // items kept in this segment
-constexpr int MISC_ROWS = 36;   // rows in use after compaction
-constexpr int MISC_FIRST = 37;  // first item that changes place
-
-// Selection of one segment by the whole workgroup.  Leaves the kept count and
-// the new row count in misc[MISC_KEPT], misc[MISC_ROWS] (valid after the next
-// barrier).  Every thread of the workgroup returns at the same point.
-template <int THREADS, int ROW_BYTES>
-__device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, unsigned char *smem_raw)
-{
-    constexpr int NW = THREADS / NGC_WAVE;
-    constexpr int HIST = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;
-    uint32_t *code = reinterpret_cast<uint32_t *>(smem_raw);
-    uint32_t *hist = code + a.items_cap;
-    int *misc = reinterpret_cast<int *>(hist + HIST);            // 64 ints
-    uint16_t *idxA = reinterpret_cast<uint16_t *>(misc + 64);
-    uint16_t *idxB = idxA + a.keep_cap;
-    float *fmisc = reinterpret_cast<float *>(misc);
-
-    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
-    int l, b, h;
-    seg_coords(seg, a.g, l, b, h);
-    const int n = seg_rows(a.len, seg, a.g.cap, a.status);
-    const int N = (n + a.g.block - 1) / a.g.block;
-    int K = a.keep[seg];
-    {
-        int lim = N < a.max_keep ? N : a.max_keep;
-        if (K < 0 || K > lim) {
-            if (tid == 0 && (K < 0 || K > N)) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
-            K = K < 0 ? 0 : lim;
-        }
-    }
-    const float *row = a.logits + (size_t)seg * a.g.cap;
-    const bool want_logp = a.logp_out != nullptr;
-    const bool want_sort = want_logp || a.sigma_out != nullptr;
-    const bool fill_holes = a.unordered && a.k != nullptr;
-
-    if (K == 0) {
-        if (tid == 0) {
-            misc[MISC_KEPT] = 0;
-            misc[MISC_ROWS] = 0;
-            if (want_logp) a.logp_out[seg] = 0.f;
-        }
-        return;
-    }
-
-    // ---- 1. keys ----------------------------------------------------------
-    float smax = -INFINITY;
-    uint32_t cmax = 0;
-    for (int quad = tid; 4 * quad < N; quad += THREADS) {
-        float s[4], key[4];
-        keys_of_quad(row, N, quad, a.na, l, b, h, s, key);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (4 * quad + i < N) {
-                const uint32_t c = ordered_code(key[i]);
-                code[4 * quad + i] = c;
-                cmax = c > cmax ? c : cmax;
-                smax = fmaxf(smax, s[i]);
-            }
-    }
-    if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
-    if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
-
-    // ---- 2. radix select of the K-th largest code -------------------------
-    uint32_t prefix = 0, pmask = 0;
-    int need = K;   // how many of the items matching `prefix` are still to take
-    {
-        const int shifts[3] = {21, 10, 0};
-        const int widths[3] = {11, 11, 10};
-#pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = shifts[pass], nb = 1 << widths[pass];
-            for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
-            __syncthreads();
-            for (int t = tid; t < N; t += THREADS) {
-                const uint32_t u = code[t];
-                if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
-            }
-            __syncthreads();
-            // bins in descending digit order; each thread owns `per` of them
-            const int per = (nb + THREADS - 1) / THREADS;
-            int mine = 0;
-            for (int i = 0; i < per; ++i) {
-                const int p = tid * per + i;
-                if (p < nb) mine += (int)hist[nb - 1 - p];
-            }
-            int total;
-            int above = block_excl_scan_i<THREADS>(mine, misc, &total);
-            if (above < need && need <= above + mine) {
-                for (int i = 0; i < per; ++i) {
-                    const int p = tid * per + i;
-                    const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
-                    if (need <= above + c) {
-                        misc[32] = nb - 1 - p;   // digit of the K-th largest
-                        misc[33] = above;        // matching items with a larger digit
-                        break;
-                    }
-                    above += c;
-                }
-            }
-            __syncthreads();
-            const uint32_t digit = (uint32_t)misc[32];
-            need -= misc[33];
-            prefix |= digit << shift;
-            pmask |= (uint32_t)(nb - 1) << shift;
-            __syncthreads();
-        }
-    }
-    const uint32_t thr = prefix;   // code of the K-th largest key; `need` items equal to it are kept
-
-    // ---- 3. kept list, ascending ------------------------------------------
-    const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-    const int w_begin = wv * per_wave;
-    const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
-    {
-        int gt = 0, eq = 0;
-        for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
-            const int t = t0 + lane;
-            const uint32_t u = (t < w_end) ? code[t] : 0u;
-            gt += __popcll(__ballot(t < w_end && u > thr));
-            eq += __popcll(__ballot(t < w_end && u == thr));
-        }
-        if (lane == 0) { misc[wv] = gt; misc[16 + wv] = eq; }
-    }
-    __syncthreads();
-    int gt_base = 0, eq_base = 0;
-    for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
-    float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
-    int32_t *kept_row = a.kept_out + (size_t)seg * a.max_keep;
-    for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
-        const int t = t0 + lane;
-        const bool in = t < w_end;
-        const uint32_t u = in ? code[t] : 0u;
-        const bool is_gt = in && u > thr, is_eq = in && u == thr;
-        const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
-        const int gt_before = gt_base + popc_below(bgt);
-        const int eq_before = eq_base + popc_below(beq);
-        const bool sel = is_gt || (is_eq && eq_before < need);
-        if (sel) {
-            const int slot = gt_before + (eq_before < need ? eq_before : need);
-            kept_row[slot] = t;
-            if (want_sort || fill_holes) idxA[slot] = (uint16_t)t;
-            if (slot == K - 1) misc[34] = t;   // highest kept index
-        } else if (in && want_logp) {
-            float x = row[t];
-            if (x != x) x = -INFINITY;
-            unpicked += expf(x - smax);
-        }
-        gt_base += __popcll(bgt);
-        eq_base += __popcll(beq);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        const int last_item = misc[34];
-        const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
-        misc[MISC_KEPT] = K;
-        misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
-    }
-    if (fill_holes) {
-        // idxA still holds the kept list in ascending order (the sort below permutes it)
-        const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
-        fill_holes_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
-                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
-                                                  a.pos ? a.pos + (size_t)seg * a.g.cap : nullptr, idxA, K);
-    }
-    if (!want_sort) return;
-
-    // ---- 4. sigma: stable sort of the kept indices by descending code ------
-    // Sort key = cmax - code (ascending), which for kept items lies in
-    // [0, cmax - thr]: only the bits of that range are sorted, SORT_BITS at a time.
-    const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-    const int k_begin = wv * per_wave_k;
-    const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
-    uint16_t *src = idxA, *dst = idxB;
-    volatile uint32_t *vh = hist;
-    const uint32_t range = cmax - thr;
-    const int range_bits = range ? 32 - __clz(range) : 0;
-    const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
-#pragma unroll 1
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = SORT_BITS * pass;
-        for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
-        __syncthreads();
-        // per-wave digit counts over the wave's own contiguous range
-        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-            const int j = j0 + lane;
-            if (j < k_end) {
-                const uint32_t d = ((cmax - code[src[j]]) >> shift) & (SORT_BINS - 1);
-                atomicAdd(&hist[wv * SORT_BINS + d], 1u);
-            }
-        }
-        __syncthreads();
-        // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
-        {
-            constexpr int PER = SORT_BINS * NW / THREADS;
-            int vals[PER], sum = 0;
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid * PER + i;
-                vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
-                sum += vals[i];
-            }
-            int total;
-            int run = block_excl_scan_i<THREADS>(sum, misc, &total);
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid * PER + i;
-                hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
-                run += vals[i];
-            }
-        }
-        __syncthreads();
-        // scatter in order: rank within the batch + running offset of (wave, digit)
-        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-            const int j = j0 + lane;
-            const bool in = j < k_end;
-            const uint16_t idx = in ? src[j] : (uint16_t)0;
-            const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
-            const uint64_t peers = match_digit(d, __ballot(in));
-            const int rank = popc_below(peers);
-            uint32_t base = 0;
-            if (in) base = vh[wv * SORT_BINS + d];
-            __builtin_amdgcn_wave_barrier();
-            if (in) {
-                dst[base + rank] = idx;
-                if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-        __syncthreads();
-        uint16_t *tmp = src; src = dst; dst = tmp;
-    }
-    // the sorted list is in `src` (idxA or idxB, depending on the number of passes)
-    if (a.sigma_out) {
-        int32_t *sig_row = a.sigma_out + (size_t)seg * a.max_keep;
-        for (int j = tid; j < K; j += THREADS) sig_row[j] = (int32_t)src[j];
-    }
-    if (!want_logp) return;
-
-    // ---- 5. log-probability of sigma (Eq. 2) -------------------------------
-    const float U = block_sum_f<THREADS>(unpicked, fmisc);
-    const int chunk = (K + THREADS - 1) / THREADS;
-    const int nchunks = (K + chunk - 1) / chunk;
-    // thread 0 owns the LAST chunk, so an ordinary exclusive scan over threads
-    // yields the mass of everything picked after a thread's chunk
-    const int cidx = nchunks - 1 - tid;
-    const int j_lo = cidx * chunk;
-    const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
-    float mass = 0.f;
-    if (cidx >= 0)
-        for (int j = j_lo; j < j_hi; ++j) {
-            float x = row[src[j]];
-            if (x != x) x = -INFINITY;
-            mass += expf(x - smax);
-        }
-    float total_mass;
-    const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
-    float acc = 0.f;
-    if (cidx >= 0) {
-        float R = U + after;
-        for (int j = j_hi - 1; j >= j_lo; --j) {
-            float x = row[src[j]];
-            if (x != x) x = -INFINITY;
-            const float d = x - smax;
-            R += expf(d);
-            acc += d - logf(R);
-        }
-    }
-    const float lp = block_sum_f<THREADS>(acc, fmisc);
-    if (tid == 0) a.logp_out[seg] = lp;
 }
 
 // ------------------------------------------- log-prob of given actions ----
@@ -1289,6 +843,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
         sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = 0; sa.keep_cap = keep_cap;
         sa.pool_codes = reinterpret_cast<uint32_t *>(reinterpret_cast<unsigned char *>(ws) + codes_off);
         sa.g = SegGeom{c->B, c->Hkv, c->cap, 1};
+        sa.logit_stride = c->cap;
         sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
         const void *fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_pooled_kernel<256>)
                                        : reinterpret_cast<const void *>(&evict_pooled_kernel<128>);
@@ -1321,6 +876,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     sa.pool_codes = nullptr;
     sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
     sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
+    sa.logit_stride = c->cap;
     sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
 
     hipStream_t st = (hipStream_t)stream;

@@ -33,6 +33,9 @@ struct ScoreArgs {
     int seg0, lb0;
     int w, G, Hkv, cap, causal;
     float scale_log2e;
+    // paged layout: k is the pool and a tile's base comes from the page table
+    const int32_t *table;   // [seg][max_pages] or nullptr (contiguous layout)
+    int max_pages, num_pages, tpp_shift;
 };
 
 template <int D, int QT>
@@ -65,7 +68,8 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
     const int h = seg % a.Hkv;
     const int lb = seg / a.Hkv - a.lb0;
     const int Hq = a.Hkv * G;
-    const unsigned char *kseg = a.k + (size_t)seg * a.cap * ROW_BYTES;
+    const unsigned char *kseg = a.table ? a.k : a.k + (size_t)seg * a.cap * ROW_BYTES;
+    const int32_t *tab = a.table ? a.table + (size_t)seg * a.max_pages : nullptr;
     float *psi = a.psi_out + (size_t)seg * a.cap;
     const int tiles = (n + SC_TILE - 1) / SC_TILE;
     const int last_row = n - 1;
@@ -94,12 +98,21 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
     u32x4 kbuf[K_LOADS];
     auto load_tile = [&](int tile) {
         const int row0 = tile * SC_TILE;
+        const unsigned char *kt = kseg;
+        int first = 0;   // row number at offset 0 of kt
+        if (tab) {       // a tile lies inside one page
+            int page = tab[tile >> a.tpp_shift];
+            page = (page < 0 || page >= a.num_pages) ? 0 : page;
+            kt = kseg + (((size_t)page << a.tpp_shift) + (size_t)(tile & ((1 << a.tpp_shift) - 1))) *
+                            (SC_TILE * ROW_BYTES);
+            first = row0;
+        }
 #pragma unroll
         for (int r = 0; r < K_LOADS; ++r) {
             int row = row0 + r * K_ROWS_PER_LOAD + lane / K_PIECES;
             row = row < last_row ? row : last_row;
             kbuf[r] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(kseg + (size_t)row * ROW_BYTES + (lane % K_PIECES) * 16));
+                reinterpret_cast<const u32x4 *>(kt + (size_t)(row - first) * ROW_BYTES + (lane % K_PIECES) * 16));
         }
     };
     auto stage_tile = [&]() {
@@ -322,12 +335,12 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ReduceArgs a)
 
 using namespace ngc;
 
-extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
-                              const float *lse_recent, int32_t w,
-                              float scale, uint32_t flags, int32_t block, float *scores_out,
-                              void *ws, size_t ws_bytes, void *stream)
+namespace {
+int launch_score(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const void *q_recent,
+                 const float *lse_recent, int32_t w, float scale, uint32_t flags, int32_t block,
+                 float *scores_out, void *ws, size_t ws_bytes, void *stream)
 {
-    if (!c || !c->k || !c->len || !q_recent || !scores_out || !ws) return NGC_EINVAL;
+    if (!c->k || !c->len || !q_recent || !scores_out || !ws) return NGC_EINVAL;
     if ((reinterpret_cast<uintptr_t>(c->k) | reinterpret_cast<uintptr_t>(q_recent)) & 15u) return NGC_EINVAL;
     if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
     if (c->D != 64 && c->D != 128) return NGC_EINVAL;
@@ -355,6 +368,13 @@ extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_r
     sa.w = w; sa.G = G; sa.Hkv = c->Hkv; sa.cap = c->cap;
     sa.causal = (flags & NGC_SCORE_NO_CAUSAL) ? 0 : 1;
     sa.scale_log2e = scale * 1.4426950408889634f;
+    sa.table = nullptr; sa.max_pages = 0; sa.num_pages = 0; sa.tpp_shift = 0;
+    if (pc) {
+        sa.table = pc->table; sa.max_pages = pc->max_pages; sa.num_pages = pc->num_pages;
+        int tpp = pc->page_rows / SC_TILE, sh = 0;
+        while ((1 << sh) < tpp) ++sh;
+        sa.tpp_shift = sh;
+    }
     hipStream_t st = (hipStream_t)stream;
     const int qt = (R + 15) / 16;
 #define NGC_LAUNCH_SCORE(DD, QQ) \
@@ -375,4 +395,32 @@ extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_r
         NGC_HIP_CHECK(hipGetLastError());
     }
     return NGC_OK;
+}
+}  // namespace
+
+extern "C" int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
+                              const float *lse_recent, int32_t w,
+                              float scale, uint32_t flags, int32_t block, float *scores_out,
+                              void *ws, size_t ws_bytes, void *stream)
+{
+    if (!c) return NGC_EINVAL;
+    return launch_score(c, nullptr, layer, q_recent, lse_recent, w, scale, flags, block, scores_out,
+                        ws, ws_bytes, stream);
+}
+
+extern "C" int ngc_paged_score_keys(const ngc_paged_cache *pc, int32_t layer, const void *q_recent,
+                                    const float *lse_recent, int32_t w,
+                                    float scale, uint32_t flags, int32_t block, float *scores_out,
+                                    void *ws, size_t ws_bytes, void *stream)
+{
+    if (!pc || !pc->table) return NGC_EINVAL;
+    if (pc->page_rows < SC_TILE || (pc->page_rows & (pc->page_rows - 1)) != 0) return NGC_EINVAL;
+    if (pc->max_pages <= 0 || pc->num_pages <= 0) return NGC_EINVAL;
+    if ((long long)pc->max_pages * pc->page_rows > 0x7FFFFFFFLL / 256) return NGC_EUNSUPPORTED;
+    ngc_cache c{};
+    c.k = pc->k_pool; c.v = pc->v_pool; c.len = pc->len; c.pos = nullptr;
+    c.L = pc->L; c.B = pc->B; c.Hkv = pc->Hkv; c.Hq = pc->Hq; c.D = pc->D;
+    c.cap = pc->max_pages * pc->page_rows;
+    return launch_score(&c, pc, layer, q_recent, lse_recent, w, scale, flags, block, scores_out,
+                        ws, ws_bytes, stream);
 }

@@ -1,0 +1,368 @@
+"""GPU parity of the paged layout: page-table eviction, pool grant / release order,
+append, decode attention and scoring through the page table, against the oracle's
+model of the layout (tables, stack and lengths bit for bit; attention and scores
+within the tolerances of the contiguous path)."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2604_18002_amd import synth
+from _harness import from_bf16_tensor, host_case, oracle_logprob, to_bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+LOGP_RTOL = 1e-4
+
+
+def _ngc():
+    from paper_2604_18002_amd import binding
+    return binding
+
+
+def _segs(wl):
+    return [(l, b, h) for l in range(wl.L) for b in range(wl.B) for h in range(wl.Hkv)]
+
+
+def _sid(wl, seg):
+    l, b, h = seg
+    return (l * wl.B + b) * wl.Hkv + h
+
+
+def build_model(case, P, max_pages, num_pages, seed=0):
+    """Oracle model holding the case's rows on pages drawn at random from the pool."""
+    wl = case.w
+    rng = np.random.default_rng(seed)
+    m = orc.PagedCache(wl.L * wl.B * wl.Hkv, P, max_pages, num_pages, wl.D)
+    m.free_stack[:] = rng.permutation(num_pages).astype(np.int32)
+    for seg in case.segs:
+        s = _sid(wl, seg)
+        k, v = case.k[seg], case.v[seg]
+        n = k.shape[0]
+        for p in range((n + P - 1) // P):
+            m.free_count -= 1
+            page = int(m.free_stack[m.free_count])
+            m.table[s, p] = page
+            lo, hi = p * P, min((p + 1) * P, n)
+            m.k_pool[page, :hi - lo] = k[lo:hi]
+            m.v_pool[page, :hi - lo] = v[lo:hi]
+            m.pos_pool[page, :hi - lo] = np.arange(lo, hi)
+        m.len[s] = n
+    return m
+
+
+def upload_model(m, wl, with_pos=True):
+    import torch
+    ngc = _ngc()
+    pc = ngc.PagedCache.allocate(wl.L, wl.B, wl.Hkv, wl.Hq, wl.D, m.P, m.max_pages, m.num_pages, with_pos=with_pos)
+    pc.k_pool.copy_(to_bf16_tensor(m.k_pool, "cuda"))
+    pc.v_pool.copy_(to_bf16_tensor(m.v_pool, "cuda"))
+    if with_pos:
+        pc.pos_pool.copy_(torch.from_numpy(m.pos_pool))
+    pc.table.copy_(torch.from_numpy(m.table.reshape(wl.L, wl.B, wl.Hkv, m.max_pages)))
+    pc.len.copy_(torch.from_numpy(m.len.reshape(wl.L, wl.B, wl.Hkv)))
+    pc.free_stack.copy_(torch.from_numpy(m.free_stack))
+    pc.free_count.fill_(int(m.free_count))
+    return pc
+
+
+def assert_same_state(pc, m, wl, what):
+    """Tables (entries in use), lengths, free stack and count, and the pools' rows in use."""
+    import torch
+    torch.cuda.synchronize()
+    table = pc.table.cpu().numpy().reshape(-1, m.max_pages)
+    ln = pc.len.cpu().numpy().reshape(-1)
+    assert ln.tolist() == m.len.tolist(), what
+    count = int(pc.free_count.cpu().item())
+    assert count == m.free_count, what
+    assert pc.free_stack.cpu().numpy()[:count].tolist() == m.free_stack[:count].tolist(), what
+    for s in range(m.nseg):
+        used = m.pages_in_use(s)
+        assert table[s, :used].tolist() == m.table[s, :used].tolist(), (what, s)
+    # every page exactly once
+    owned = [int(table[s, i]) for s in range(m.nseg) for i in range(m.pages_in_use(s))]
+    assert sorted(owned + pc.free_stack.cpu().numpy()[:count].tolist()) == list(range(m.num_pages)), what
+
+
+def device_rows(pc, m, s):
+    """Logical rows of a segment gathered from the device pools through the device table."""
+    table = pc.table.cpu().numpy().reshape(-1, m.max_pages)
+    n = int(pc.len.cpu().numpy().reshape(-1)[s])
+    pages = table[s, :(n + m.P - 1) // m.P]
+    k = from_bf16_tensor(pc.k_pool[pages.tolist()]).reshape(-1, m.D)[:n]
+    v = from_bf16_tensor(pc.v_pool[pages.tolist()]).reshape(-1, m.D)[:n]
+    return k, v
+
+
+def check_attention(pc, m, wl, ws, layer, salt, lse=False):
+    import torch
+    ngc = _ngc()
+    scale = 1.0 / np.sqrt(wl.D)
+    layers = range(wl.L) if layer < 0 else [layer]
+    q = np.stack([synth.queries(wl, l, salt) for l in layers])                 # [nl, B, Hq, D]
+    out = torch.zeros(len(layers), wl.B, wl.Hq, wl.D, dtype=torch.float32, device="cuda")
+    lse_t = torch.zeros(len(layers), wl.B, wl.Hq, dtype=torch.float32, device="cuda") if lse else None
+    print(f"[paged attn] layer={layer} salt={salt}", flush=True)
+    ngc.ngc_paged_decode_attn(pc, layer, to_bf16_tensor(q if layer < 0 else q[0], "cuda"), scale, 0, out, ws,
+                              lse_out=lse_t)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    got_lse = lse_t.cpu().numpy() if lse else None
+    worst = 0.0
+    for i, l in enumerate(layers):
+        for b in range(wl.B):
+            for h in range(wl.Hkv):
+                k, v = m.rows(_sid(wl, (l, b, h)))
+                if k.shape[0] == 0:
+                    assert not got[i, b, h * wl.G:(h + 1) * wl.G].any()
+                    continue
+                want = orc.decode_attn(q[i, b, h * wl.G:(h + 1) * wl.G], k, v, scale)
+                worst = max(worst, float(np.abs(got[i, b, h * wl.G:(h + 1) * wl.G] - want).max()))
+                if lse:
+                    want_lse = orc.decode_lse(q[i, b, h * wl.G:(h + 1) * wl.G], k, scale)
+                    assert np.abs(got_lse[i, b, h * wl.G:(h + 1) * wl.G] - want_lse).max() <= 2e-5
+    assert worst <= ATTN_TOL, worst
+
+
+def block_logits(wl, seg, n_items):
+    return synth.segment_logits(wl, seg[0], seg[1], seg[2], n_items)
+
+
+def run_round(pc, m, wl, ws, rnd, keep_of, tau=1.0, layer=-1, share_heads=0, select_only=False):
+    """One eviction round on device and on the model; compares the sampled actions."""
+    import torch
+    ngc = _ngc()
+    P = m.P
+    segs = [s for s in _segs(wl) if layer < 0 or s[0] == layer]
+    logits = np.zeros((m.nseg, m.max_pages), np.float32)
+    keep = np.zeros(m.nseg, np.int32)
+    for seg in _segs(wl):
+        s = _sid(wl, seg)
+        N = m.pages_in_use(s)
+        logits[s, :N] = block_logits(wl, (seg[0] * 7 + rnd, seg[1], seg[2]), N)
+        keep[s] = keep_of(N)
+    max_keep = max(1, int(keep.max()))
+    kept = torch.full((m.nseg, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.zeros(m.nseg, dtype=torch.float32, device="cuda")
+    flags = ngc.EVICT_SELECT_ONLY if select_only else 0
+    p = ngc.make_params(block=P, share_heads=share_heads, noise_scale=tau, round=rnd, seed=wl.gumbel_seed, flags=flags)
+    print(f"[paged evict] round={rnd} layer={layer} tau={tau} select_only={select_only}", flush=True)
+    ngc.ngc_paged_evict(pc, layer, torch.from_numpy(logits).cuda(), m.max_pages, torch.from_numpy(keep).cuda(), p,
+                        max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    hk, hs, hl = kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy()
+    kept_lists = []
+    for seg in segs:
+        s = _sid(wl, seg)
+        N, K = m.pages_in_use(s), int(min(keep[s], m.pages_in_use(s)))
+        hsel = 0xFFFF if share_heads else seg[2]
+        okept, osig = orc.evict_select(logits[s, :N], K, tau, wl.gumbel_seed, rnd, seg[0], seg[1], hsel)
+        assert hk[s, :K].tolist() == okept.tolist(), seg
+        assert hs[s, :K].tolist() == osig.tolist(), seg
+        want_lp = oracle_logprob(logits[s, :N], osig)
+        assert abs(hl[s] - want_lp) <= LOGP_RTOL * max(1.0, abs(want_lp)), (seg, hl[s], want_lp)
+        kept_lists.append(okept.tolist())
+    if not select_only:
+        m.evict([_sid(wl, seg) for seg in segs], kept_lists)
+    return kept_lists
+
+
+def append_step(pc, m, wl, ws, step, layer=-1):
+    import torch
+    ngc = _ngc()
+    layers = range(wl.L) if layer < 0 else [layer]
+    nk = np.stack([synth.new_token_kv(wl, l, step)[0] for l in layers])        # [nl, B, Hkv, D]
+    nv = np.stack([synth.new_token_kv(wl, l, step)[1] for l in layers])
+    new_pos = torch.full((wl.B,), 100000 + step, dtype=torch.int32, device="cuda")
+    ngc.ngc_paged_append(pc, layer, to_bf16_tensor(nk if layer < 0 else nk[0], "cuda"),
+                         to_bf16_tensor(nv if layer < 0 else nv[0], "cuda"), new_pos, ws)
+    segs = [s for s in _segs(wl) if layer < 0 or s[0] == layer]
+    rows_k = [nk[(seg[0] if layer < 0 else 0), seg[1], seg[2]] for seg in segs]
+    rows_v = [nv[(seg[0] if layer < 0 else 0), seg[1], seg[2]] for seg in segs]
+    return m.append([_sid(wl, seg) for seg in segs], rows_k, rows_v, [100000 + step] * len(segs))
+
+
+@pytest.mark.parametrize("D,P", [(128, 32), (64, 32), (128, 64), (64, 128)])
+def test_attention_through_the_page_table(D, P):
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=3, D=D, n_lo=40, n_hi=1500)
+    case = host_case(wl)
+    max_pages = (wl.cap + P - 1) // P + 1
+    m = build_model(case, P, max_pages, wl.L * wl.B * wl.Hkv * max_pages + 5, seed=D + P)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    check_attention(pc, m, wl, ws, -1, 1, lse=True)
+    check_attention(pc, m, wl, ws, 1, 2)
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_long_segments_split_over_workgroups():
+    # few segments, many tiles: the split path and its merge, through the table
+    ngc = _ngc()
+    wl = synth.workload(1, L=1, B=2, n_lo=5000, n_hi=9000)
+    case = host_case(wl)
+    P = 32
+    max_pages = (wl.cap + P - 1) // P
+    m = build_model(case, P, max_pages, wl.B * wl.Hkv * max_pages, seed=5)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    check_attention(pc, m, wl, ws, -1, 3, lse=True)
+    check_attention(pc, m, wl, ws, 0, 4)
+
+
+@pytest.mark.parametrize("P,tau", [(32, 1.0), (64, 1.0), (32, 0.0)])
+def test_eviction_edits_tables_and_releases_pages(P, tau):
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=4, n_lo=700, n_hi=2048)
+    case = host_case(wl)
+    max_pages = wl.cap // P + 2
+    m = build_model(case, P, max_pages, wl.L * wl.B * wl.Hkv * max_pages, seed=P)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    before = [m.rows(s) for s in range(m.nseg)]
+    kept = run_round(pc, m, wl, ws, 0, lambda N: (N + 1) // 2, tau=tau)
+    assert_same_state(pc, m, wl, "after round 0")
+    # nothing moved: the survivors are the same bytes, seen through the new table
+    for s in range(m.nseg):
+        n0 = before[s][0].shape[0]
+        rows = np.concatenate([np.arange(b * P, min((b + 1) * P, n0)) for b in kept[s]])
+        k, v = device_rows(pc, m, s)
+        assert k.tobytes() == before[s][0][rows].tobytes() and v.tobytes() == before[s][1][rows].tobytes()
+    check_attention(pc, m, wl, ws, -1, 7)
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_select_only_and_single_layer_rounds():
+    ngc = _ngc()
+    wl = synth.workload(1, L=3, B=3, n_lo=300, n_hi=900)
+    case = host_case(wl)
+    P = 32
+    max_pages = wl.cap // P + 3
+    m = build_model(case, P, max_pages, wl.L * wl.B * wl.Hkv * max_pages, seed=9)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    run_round(pc, m, wl, ws, 0, lambda N: max(1, N // 3), select_only=True)
+    assert_same_state(pc, m, wl, "select only changes nothing")
+    run_round(pc, m, wl, ws, 1, lambda N: max(1, N // 3), layer=1)          # only layer 1 evicts
+    assert_same_state(pc, m, wl, "layer 1 evicted")
+    run_round(pc, m, wl, ws, 2, lambda N: max(1, (2 * N) // 3), share_heads=1)
+    assert_same_state(pc, m, wl, "all layers, shared noise")
+    check_attention(pc, m, wl, ws, -1, 11)
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_grow_then_evict_cycles():
+    """Several rounds of (delta appends + attention, eviction): tables, stack order, pool rows,
+    positions and attention stay equal to the model's."""
+    import torch
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=3, n_lo=100, n_hi=420)
+    case = host_case(wl)
+    P = 32
+    max_pages = 24
+    m = build_model(case, P, max_pages, 260, seed=13)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    step = 0
+    for rnd in range(3):
+        for _ in range(45):
+            skipped = append_step(pc, m, wl, ws, step)
+            assert skipped == []
+            step += 1
+        assert_same_state(pc, m, wl, f"after growth {rnd}")
+        check_attention(pc, m, wl, ws, -1, 20 + rnd)
+        run_round(pc, m, wl, ws, rnd, lambda N: max(1, (N + 1) // 2))
+        assert_same_state(pc, m, wl, f"after round {rnd}")
+    # single-layer appends
+    for _ in range(3):
+        assert append_step(pc, m, wl, ws, step, layer=1) == []
+        step += 1
+    assert_same_state(pc, m, wl, "after single-layer appends")
+    for s in range(m.nseg):
+        k, v = device_rows(pc, m, s)
+        mk, mv = m.rows(s)
+        assert k.tobytes() == mk.tobytes() and v.tobytes() == mv.tobytes(), s
+    table = pc.table.cpu().numpy().reshape(-1, m.max_pages)
+    pos_pool = pc.pos_pool.cpu().numpy()
+    for s in range(m.nseg):
+        n = int(m.len[s])
+        got = [int(pos_pool[table[s, r // P], r % P]) for r in range(n)]
+        assert got == m.positions(s).tolist()
+    check_attention(pc, m, wl, ws, -1, 30)
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_pool_exhaustion_and_capacity_are_counted_not_fatal():
+    ngc = _ngc()
+    wl = synth.workload(1, L=1, B=4, n_lo=64, n_hi=64)        # every segment: 2 full pages of 32
+    case = host_case(wl)
+    P, max_pages = 32, 4
+    nseg = wl.B * wl.Hkv
+    m = build_model(case, P, max_pages, 2 * nseg + 3, seed=17)  # 3 spare pages for 8 segments
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    skipped = append_step(pc, m, wl, ws, 0)
+    assert len(skipped) == nseg - 3                            # the three lowest segments got the spare pages
+    st = ngc.read_status(ws)
+    assert st[ngc.STATUS_APPEND_FULL] == nseg - 3 and st[ngc.STATUS_POOL_BOUNDS] == 0
+    assert_same_state(pc, m, wl, "pool exhausted")
+    # free everything of the last segment, then the stalled segments can grow again (lowest first)
+    keep_one = [[0]] * (nseg - 1) + [[]]
+    import torch
+    logits = torch.zeros(nseg, max_pages, dtype=torch.float32, device="cuda")
+    logits[:, 0] = 5.0                                         # greedy: page 0 of every segment survives
+    keep = torch.tensor([1] * (nseg - 1) + [0], dtype=torch.int32, device="cuda")
+    kept = torch.zeros(nseg, 1, dtype=torch.int32, device="cuda")
+    ngc.ngc_paged_evict(pc, -1, logits, max_pages, keep, ngc.make_params(block=P, noise_scale=0.0), 1, kept, None,
+                        None, ws)
+    m.evict(range(nseg), keep_one)
+    assert_same_state(pc, m, wl, "after freeing")
+    for step in range(1, 3 * P + 5):                           # up to capacity: 4 pages of 32 rows
+        append_step(pc, m, wl, ws, step)
+    assert_same_state(pc, m, wl, "after refill")
+    check_attention(pc, m, wl, ws, -1, 40)
+
+
+def test_scores_through_the_page_table_feed_the_round():
+    import torch
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=3, n_lo=500, n_hi=1300)
+    case = host_case(wl)
+    P, w_ = 32, 5
+    max_pages = wl.cap // P + 2
+    cap = max_pages * P
+    m = build_model(case, P, max_pages, wl.L * wl.B * wl.Hkv * max_pages, seed=21)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    scale = 1.0 / np.sqrt(wl.D)
+    q = np.stack([np.stack([synth.queries(wl, l, 300 + j) for j in range(w_)], axis=1) for l in range(wl.L)])
+    scores = torch.zeros(wl.L, wl.B, wl.Hkv, cap, dtype=torch.float32, device="cuda")
+    print("[paged score] per row, then per page", flush=True)
+    ngc.ngc_paged_score_keys(pc, -1, to_bf16_tensor(q, "cuda"), w_, scale, 0, 1, scores, ws)
+    torch.cuda.synchronize()
+    per_row = scores.cpu().numpy()
+    ngc.ngc_paged_score_keys(pc, -1, to_bf16_tensor(q, "cuda"), w_, scale, 0, P, scores, ws)
+    torch.cuda.synchronize()
+    per_page = scores.cpu().numpy()
+    for (l, b, h) in _segs(wl):
+        k, _ = m.rows(_sid(wl, (l, b, h)))
+        psi = orc.score_keys(q[l, b, :, h * wl.G:(h + 1) * wl.G], k, scale, True)
+        assert np.all(np.abs(per_row[l, b, h, :psi.size] - psi) <= 2e-3 * np.abs(psi) + 1e-7)
+        want = orc.block_means(psi, P)
+        assert np.all(np.abs(per_page[l, b, h, :want.size] - want) <= 2e-3 * np.abs(want) + 1e-7)
+    # the round takes the scores where the scoring kernel left them (stride = max_pages * P)
+    keep = torch.from_numpy(np.array([max(1, m.pages_in_use(s) // 2) for s in range(m.nseg)], np.int32)).cuda()
+    max_keep = int(keep.max().item())
+    kept = torch.zeros(m.nseg, max_keep, dtype=torch.int32, device="cuda")
+    ngc.ngc_paged_evict(pc, -1, scores, cap, keep, ngc.make_params(block=P, noise_scale=0.0), max_keep, kept,
+                        None, None, ws)
+    torch.cuda.synchronize()
+    hk = kept.cpu().numpy()
+    flat = per_page.reshape(m.nseg, cap)
+    for s in range(m.nseg):
+        N, K = m.pages_in_use(s), max(1, m.pages_in_use(s) // 2)
+        # greedy top-K of the device's own scores, by a library sort (ties by index)
+        order = np.argsort(-flat[s, :N].astype(np.float64), kind="stable")[:K]
+        assert hk[s, :K].tolist() == sorted(order.tolist())
+    assert all(x == 0 for x in ngc.read_status(ws))
