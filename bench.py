@@ -52,6 +52,7 @@ def parse_args():
     ap.add_argument("--evict-reps", type=int, default=5, help="timed repetitions of the round-0 eviction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also time decode attention launched layer by layer")
+    ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout section")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy first (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -521,6 +522,102 @@ def main():
         per_layer["hip_graph_ms_per_token_step"] = gms
         per_layer["hip_graph_hbm_frac"] = attn_bytes(w, rows_after, nseg) / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
+    # ---- the same cycle over the paged layout (pages of 32 rows = the paper's blocks): eviction edits page
+    # tables, nothing moves; decode attention and append go through the table.  Runs last: the contiguous
+    # cache is released first.
+    paged = None
+    if not args.no_paged:
+        del cache, logits, kept, sigma, scores
+        torch.cuda.empty_cache()
+        P = 32
+        max_pages = (cap + P - 1) // P + 1
+        pages_b = (lens + P - 1) // P                                        # [B] pages per segment at the peak
+        n_pg = np.broadcast_to(pages_b[None, :, None], (w.L, w.B, w.Hkv)).reshape(-1).astype(np.int64)
+        keep_pg = np.array([(int(n) * w.keep_num + w.keep_den - 1) // w.keep_den for n in n_pg], np.int32)
+        grow_pg = (w.delta + P - 1) // P + 1
+        num_pages = int(n_pg.sum() + nseg * grow_pg)
+        pc = ngc.PagedCache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, P, max_pages, num_pages, device=dev)
+        synth.fill_normal_bf16_(pc.k_pool, w.data_seed * 2 + 10)
+        synth.fill_normal_bf16_(pc.v_pool, w.data_seed * 2 + 11)
+        first = np.concatenate([[0], np.cumsum(n_pg)[:-1]])
+        table_h = np.full((nseg, max_pages), -1, np.int32)
+        for sg in range(nseg):
+            table_h[sg, :n_pg[sg]] = np.arange(first[sg], first[sg] + n_pg[sg])
+        table0 = torch.from_numpy(table_h.reshape(w.L, w.B, w.Hkv, max_pages)).to(dev)
+        stack0 = torch.from_numpy(np.arange(num_pages - 1, int(n_pg.sum()) - 1, -1, dtype=np.int32)).to(dev)
+        n_free0 = int(stack0.numel())
+        keep_p = torch.from_numpy(keep_pg.reshape(w.L, w.B, w.Hkv)).to(dev)
+        max_keep_p = int(keep_pg.max())
+        plog = torch.randn(w.L, w.B, w.Hkv, max_pages, generator=g, device=dev)
+        kept_p = torch.empty(w.L, w.B, w.Hkv, max_keep_p, dtype=torch.int32, device=dev)
+        sigma_p = torch.empty_like(kept_p)
+        ws_p = ngc.allocate_paged_workspace(pc)
+
+        def reset_paged():
+            pc.table.copy_(table0)
+            pc.len.copy_(len0)
+            pc.free_stack[:n_free0].copy_(stack0)
+            pc.free_count.fill_(n_free0)
+
+        def paged_evict(r):
+            ngc.ngc_paged_evict(pc, -1, plog, max_pages, keep_p,
+                                ngc.make_params(block=P, noise_scale=1.0, round=r, seed=w.gumbel_seed),
+                                max_keep_p, kept_p, sigma_p if w.with_logprob else None,
+                                logp if w.with_logprob else None, ws_p)
+
+        pg_p1 = []
+        for rep in range(4):
+            reset_paged()
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            paged_evict(0)
+            e1.record()
+            torch.cuda.synchronize()
+            pg_p1.append(1e3 * e0.elapsed_time(e1))
+        rows_after_p = float(pc.len.sum().item())
+        hint_p = int(pc.len.max().item()) + w.delta
+        pg_events, pg_evict_us = [], []
+        periods = 1 + min(args.steps, 3)
+        t_start = None
+        for per in range(periods):
+            if per == 1:
+                torch.cuda.synchronize()
+                t_start = time.perf_counter()
+            for t in range(w.delta):
+                ngc.ngc_paged_append(pc, -1, k_new, v_new, None, ws_p)
+                e0, e1 = ev(), ev()
+                e0.record()
+                ngc.ngc_paged_decode_attn(pc, -1, q, scale, hint_p, out, ws_p)
+                e1.record()
+                if per > 0:
+                    pg_events.append((e0, e1, rows_after_p + (t + 1) * nseg))
+            e0, e1 = ev(), ev()
+            e0.record()
+            paged_evict(per + 1)
+            e1.record()
+            if per > 0:
+                pg_evict_us.append((e0, e1))
+            rows_after_p = float(pc.len.sum().item())     # (synchronises once per period)
+        torch.cuda.synchronize()
+        pg_elapsed = time.perf_counter() - t_start
+        pg_attn_ms = sum(a.elapsed_time(b) for a, b, _ in pg_events)
+        pg_attn_b = sum(attn_bytes(w, rows, nseg) for _, _, rows in pg_events)
+        assert all(x == 0 for x in ngc.read_status(ws_p)), "paged run: status words not clean"
+        used = int(((pc.len + (P - 1)) // P).sum().item())
+        assert used + int(pc.free_count.item()) == num_pages, "paged run: pages lost"
+        paged = {
+            "what": f"same cycle over the paged layout, pages of {P} rows, keep {w.keep_num}/{w.keep_den} of the pages "
+                    "per round; eviction = sampling + log-prob + page-table edit + ordered release, no K/V bytes moved",
+            "pool_pages": num_pages, "pool_GB": 2.0 * num_pages * P * w.D * 2 / 1e9,
+            "eviction_step_us": float(np.mean(pg_p1[1:])),
+            "eviction_step_us_steady": 1e3 * float(np.mean([a.elapsed_time(b) for a, b in pg_evict_us])),
+            "tokens_per_s": w.B * w.delta * (periods - 1) / pg_elapsed,
+            "decode_attn_ms_per_token_step": pg_attn_ms / len(pg_events),
+            "decode_attn_hbm_frac": pg_attn_b / (pg_attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "rows_per_segment_after_round": rows_after_p / nseg,
+        }
+
     line = {
         "metric": METRIC,
         "value": value,
@@ -554,7 +651,7 @@ def main():
             "bytes_per_launch": attn_b / n_attn, "launch_ms": attn_ms / n_attn, "launches": n_attn,
         },
         "roofline_evict": {
-            "kernels": "select_kernel + compact_kernel (round 0 at peak cache)",
+            "kernels": "evict_kernel (selection + log-prob + in-place compaction fused; round 0 at peak cache)",
             "bound": "hbm", "achieved": p1_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": p1_gbs / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("evict"),
@@ -565,6 +662,7 @@ def main():
         "logprob_backward": bwd,
         "eviction_pooled_heads": pooled,
         "replay_attn": replay,
+        "paged_layout": paged,
         "setup_s": t_setup,
     }
     if per_layer:

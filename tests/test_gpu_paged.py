@@ -366,3 +366,155 @@ def test_scores_through_the_page_table_feed_the_round():
         order = np.argsort(-flat[s, :N].astype(np.float64), kind="stable")[:K]
         assert hk[s, :K].tolist() == sorted(order.tolist())
     assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_identity_table_gives_the_contiguous_result_bit_for_bit():
+    """A contiguous cache is a paged one whose table counts 0, 1, 2, ...: both entry points must
+    then return the same bits (same tiles, same order of operations)."""
+    import torch
+    ngc = _ngc()
+    wl = synth.workload(1, L=2, B=5, n_lo=200, n_hi=2048)
+    case = host_case(wl)
+    from _harness import upload
+    cache, _, _ = upload(case)
+    P = 64
+    mp = wl.cap // P
+    nseg = wl.L * wl.B * wl.Hkv
+    table = (torch.arange(nseg, dtype=torch.int32, device="cuda")[:, None] * mp +
+             torch.arange(mp, dtype=torch.int32, device="cuda")[None]).view(wl.L, wl.B, wl.Hkv, mp).contiguous()
+    pc = ngc.PagedCache(cache.k.view(nseg * mp, P, wl.D), cache.v.view(nseg * mp, P, wl.D), None, table, cache.len,
+                        torch.zeros(nseg * mp, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, dtype=torch.int32, device="cuda"), wl.Hq)
+    ws = ngc.allocate_workspace(cache, 1)
+    q = np.stack([synth.queries(wl, l, 77) for l in range(wl.L)])
+    a = torch.zeros(wl.L, wl.B, wl.Hq, wl.D, dtype=torch.float32, device="cuda")
+    b = torch.zeros_like(a)
+    la = torch.zeros(wl.L, wl.B, wl.Hq, dtype=torch.float32, device="cuda")
+    lb = torch.zeros_like(la)
+    scale = 1.0 / np.sqrt(wl.D)
+    for hint in (0, 300):                        # two different splits of the work
+        ngc.ngc_decode_attn(cache, -1, to_bf16_tensor(q, "cuda"), scale, hint, a, ws, lse_out=la)
+        ngc.ngc_paged_decode_attn(pc, -1, to_bf16_tensor(q, "cuda"), scale, hint, b, ws, lse_out=lb)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(la, lb)
+
+
+def test_full_size_paged_sampled_segments():
+    """Config 2 at full size in the launch configuration bench.py times (pages of 32 rows, all layers per
+    launch): pools filled on the device, a sample of segments generated on the host; round 0, one append,
+    decode attention; sampled segments against the oracle, pool accounting everywhere."""
+    import torch
+    ngc = _ngc()
+    w = synth.workload(2)
+    P = 32
+    rng = np.random.default_rng(202)
+    segs = {(0, 0, 0), (w.L - 1, w.B - 1, w.Hkv - 1)}
+    while len(segs) < 20:
+        segs.add((int(rng.integers(w.L)), int(rng.integers(w.B)), int(rng.integers(w.Hkv))))
+    segs = sorted(segs)
+    case = host_case(w, segs)
+    nseg = w.L * w.B * w.Hkv
+    max_pages = w.cap // P + 1
+    n_pg = np.broadcast_to(((case.lens + P - 1) // P)[None, :, None], (w.L, w.B, w.Hkv)).reshape(-1).astype(np.int64)
+    keep_pg = ((n_pg + 2) // 3).astype(np.int32)
+    spare = nseg * 2
+    num_pages = int(n_pg.sum()) + spare
+    print(f"[full paged] pool {2 * num_pages * P * w.D * 2 / 1e9:.1f} GB, {nseg} segments", flush=True)
+    pc = ngc.PagedCache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, P, max_pages, num_pages)
+    synth.fill_normal_bf16_(pc.k_pool, 1)
+    synth.fill_normal_bf16_(pc.v_pool, 2)
+    # segment s owns pages perm[first_s ...]: scattered over the pool
+    perm = np.random.default_rng(7).permutation(num_pages).astype(np.int32)
+    first = np.concatenate([[0], np.cumsum(n_pg)[:-1]])
+    table_h = np.full((nseg, max_pages), -1, np.int32)
+    for s in range(nseg):
+        table_h[s, :n_pg[s]] = perm[first[s]:first[s] + n_pg[s]]
+    stack_h = perm[int(n_pg.sum()):].copy()
+    pc.table.copy_(torch.from_numpy(table_h.reshape(w.L, w.B, w.Hkv, max_pages)))
+    pc.free_stack[:spare].copy_(torch.from_numpy(stack_h))
+    pc.free_count.fill_(spare)
+    pc.len.copy_(torch.from_numpy(np.broadcast_to(case.lens[None, :, None], (w.L, w.B, w.Hkv)).copy()))
+    logits = torch.randn(nseg, max_pages, device="cuda")
+    host_logits = {}
+    for seg in segs:
+        s = _sid(w, seg)
+        n = case.k[seg].shape[0]
+        kk = np.zeros((n_pg[s] * P, w.D), np.uint16)
+        vv = np.zeros_like(kk)
+        kk[:n], vv[:n] = case.k[seg], case.v[seg]
+        idx = torch.from_numpy(table_h[s, :n_pg[s]].astype(np.int64)).cuda()
+        pc.k_pool[idx] = to_bf16_tensor(kk.reshape(-1, P, w.D), "cuda")
+        pc.v_pool[idx] = to_bf16_tensor(vv.reshape(-1, P, w.D), "cuda")
+        host_logits[seg] = synth.segment_logits(w, seg[0], seg[1], seg[2], int(n_pg[s]))
+        logits[s, :n_pg[s]] = torch.from_numpy(host_logits[seg]).cuda()
+    keep = torch.from_numpy(keep_pg).cuda()
+    max_keep = int(keep_pg.max())
+    kept = torch.empty(nseg, max_keep, dtype=torch.int32, device="cuda")
+    sigma = torch.empty_like(kept)
+    logp = torch.empty(nseg, dtype=torch.float32, device="cuda")
+    ws = ngc.allocate_paged_workspace(pc)
+    print("[full paged] evict, all layers", flush=True)
+    ngc.ngc_paged_evict(pc, -1, logits, max_pages, keep, ngc.make_params(block=P, noise_scale=1.0, round=0,
+                                                                        seed=w.gumbel_seed),
+                        max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    k_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    v_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    q = torch.randn(w.L, w.B, w.Hq, w.D, generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty(w.L, w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    print("[full paged] append + decode attention, all layers", flush=True)
+    ngc.ngc_paged_append(pc, -1, k_new, v_new, None, ws)
+    scale = 1.0 / np.sqrt(w.D)
+    ngc.ngc_paged_decode_attn(pc, -1, q, scale, int(keep_pg.max()) * P + w.delta, out, ws)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    # pool accounting everywhere (inputs only: page counts and keep counts)
+    freed = n_pg - keep_pg
+    push_at = spare + np.concatenate([[0], np.cumsum(freed)[:-1]])
+    table_d = pc.table.cpu().numpy().reshape(nseg, max_pages)
+    len_d = pc.len.cpu().numpy().reshape(-1)
+    stack_d = pc.free_stack.cpu().numpy()
+    count_d = int(pc.free_count.item())
+    # after the round every segment has K full pages (4096 rows = 128 full pages, so no short page), and the
+    # append that follows takes one page per segment from the top of the stack, lowest segment first
+    assert len_d.tolist() == (keep_pg * P + 1).tolist()
+    total_after_round = spare + int(freed.sum())
+    assert count_d == total_after_round - nseg
+    for seg in segs:
+        s = _sid(w, seg)
+        N, K = int(n_pg[s]), int(keep_pg[s])
+        okept, osig = orc.evict_select(host_logits[seg], K, 1.0, w.gumbel_seed, 0, seg[0], seg[1], seg[2])
+        assert kept[s, :K].cpu().numpy().tolist() == okept.tolist(), seg
+        assert sigma[s, :K].cpu().numpy().tolist() == osig.tolist(), seg
+        want_lp = oracle_logprob(host_logits[seg], osig)
+        assert float(logp[s]) == pytest.approx(want_lp, rel=LOGP_RTOL), seg
+        gone = [t for t in range(N) if t not in set(okept.tolist())]
+        assert table_d[s, :K].tolist() == table_h[s, okept].tolist(), seg
+        # released pages sit on the stack where the segment order puts them, unless a later grant took them
+        for r, t in enumerate(gone):
+            at = int(push_at[s]) + r
+            if at < count_d:
+                assert stack_d[at] == table_h[s, t], (seg, r)
+        # the page granted for the appended row (its id depends on every segment's sample: checked to be valid
+        # here, exactly in the small cases)
+        page = int(table_d[s, K])
+        assert 0 <= page < num_pages
+        rows = np.concatenate([np.arange(b * P, (b + 1) * P) for b in okept])
+        kk = np.concatenate([case.k[seg][rows], bits(k_new[seg[0], seg[1], seg[2]])[None]])
+        vv = np.concatenate([case.v[seg][rows], bits(v_new[seg[0], seg[1], seg[2]])[None]])
+        # the appended row really is in the granted page
+        assert bits(pc.k_pool[page, 0]).tobytes() == kk[-1].tobytes()
+        want = orc.decode_attn(bits(q[seg[0], seg[1], seg[2] * w.G:(seg[2] + 1) * w.G]), kk, vv, scale)
+        got = out[seg[0], seg[1], seg[2] * w.G:(seg[2] + 1) * w.G].cpu().numpy()
+        assert np.abs(got - want).max() <= ATTN_TOL, (seg, np.abs(got - want).max())
+    # every page exactly once, at any size
+    used = torch.from_numpy(np.concatenate([table_d[s, :keep_pg[s] + 1] for s in range(nseg)])).cuda()
+    everything = torch.cat([used, pc.free_stack[:count_d]]).sort().values
+    assert torch.equal(everything, torch.arange(num_pages, dtype=torch.int32, device="cuda"))
+    assert bool(torch.isfinite(out).all())
