@@ -46,7 +46,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default 3: 7B-shaped)")
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default 3: 7B-shaped); 5 = the small-cache shape of the paper's "
+                         "own runs (latency-bound, see --per-layer)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (0 = the workload's)")
     ap.add_argument("--evict-reps", type=int, default=5, help="timed repetitions of the round-0 eviction")
@@ -333,6 +334,51 @@ def main():
         "eviction_step_us_steady": un_steady_us, "moved_rows_steady": un_steady_moved,
         "hbm_frac_steady": un_steady_bytes / (un_steady_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
     }
+
+    # ---- the paper's granularity on the contiguous layout: items are blocks of 32 rows and the KV heads of a
+    # (layer, sequence) share one noise draw (Sec. 4.2); whole blocks (8 KB of K, 8 KB of V) move
+    BLK = 32
+    items_b = (lens + BLK - 1) // BLK
+    keep_b_h = np.zeros((w.L, w.B, w.Hkv), np.int32)
+    for b in range(w.B):
+        keep_b_h[:, b, :] = (int(items_b[b]) * w.keep_num + w.keep_den - 1) // w.keep_den
+    keep_b = torch.from_numpy(keep_b_h).to(dev)
+    max_keep_b = int(keep_b_h.max())
+    kept_b = torch.empty(w.L, w.B, w.Hkv, max_keep_b, dtype=torch.int32, device=dev)
+    sigma_b = torch.empty_like(kept_b)
+    b32_us = []
+    for rep in range(3):
+        cache.len.copy_(len0)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        ngc.ngc_evict(cache, -1, logits, keep_b,
+                      ngc.make_params(block=BLK, share_heads=1, noise_scale=1.0, round=0, seed=w.gumbel_seed),
+                      max_keep_b, kept_b, sigma_b, logp, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        b32_us.append(1e3 * e0.elapsed_time(e1))
+    slot_b = torch.arange(max_keep_b, device=dev, dtype=torch.int32)
+    moved_blocks = ((kept_b != slot_b) & (slot_b < keep_b.unsqueeze(-1)))
+    # rows of a moved block: BLK, except a segment's short last block
+    n0_t = torch.from_numpy(np.broadcast_to(lens[None, :, None], keep_b_h.shape).copy()).to(dev).unsqueeze(-1)
+    rows_in = torch.clamp(n0_t - kept_b * BLK, max=BLK)
+    moved_b_rows = float((rows_in * moved_blocks).sum().item())
+    b32_us_m = float(np.mean(b32_us[1:]))
+    b32_bytes = evict_bytes(w, np.broadcast_to(items_b[None, :, None], keep_b_h.shape), keep_b_h, moved_b_rows,
+                            True, True)
+    block32 = {
+        "what": "round 0 with blocks of 32 rows and one noise draw per (layer, sequence): whole blocks move",
+        "eviction_step_us": b32_us_m, "moved_rows": moved_b_rows, "bytes_per_round": b32_bytes,
+        "hbm_frac": b32_bytes / (b32_us_m * 1e-6) / 1e9 / HBM_PEAK_GBS,
+    }
+    del kept_b, sigma_b
+    # back to the per-row schedule's state: one per-row round from the peak
+    cache.len.copy_(len0)
+    evict(rnd + 20)
+    for t in range(w.delta):
+        ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+    evict(rnd + 21)
 
     # ---- key scoring (the step before the eviction round): w = 5 recent queries, steady-state size
     w_recent = 5
@@ -632,7 +678,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"configs[{w.index}] {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} "
+            "workload": f"{'configs[%d]' % w.index if w.index < 5 else 'extra (paper-shaped, not a BASELINE config)'} {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} "
                         f"peak cache {w.n_lo}..{w.n_hi} rows, keep {w.keep_num}/{w.keep_den} (budget rule), "
                         f"delta={w.delta}, logits {w.logits_kind}, log-prob {'on' if w.with_logprob else 'off'}",
             "step": f"{w.delta} x (append + decode attention, all {w.L} layers in one launch) + 1 eviction round",
@@ -658,6 +704,7 @@ def main():
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
         },
         "eviction_unordered": unordered,
+        "eviction_block32_shared_heads": block32,
         "scoring": scoring,
         "logprob_backward": bwd,
         "eviction_pooled_heads": pooled,

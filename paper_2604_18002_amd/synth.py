@@ -72,6 +72,12 @@ WORKLOADS = (
     Workload("long-reasoning-stress", 4, L=4, B=256, Hq=28, Hkv=4, D=128, n_lo=16384, n_hi=16384,
              keep_num=1, keep_den=3, delta=1024, decode_steps=1024, logits_kind="heavy",
              with_logprob=True, per_head_budget=True),
+    # not one of the benchmark configurations: the shape of the paper's own training runs (1.5B model, one
+    # group of 16 rollouts, rounds every 350 tokens at a retention of 1/2, so the cache swings between 350
+    # and 700 rows): a small-cache case where launch latency, not bandwidth, decides
+    Workload("paper-rollout-group", 5, L=28, B=16, Hq=12, Hkv=2, D=128, n_lo=700, n_hi=700,
+             keep_num=1, keep_den=2, delta=350, decode_steps=350, logits_kind="normal",
+             with_logprob=True),
 )
 
 
