@@ -63,6 +63,73 @@ def test_host_side_argument_checks_need_no_gpu(lib):
     assert lib.ngc_workspace_bytes(C.byref(c), 256) >= binding.STATUS_WORDS * 4 + 2 * 2 * 4
 
 
+def test_paged_struct_and_argument_checks_need_no_gpu(lib):
+    from paper_2604_18002_amd import binding
+    assert C.sizeof(binding.ngc_paged_cache) == 7 * 8 + 8 * 4
+    A = 0x10000                      # a made-up, 16-byte aligned device address: the host side never reads it
+    def pc(**kw):
+        f = dict(k_pool=A, v_pool=A, pos_pool=None, table=A, len=A, free_stack=A, free_count=A,
+                 L=2, B=3, Hkv=2, Hq=12, D=128, page_rows=32, max_pages=64, num_pages=1000)
+        f.update(kw)
+        return binding.ngc_paged_cache(*[f[k] for k, _ in binding.ngc_paged_cache._fields_])
+    good = pc()
+    need = lib.ngc_paged_workspace_bytes(C.byref(good))
+    assert need >= binding.STATUS_WORDS * 4 + 2 * 4 * 12
+    p32 = binding.make_params(block=32)
+    def evict(cache, params=p32, stride=64, ws=A, ws_bytes=None, max_keep=8):
+        return lib.ngc_paged_evict(C.byref(cache), -1, A, stride, A, C.byref(params), max_keep, A, None, None,
+                                   ws, need if ws_bytes is None else ws_bytes, None)
+    assert evict(pc(page_rows=48)) == binding.NGC_EINVAL                  # not a power of two
+    assert evict(pc(page_rows=16)) == binding.NGC_EINVAL                  # below the 32-row tile
+    assert evict(pc(D=96)) == binding.NGC_EINVAL
+    assert evict(pc(Hq=13)) == binding.NGC_EINVAL                         # not a multiple of Hkv
+    assert evict(pc(table=None)) == binding.NGC_EINVAL
+    assert evict(pc(k_pool=A + 8)) == binding.NGC_EINVAL                  # misaligned pool
+    assert evict(pc(max_pages=20000)) == binding.NGC_EUNSUPPORTED
+    assert evict(good, params=binding.make_params(block=1)) == binding.NGC_EINVAL        # items are pages
+    assert evict(good, stride=63) == binding.NGC_EINVAL                   # logit rows would overlap
+    assert evict(good, params=binding.make_params(block=32, flags=binding.EVICT_UNORDERED)) == binding.NGC_EUNSUPPORTED
+    assert evict(good, params=binding.make_params(block=32, flags=binding.EVICT_POOL_HEADS)) == binding.NGC_EUNSUPPORTED
+    assert evict(good, ws_bytes=64) == binding.NGC_ENOSPC
+    assert evict(good, max_keep=0) == binding.NGC_EINVAL
+    assert lib.ngc_paged_append(C.byref(good), 5, A, A, None, A, need, None) == binding.NGC_EINVAL     # no such layer
+    assert lib.ngc_paged_append(C.byref(good), 0, A + 4, A, None, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_paged_decode_attn(C.byref(good), -1, A, 0.1, 0, A, None, A, 16, None) == binding.NGC_ENOSPC
+    assert lib.ngc_paged_decode_attn(C.byref(pc(page_rows=24)), -1, A, 0.1, 0, A, None, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_paged_score_keys(C.byref(good), -1, A, None, 20, 0.1, 0, 32, A, A, need, None) == binding.NGC_EUNSUPPORTED
+    assert lib.ngc_paged_score_keys(C.byref(good), -1, A, A, 5, 0.1, binding.SCORE_NO_CAUSAL, 32, A, A, need, None) \
+        == binding.NGC_EINVAL
+
+
+def test_contiguous_argument_checks_need_no_gpu(lib):
+    from paper_2604_18002_amd import binding
+    A = 0x10000
+    def cache(**kw):
+        f = dict(k=A, v=A, len=A, pos=None, L=2, B=3, Hkv=2, Hq=12, D=128, cap=4096)
+        f.update(kw)
+        return binding.ngc_cache(*[f[k] for k, _ in binding.ngc_cache._fields_])
+    good = cache()
+    need = lib.ngc_workspace_bytes(C.byref(good), 100)
+    p = binding.make_params()
+    def evict(c, params=p, ws_bytes=None, max_keep=100):
+        return lib.ngc_evict(C.byref(c), -1, A, A, C.byref(params), max_keep, A, None, None, A,
+                             need if ws_bytes is None else ws_bytes, None)
+    assert evict(cache(D=80)) == binding.NGC_EINVAL
+    assert evict(cache(Hq=34)) == binding.NGC_EINVAL                      # more than 16 query heads per KV head
+    assert evict(cache(v=A + 2)) == binding.NGC_EINVAL
+    assert evict(cache(cap=70000)) == binding.NGC_EUNSUPPORTED            # more items than a segment's LDS holds
+    assert evict(good, params=binding.make_params(block=0)) == binding.NGC_EINVAL
+    assert evict(good, params=binding.make_params(block=2, flags=binding.EVICT_UNORDERED)) == binding.NGC_EUNSUPPORTED
+    assert evict(good, params=binding.make_params(flags=binding.EVICT_POOL_HEADS), ws_bytes=need) == binding.NGC_ENOSPC
+    assert evict(good, ws_bytes=8) == binding.NGC_ENOSPC
+    assert lib.ngc_cache_append(C.byref(good), 2, A, A, None, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_decode_attn(C.byref(good), -1, A, float("nan"), 0, A, None, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_decode_attn(C.byref(good), -1, A, 0.1, -5, A, None, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_score_keys(C.byref(good), -1, A, None, 0, 0.1, 0, 1, A, A, need, None) == binding.NGC_EINVAL
+    assert lib.ngc_subset_logprob_backward(A, A, A, A, 4, 10, 10, 40000, None, A, A, need, None) == binding.NGC_EUNSUPPORTED
+    assert lib.ngc_replay_attn(A, A, A, A, 1, 70000, 12, 2, 128, 0, 0.1, A, A, 1 << 30, None) != binding.NGC_OK
+
+
 def test_workspace_grows_with_the_geometry(lib):
     from paper_2604_18002_amd import binding
     small = binding.ngc_cache(None, None, None, None, 1, 1, 2, 8, 64, 512)
