@@ -54,6 +54,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also time decode attention launched layer by layer")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout section")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming read / copy probes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy first (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -184,6 +185,32 @@ def main():
         b.copy_(a)          # the plain copy of known size: 1 GiB read, 1 GiB written
         torch.cuda.synchronize()
         del a, b
+
+    # ------------------------------------------- streaming ceilings, same job
+    # (16 bytes per lane, grid-stride, 8 GiB: what this machine gives the plainest read and copy kernels)
+    ceilings = None
+    if not args.no_ceilings:
+        nb = 8 << 30
+        src = torch.empty(nb, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nb, dtype=torch.uint8, device=dev)
+        src.fill_(1)
+        dst.fill_(2)
+        ceilings = {"bytes": nb, "what": "ngc_probe_stream over 8 GiB, best of 3 after a warm-up; copy counts read + write"}
+        for name, kind, factor in (("read", ngc.PROBE_READ, 1.0), ("read_nontemporal", ngc.PROBE_READ_NT, 1.0),
+                                   ("copy", ngc.PROBE_COPY, 2.0), ("copy_nontemporal", ngc.PROBE_COPY_NT, 2.0)):
+            best = None
+            for rep in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ngc.ngc_probe_stream(kind, src, dst, nb)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep > 0:
+                    ms = e0.elapsed_time(e1)
+                    best = ms if best is None or ms < best else best
+            ceilings[name + "_GBs"] = factor * nb / (best * 1e-3) / 1e9
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- inputs
     lens = synth.lengths(w)                                   # [B] peak rows per sequence
@@ -695,6 +722,8 @@ def main():
             "frac": attn_gbs / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("decode"),
             "bytes_per_launch": attn_b / n_attn, "launch_ms": attn_ms / n_attn, "launches": n_attn,
+            "frac_of_measured_read_ceiling": (attn_gbs / max(ceilings["read_GBs"], ceilings["read_nontemporal_GBs"])
+                                              if ceilings else None),
         },
         "roofline_evict": {
             "kernels": "evict_kernel (selection + log-prob + in-place compaction fused; round 0 at peak cache)",
@@ -702,6 +731,8 @@ def main():
             "frac": p1_gbs / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("evict"),
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
+            "frac_of_measured_copy_ceiling": (p1_gbs / max(ceilings["copy_GBs"], ceilings["copy_nontemporal_GBs"])
+                                              if ceilings else None),
         },
         "eviction_unordered": unordered,
         "eviction_block32_shared_heads": block32,
@@ -710,6 +741,7 @@ def main():
         "eviction_pooled_heads": pooled,
         "replay_attn": replay,
         "paged_layout": paged,
+        "measured_ceilings": ceilings,
         "setup_s": t_setup,
     }
     if per_layer:

@@ -21,6 +21,7 @@ _UNITS = (
     ("ngc_attn.hip", []),
     ("ngc_score.hip", []),
     ("ngc_replay.hip", []),
+    ("ngc_probe.hip", []),
 )
 
 

@@ -38,7 +38,8 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
-           "ngc_paged_score_keys")
+           "ngc_paged_score_keys", "ngc_probe_stream")
+PROBE_READ, PROBE_COPY, PROBE_READ_NT, PROBE_COPY_NT = 0, 1, 2, 3
 
 
 class NgcError(RuntimeError):
@@ -117,6 +118,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_paged_decode_attn.restype = C.c_int
     lib.ngc_paged_score_keys.argtypes = [gp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_paged_score_keys.restype = C.c_int
+    lib.ngc_probe_stream.argtypes = [i32, vp, vp, sz, vp]
+    lib.ngc_probe_stream.restype = C.c_int
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -350,3 +353,7 @@ def ngc_paged_score_keys(pc: PagedCache, layer: int, q_recent, w: int, scale: fl
     _check(load_library().ngc_paged_score_keys(C.byref(v), layer, _ptr(q_recent), _ptr(lse_recent), w, scale, flags,
                                                block, _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
            "ngc_paged_score_keys")
+
+
+def ngc_probe_stream(kind: int, src, dst, nbytes: int, stream=None):
+    _check(load_library().ngc_probe_stream(kind, _ptr(src), _ptr(dst), nbytes, _stream(stream)), "ngc_probe_stream")
