@@ -29,6 +29,9 @@ constexpr int RP_WAVES = 4;
 constexpr int RP_QW = 32;                    // query positions per wave
 constexpr int RP_QT = RP_WAVES * RP_QW;      // query positions per workgroup
 constexpr int RP_KT = 32;                    // keys per tile
+// Start of the running max: finite and below every real score, so that 2^(x - m) is 0 for a masked
+// x = -inf without a special case, and the first rescale factor 2^(m_init - m_new) is 0.
+constexpr float RP_M_INIT = -1.0e30f;
 
 struct ReplayArgs {
     const unsigned char *q;    // bf16 [B][T][Hq][D]
@@ -37,6 +40,7 @@ struct ReplayArgs {
     const int32_t *death;      // [B][Hd][T]
     uint16_t *klist;           // [B*Hd][nqt][T] visible keys per query tile, ascending
     int32_t *kcount;           // [B*Hd][nqt]
+    int32_t *tile_death;       // [B*Hd][nqt][ceil(T/32)] smallest death among the keys of each 32-key list tile
     float *out;                // fp32 [B][T][Hq][D]
     int B, T, Hq, Hkv, Hd;     // Hd = Hkv (a death row per KV head) or 1 (shared by the heads)
     float scale_log2e;
@@ -73,6 +77,19 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_lists_kernel(ReplayArgs 
         __syncthreads();
     }
     if (tid == 0) a.kcount[(size_t)row * nqt + qt] = n_list;
+    // smallest death per list tile: a tile whose keys all outlive a wave's queries needs no per-element mask
+    // (the list writes above are this workgroup's own and the loop ended on a barrier)
+    const int tiles_max = (T + RP_KT - 1) / RP_KT;
+    int32_t *tmin = a.tile_death + ((size_t)row * nqt + qt) * tiles_max;
+    for (int t = tid; t * RP_KT < n_list; t += RP_WAVES * 64) {
+        const int s1 = (t + 1) * RP_KT < n_list ? (t + 1) * RP_KT : n_list;
+        int m = 0x7FFFFFFF;
+        for (int s = t * RP_KT; s < s1; ++s) {
+            const int d = death[klist[s]];
+            m = d < m ? d : m;
+        }
+        tmin[t] = m;
+    }
 }
 
 template <int D>
@@ -91,6 +108,7 @@ void replay_attn_kernel(ReplayArgs a)
     __shared__ __align__(16) unsigned char lds_v[2][TILE_LDS];
     __shared__ __align__(16) int32_t lds_death[2][RP_KT];
     __shared__ __align__(16) int32_t lds_kidx[2][RP_KT];
+    __shared__ int32_t lds_tmin[2];
 
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const int li = lane & 15, kg = lane >> 4;
@@ -124,7 +142,7 @@ void replay_attn_kernel(ReplayArgs a)
     float m_run[2], l_run[2];
 #pragma unroll
     for (int qa = 0; qa < 2; ++qa) {
-        m_run[qa] = -INFINITY;
+        m_run[qa] = RP_M_INIT;
         l_run[qa] = 0.f;
 #pragma unroll
         for (int c = 0; c < DPL; ++c) oacc[qa][c] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -138,29 +156,48 @@ void replay_attn_kernel(ReplayArgs a)
     const uint16_t *klist = a.klist + (((size_t)b * a.Hd + hd) * nqt + qt) * T;
     const int n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
     const int t_end = (n_list + RP_KT - 1) / RP_KT;
+    const int32_t *tmin = a.tile_death + (((size_t)b * a.Hd + hd) * nqt + qt) * ((T + RP_KT - 1) / RP_KT);
+    const int wave_q0 = i0 + wv * RP_QW;                               // first query position of this wave
+    const int wave_q1 = (wave_q0 + RP_QW - 1 < T - 1) ? wave_q0 + RP_QW - 1 : T - 1;   // last real one
 
-    // one tile in registers on its way from global memory to LDS
+    // One tile on its way from global memory to LDS, in two steps so that no load waits for another
+    // inside one step: first the list entries (which keys), one step later the rows they name.
+    struct IdxStage {
+        int key[LOADS];   // key index of the rows this thread copies
+        int mine;         // threads < RP_KT: the key of list slot s0 + tid (0x7FFFFFFF past the end)
+    };
     struct Stage {
         u32x4 k[LOADS], v[LOADS];
         int d, i;
+        int tmin;   // thread 0 only
     };
-    auto load_tile = [&](int t, Stage &st) {
+    auto load_idx = [&](int t, IdxStage &ix) {
         const int s0 = t * RP_KT;           // past the end every slot clamps to the last key: harmless re-reads
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
             int slot = s0 + piece_id / PIECES;
             slot = slot < n_list ? slot : n_list - 1;
-            const size_t off = (size_t)klist[slot] * kv_row + (piece_id % PIECES) * 16;
+            slot = slot < 0 ? 0 : slot;                 // an empty list (only with death[j] <= j, not a valid input)
+            const int key = (int)klist[slot];
+            ix.key[r] = key < T ? key : T - 1;          // whatever the list holds, stay inside k / v
+        }
+        ix.mine = 0x7FFFFFFF;               // a key no query comes after
+        if (tid < RP_KT && s0 + tid < n_list) ix.mine = (int)klist[s0 + tid];
+    };
+    auto load_rows = [&](int t, const IdxStage &ix, Stage &st) {
+#pragma unroll
+        for (int r = 0; r < LOADS; ++r) {
+            const int piece_id = r * (RP_WAVES * 64) + tid;
+            const size_t off = (size_t)ix.key[r] * kv_row + (piece_id % PIECES) * 16;
             st.k[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
             st.v[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
         }
+        st.tmin = 0;
+        if (tid == 0 && t < t_end) st.tmin = tmin[t];
+        st.i = ix.mine;
         st.d = 0;
-        st.i = 0x7FFFFFFF;                  // a key no query comes after
-        if (tid < RP_KT && s0 + tid < n_list) {
-            st.i = (int)klist[s0 + tid];
-            st.d = death[st.i];
-        }
+        if (ix.mine != 0x7FFFFFFF) st.d = death[ix.mine];
     };
     auto store_tile = [&](int buf, const Stage &st) {
 #pragma unroll
@@ -171,6 +208,7 @@ void replay_attn_kernel(ReplayArgs a)
             *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = st.v[r];
         }
         if (tid < RP_KT) { lds_death[buf][tid] = st.d; lds_kidx[buf][tid] = st.i; }
+        if (tid == 0) lds_tmin[buf] = st.tmin;
     };
 
     auto compute_tile = [&](int buf) {
@@ -186,8 +224,14 @@ void replay_attn_kernel(ReplayArgs a)
                 for (int c = 0; c < KCH; ++c)
                     kop[mt][c] = __builtin_bit_cast(
                         bf16x8, *reinterpret_cast<const u32x4 *>(lk + (mt * 16 + li) * LROW + c * 64 + kg * 16));
+            // A tile whose keys all precede this wave's first query and all outlive its last one needs no
+            // mask (wave-uniform, so the branches below do not diverge).
+            const bool full = __builtin_amdgcn_readfirstlane(
+                (lds_kidx[buf][RP_KT - 1] <= wave_q0 && lds_tmin[buf] > wave_q1) ? 1 : 0) != 0;
             int dk[8], jk[8];
-            {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { dk[e] = 0x7FFFFFFF; jk[e] = 0; }
+            if (!full) {
                 const int4 d0 = *reinterpret_cast<const int4 *>(&lds_death[buf][4 * kg]);
                 const int4 d1 = *reinterpret_cast<const int4 *>(&lds_death[buf][16 + 4 * kg]);
                 dk[0] = d0.x; dk[1] = d0.y; dk[2] = d0.z; dk[3] = d0.w;
@@ -211,7 +255,12 @@ void replay_attn_kernel(ReplayArgs a)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float sc = (e < 4) ? s0[e] : s1[e - 4];
-                    x[e] = (jk[e] <= qp && qp < dk[e]) ? sc * a.scale_log2e : -INFINITY;
+                    x[e] = sc * a.scale_log2e;
+                }
+                if (!full) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (!(jk[e] <= qp && qp < dk[e])) x[e] = -INFINITY;
                 }
                 float tmx = x[0];
 #pragma unroll
@@ -230,7 +279,7 @@ void replay_attn_kernel(ReplayArgs a)
                 float p[8], psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = (x[e] == -INFINITY) ? 0.f : fast_exp2(x[e] - m_run[qa]);
+                    p[e] = fast_exp2(x[e] - m_run[qa]);   // x = -inf gives 0: m_run is always finite
                     psum += p[e];
                 }
                 l_run[qa] += psum;
@@ -277,18 +326,23 @@ void replay_attn_kernel(ReplayArgs a)
         }
     };
 
-    // Three tiles are in play: tile t is computed from LDS, tile t+1 sits in registers (loaded one
-    // step ago, stored to the other LDS buffer after the math), tile t+2 is being loaded.  Unrolled by
-    // two so that the two register stages swap roles without copies; every load is unconditional so the
-    // number of loads in flight is the same on every path.
+    // Four tiles are in play: tile t is computed from LDS, tile t+1 sits in registers (loaded one step
+    // ago, stored to the other LDS buffer after the math), the rows of tile t+2 are being loaded, and so
+    // are the list entries of tile t+3.  Unrolled by two so that the register stages swap roles without
+    // copies; every load is unconditional so the number of loads in flight is the same on every path.
     Stage st_a, st_b;
-    load_tile(0, st_a);
+    IdxStage ix_a, ix_b;
+    load_idx(0, ix_a);
+    load_idx(1, ix_b);
+    load_rows(0, ix_a, st_a);
+    load_idx(2, ix_a);
     store_tile(0, st_a);
-    load_tile(1, st_a);
+    load_rows(1, ix_b, st_a);
     __syncthreads();
     int t = 0, buf = 0;
     while (t < t_end) {
-        load_tile(t + 2, st_b);
+        load_idx(t + 3, ix_b);
+        load_rows(t + 2, ix_a, st_b);
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(buf);
         __builtin_amdgcn_sched_barrier(0);
@@ -296,7 +350,8 @@ void replay_attn_kernel(ReplayArgs a)
         __syncthreads();
         buf ^= 1;
         if (++t >= t_end) break;
-        load_tile(t + 2, st_a);
+        load_idx(t + 3, ix_a);
+        load_rows(t + 2, ix_b, st_a);
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(buf);
         __builtin_amdgcn_sched_barrier(0);
@@ -339,7 +394,10 @@ extern "C" size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv)
     const size_t nqt = (size_t)(T + RP_QT - 1) / RP_QT;
     size_t lists = (size_t)B * Hkv * nqt * T * sizeof(uint16_t);
     lists = (lists + 255) & ~(size_t)255;
-    return 256 + lists + (size_t)B * Hkv * nqt * sizeof(int32_t);
+    size_t counts = (size_t)B * Hkv * nqt * sizeof(int32_t);
+    counts = (counts + 255) & ~(size_t)255;
+    const size_t tiles_max = (size_t)(T + RP_KT - 1) / RP_KT;
+    return 256 + lists + counts + (size_t)B * Hkv * nqt * tiles_max * sizeof(int32_t);
 }
 
 extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *death,
@@ -371,6 +429,9 @@ extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, cons
     lists = (lists + 255) & ~(size_t)255;
     ra.klist = reinterpret_cast<uint16_t *>(reinterpret_cast<unsigned char *>(ws) + 256);
     ra.kcount = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) + 256 + lists);
+    size_t counts = (size_t)B * ra.Hd * nqt * sizeof(int32_t);
+    counts = (counts + 255) & ~(size_t)255;
+    ra.tile_death = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) + 256 + lists + counts);
     hipLaunchKernelGGL(replay_lists_kernel, dim3(nqt, B * ra.Hd), dim3(RP_WAVES * 64), 0, st, ra);
     NGC_HIP_CHECK(hipGetLastError());
     if (D == 128)
