@@ -28,7 +28,8 @@ namespace ngc {
 constexpr int RP_WAVES = 4;
 constexpr int RP_QW = 32;                    // query positions per wave
 constexpr int RP_QT = RP_WAVES * RP_QW;      // query positions per workgroup
-constexpr int RP_KT = 32;                    // keys per tile
+constexpr int RP_KT = 64;                    // keys per LDS tile (one barrier per tile)
+constexpr int RP_MT = 32;                    // keys per step of the math (and per entry of tile_death)
 // Start of the running max: finite and below every real score, so that 2^(x - m) is 0 for a masked
 // x = -inf without a special case, and the first rescale factor 2^(m_init - m_new) is 0.
 constexpr float RP_M_INIT = -1.0e30f;
@@ -40,7 +41,7 @@ struct ReplayArgs {
     const int32_t *death;      // [B][Hd][T]
     uint16_t *klist;           // [B*Hd][nqt][T] visible keys per query tile, ascending
     int32_t *kcount;           // [B*Hd][nqt]
-    int32_t *tile_death;       // [B*Hd][nqt][ceil(T/32)] smallest death among the keys of each 32-key list tile
+    int32_t *tile_death;       // [B*Hd][nqt][ceil(T/32)] smallest death among each RP_MT keys of a list
     float *out;                // fp32 [B][T][Hq][D]
     int B, T, Hq, Hkv, Hd;     // Hd = Hkv (a death row per KV head) or 1 (shared by the heads)
     float scale_log2e;
@@ -79,12 +80,12 @@ __global__ __launch_bounds__(RP_WAVES * 64) void replay_lists_kernel(ReplayArgs 
     if (tid == 0) a.kcount[(size_t)row * nqt + qt] = n_list;
     // smallest death per list tile: a tile whose keys all outlive a wave's queries needs no per-element mask
     // (the list writes above are this workgroup's own and the loop ended on a barrier)
-    const int tiles_max = (T + RP_KT - 1) / RP_KT;
+    const int tiles_max = (T + RP_MT - 1) / RP_MT;
     int32_t *tmin = a.tile_death + ((size_t)row * nqt + qt) * tiles_max;
-    for (int t = tid; t * RP_KT < n_list; t += RP_WAVES * 64) {
-        const int s1 = (t + 1) * RP_KT < n_list ? (t + 1) * RP_KT : n_list;
+    for (int t = tid; t * RP_MT < n_list; t += RP_WAVES * 64) {
+        const int s1 = (t + 1) * RP_MT < n_list ? (t + 1) * RP_MT : n_list;
         int m = 0x7FFFFFFF;
-        for (int s = t * RP_KT; s < s1; ++s) {
+        for (int s = t * RP_MT; s < s1; ++s) {
             const int d = death[klist[s]];
             m = d < m ? d : m;
         }
@@ -108,7 +109,7 @@ void replay_attn_kernel(ReplayArgs a)
     __shared__ __align__(16) unsigned char lds_v[2][TILE_LDS];
     __shared__ __align__(16) int32_t lds_death[2][RP_KT];
     __shared__ __align__(16) int32_t lds_kidx[2][RP_KT];
-    __shared__ int32_t lds_tmin[2];
+    __shared__ int32_t lds_tmin[2][RP_KT / RP_MT];
 
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const int li = lane & 15, kg = lane >> 4;
@@ -156,7 +157,7 @@ void replay_attn_kernel(ReplayArgs a)
     const uint16_t *klist = a.klist + (((size_t)b * a.Hd + hd) * nqt + qt) * T;
     const int n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
     const int t_end = (n_list + RP_KT - 1) / RP_KT;
-    const int32_t *tmin = a.tile_death + (((size_t)b * a.Hd + hd) * nqt + qt) * ((T + RP_KT - 1) / RP_KT);
+    const int32_t *tmin = a.tile_death + (((size_t)b * a.Hd + hd) * nqt + qt) * ((T + RP_MT - 1) / RP_MT);
     const int wave_q0 = i0 + wv * RP_QW;                               // first query position of this wave
     const int wave_q1 = (wave_q0 + RP_QW - 1 < T - 1) ? wave_q0 + RP_QW - 1 : T - 1;   // last real one
 
@@ -169,7 +170,7 @@ void replay_attn_kernel(ReplayArgs a)
     struct Stage {
         u32x4 k[LOADS], v[LOADS];
         int d, i;
-        int tmin;   // thread 0 only
+        int tmin;   // threads < RP_KT / RP_MT only
     };
     auto load_idx = [&](int t, IdxStage &ix) {
         const int s0 = t * RP_KT;           // past the end every slot clamps to the last key: harmless re-reads
@@ -194,7 +195,7 @@ void replay_attn_kernel(ReplayArgs a)
             st.v[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
         }
         st.tmin = 0;
-        if (tid == 0 && t < t_end) st.tmin = tmin[t];
+        if (tid < RP_KT / RP_MT && (t * (RP_KT / RP_MT) + tid) * RP_MT < n_list) st.tmin = tmin[t * (RP_KT / RP_MT) + tid];
         st.i = ix.mine;
         st.d = 0;
         if (ix.mine != 0x7FFFFFFF) st.d = death[ix.mine];
@@ -208,14 +209,17 @@ void replay_attn_kernel(ReplayArgs a)
             *reinterpret_cast<u32x4 *>(lds_v[buf] + off) = st.v[r];
         }
         if (tid < RP_KT) { lds_death[buf][tid] = st.d; lds_kidx[buf][tid] = st.i; }
-        if (tid == 0) lds_tmin[buf] = st.tmin;
+        if (tid < RP_KT / RP_MT) lds_tmin[buf][tid] = st.tmin;
     };
 
     auto compute_tile = [&](int buf) {
-        // ---- this tile, from LDS ---------------------------------------------
-        const unsigned char *lk = lds_k[buf], *lv = lds_v[buf];
-        // the list ascends: if its first key of this tile is after this wave's last query, so are all
-        const bool wave_needs = (lds_kidx[buf][0] <= i0 + wv * RP_QW + RP_QW - 1);
+#pragma unroll
+      for (int half = 0; half < RP_KT / RP_MT; ++half) {
+        // ---- RP_MT keys of this tile, from LDS --------------------------------
+        const unsigned char *lk = lds_k[buf] + half * RP_MT * LROW, *lv = lds_v[buf] + half * RP_MT * LROW;
+        const int32_t *ldeath = &lds_death[buf][half * RP_MT], *lkidx = &lds_kidx[buf][half * RP_MT];
+        // the list ascends: if the first of these keys is after this wave's last query, so are all
+        const bool wave_needs = (lkidx[0] <= i0 + wv * RP_QW + RP_QW - 1);
         if (wave_needs) {
             bf16x8 kop[2][KCH];
 #pragma unroll
@@ -227,17 +231,17 @@ void replay_attn_kernel(ReplayArgs a)
             // A tile whose keys all precede this wave's first query and all outlive its last one needs no
             // mask (wave-uniform, so the branches below do not diverge).
             const bool full = __builtin_amdgcn_readfirstlane(
-                (lds_kidx[buf][RP_KT - 1] <= wave_q0 && lds_tmin[buf] > wave_q1) ? 1 : 0) != 0;
+                (lkidx[RP_MT - 1] <= wave_q0 && lds_tmin[buf][half] > wave_q1) ? 1 : 0) != 0;
             int dk[8], jk[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { dk[e] = 0x7FFFFFFF; jk[e] = 0; }
             if (!full) {
-                const int4 d0 = *reinterpret_cast<const int4 *>(&lds_death[buf][4 * kg]);
-                const int4 d1 = *reinterpret_cast<const int4 *>(&lds_death[buf][16 + 4 * kg]);
+                const int4 d0 = *reinterpret_cast<const int4 *>(&ldeath[4 * kg]);
+                const int4 d1 = *reinterpret_cast<const int4 *>(&ldeath[16 + 4 * kg]);
                 dk[0] = d0.x; dk[1] = d0.y; dk[2] = d0.z; dk[3] = d0.w;
                 dk[4] = d1.x; dk[5] = d1.y; dk[6] = d1.z; dk[7] = d1.w;
-                const int4 j0v = *reinterpret_cast<const int4 *>(&lds_kidx[buf][4 * kg]);
-                const int4 j1v = *reinterpret_cast<const int4 *>(&lds_kidx[buf][16 + 4 * kg]);
+                const int4 j0v = *reinterpret_cast<const int4 *>(&lkidx[4 * kg]);
+                const int4 j1v = *reinterpret_cast<const int4 *>(&lkidx[16 + 4 * kg]);
                 jk[0] = j0v.x; jk[1] = j0v.y; jk[2] = j0v.z; jk[3] = j0v.w;
                 jk[4] = j1v.x; jk[5] = j1v.y; jk[6] = j1v.z; jk[7] = j1v.w;
             }
@@ -324,38 +328,37 @@ void replay_attn_kernel(ReplayArgs a)
                 }
             }
         }
+      }
     };
 
-    // Four tiles are in play: tile t is computed from LDS, tile t+1 sits in registers (loaded one step
-    // ago, stored to the other LDS buffer after the math), the rows of tile t+2 are being loaded, and so
-    // are the list entries of tile t+3.  Unrolled by two so that the register stages swap roles without
-    // copies; every load is unconditional so the number of loads in flight is the same on every path.
-    Stage st_a, st_b;
+    // Per step: tile t is computed from LDS while the rows of tile t+1 travel through registers into
+    // the other LDS buffer and the list entries of tile t+2 are fetched.  Unrolled by two so that the two
+    // list-entry stages swap roles without copies; every load is unconditional so the number of loads in
+    // flight is the same on every path.
+    Stage st;
     IdxStage ix_a, ix_b;
     load_idx(0, ix_a);
     load_idx(1, ix_b);
-    load_rows(0, ix_a, st_a);
-    load_idx(2, ix_a);
-    store_tile(0, st_a);
-    load_rows(1, ix_b, st_a);
+    load_rows(0, ix_a, st);
+    store_tile(0, st);
     __syncthreads();
     int t = 0, buf = 0;
     while (t < t_end) {
-        load_idx(t + 3, ix_b);
-        load_rows(t + 2, ix_a, st_b);
+        load_idx(t + 2, ix_a);
+        load_rows(t + 1, ix_b, st);
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(buf);
         __builtin_amdgcn_sched_barrier(0);
-        store_tile(buf ^ 1, st_a);
+        store_tile(buf ^ 1, st);
         __syncthreads();
         buf ^= 1;
         if (++t >= t_end) break;
-        load_idx(t + 3, ix_a);
-        load_rows(t + 2, ix_b, st_a);
+        load_idx(t + 2, ix_b);
+        load_rows(t + 1, ix_a, st);
         __builtin_amdgcn_sched_barrier(0);
         compute_tile(buf);
         __builtin_amdgcn_sched_barrier(0);
-        store_tile(buf ^ 1, st_b);
+        store_tile(buf ^ 1, st);
         __syncthreads();
         buf ^= 1;
         ++t;
@@ -396,7 +399,7 @@ extern "C" size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv)
     lists = (lists + 255) & ~(size_t)255;
     size_t counts = (size_t)B * Hkv * nqt * sizeof(int32_t);
     counts = (counts + 255) & ~(size_t)255;
-    const size_t tiles_max = (size_t)(T + RP_KT - 1) / RP_KT;
+    const size_t tiles_max = (size_t)(T + RP_MT - 1) / RP_MT;
     return 256 + lists + counts + (size_t)B * Hkv * nqt * tiles_max * sizeof(int32_t);
 }
 
