@@ -518,3 +518,88 @@ def test_full_size_paged_sampled_segments():
     everything = torch.cat([used, pc.free_stack[:count_d]]).sort().values
     assert torch.equal(everything, torch.arange(num_pages, dtype=torch.int32, device="cuda"))
     assert bool(torch.isfinite(out).all())
+
+
+def test_degenerate_segments_and_rounds():
+    """Empty, one-row, exactly-one-page and completely full segments; rounds that keep everything, nothing, or
+    ask for more than there is (clamped and counted); appends into empty and into full segments."""
+    import torch
+    ngc = _ngc()
+    P, max_pages, D = 32, 4, 64
+    wl = synth.workload(0, L=1, B=4, D=D, n_lo=1, n_hi=1)             # shapes only: Hq 8, Hkv 2
+    nseg = wl.B * wl.Hkv
+    lens = [0, 1, P, P * max_pages, P + 5, 0, 2 * P, 3 * P - 1]
+    rng = np.random.default_rng(31)
+    m = orc.PagedCache(nseg, P, max_pages, 40, D)
+    m.free_stack[:] = rng.permutation(40).astype(np.int32)
+    for s, n in enumerate(lens):
+        for p in range((n + P - 1) // P):
+            m.free_count -= 1
+            m.table[s, p] = m.free_stack[m.free_count]
+            rows = min(P, n - p * P)
+            m.k_pool[m.table[s, p], :rows] = synth.f32_to_bf16_bits(rng.standard_normal((rows, D), dtype=np.float32))
+            m.v_pool[m.table[s, p], :rows] = synth.f32_to_bf16_bits(rng.standard_normal((rows, D), dtype=np.float32))
+        m.len[s] = n
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    check_attention(pc, m, wl, ws, -1, 1, lse=False)                    # two empty segments: zeros, counted
+    st = ngc.read_status(ws)
+    assert st[ngc.STATUS_EMPTY_ATTN] == 2
+
+    def round_with(keep_list, rnd):
+        logits = torch.from_numpy(rng.standard_normal((nseg, max_pages)).astype(np.float32)).cuda()
+        keep = torch.tensor(keep_list, dtype=torch.int32, device="cuda")
+        max_keep = max(1, max(keep_list))
+        kept = torch.full((nseg, max_keep), -1, dtype=torch.int32, device="cuda")
+        sigma = torch.full_like(kept, -1)
+        logp = torch.full((nseg,), 7.0, dtype=torch.float32, device="cuda")
+        ngc.ngc_paged_evict(pc, -1, logits, max_pages, keep, ngc.make_params(block=P, noise_scale=1.0, round=rnd, seed=5),
+                            max_keep, kept, sigma, logp, ws)
+        torch.cuda.synchronize()
+        hl, hk, hs, hp = logits.cpu().numpy(), kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy()
+        lists = []
+        for s in range(nseg):
+            N = m.pages_in_use(s)
+            K = max(0, min(keep_list[s], N))
+            b, h = divmod(s, wl.Hkv)
+            okept, osig = orc.evict_select(hl[s, :N], K, 1.0, 5, rnd, 0, b, h)
+            assert hk[s, :K].tolist() == okept.tolist() and hs[s, :K].tolist() == osig.tolist(), s
+            want = oracle_logprob(hl[s, :N], osig) if K else 0.0
+            assert abs(hp[s] - want) <= LOGP_RTOL * max(1.0, abs(want)), s
+            lists.append(okept.tolist())
+        m.evict(range(nseg), lists)
+        assert_same_state(pc, m, wl, f"round {rnd}")
+
+    before = ngc.read_status(ws)[ngc.STATUS_KEEP_CLAMPED]
+    round_with([m.pages_in_use(s) for s in range(nseg)], 0)            # keep everything: nothing changes
+    assert ngc.read_status(ws)[ngc.STATUS_KEEP_CLAMPED] == before
+    round_with([m.pages_in_use(s) + 3 for s in range(nseg)], 1)        # more than there is: clamped, counted
+    assert ngc.read_status(ws)[ngc.STATUS_KEEP_CLAMPED] == before + nseg
+    assert append_step(pc, m, wl, ws, 0) == [3]                        # the full segment cannot grow
+    assert_same_state(pc, m, wl, "append into empty and full segments")
+    round_with([1, 0, 1, 2, 1, 1, 0, 2], 2)                            # some segments evict everything
+    check_attention(pc, m, wl, ws, -1, 2)
+    for step in range(1, 4):
+        append_step(pc, m, wl, ws, step)
+    assert_same_state(pc, m, wl, "regrowth")
+    check_attention(pc, m, wl, ws, 0, 3)
+
+
+def test_large_pages():
+    # pages of 256 rows (8 tiles per page), D = 64
+    ngc = _ngc()
+    wl = synth.workload(1, L=1, B=3, D=64, n_lo=300, n_hi=2000)
+    case = host_case(wl)
+    P = 256
+    max_pages = wl.cap // P + 2
+    m = build_model(case, P, max_pages, wl.B * wl.Hkv * max_pages, seed=41)
+    pc = upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    check_attention(pc, m, wl, ws, -1, 1, lse=True)
+    run_round(pc, m, wl, ws, 0, lambda N: max(1, N - 2))
+    assert_same_state(pc, m, wl, "large pages, round 0")
+    for step in range(3):
+        assert append_step(pc, m, wl, ws, step) == []
+    assert_same_state(pc, m, wl, "large pages, appends")
+    check_attention(pc, m, wl, ws, -1, 2)
+    assert all(x == 0 for x in ngc.read_status(ws))
