@@ -174,6 +174,46 @@ def logprob_grad(logits, sigma) -> np.ndarray:
     return g[:s.size]
 
 
+# ----------------------------------------------- eviction loss (Eq. 4) ------
+
+def advantages(reward, group: int) -> np.ndarray:
+    """A_i = r_i - mean of r over the rollouts of the same prompt (groups of `group` consecutive rollouts)."""
+    r = np.asarray(reward, np.float64)
+    assert r.size % group == 0
+    out = np.zeros_like(r)
+    for g0 in range(0, r.size, group):
+        out[g0:g0 + group] = r[g0:g0 + group] - r[g0:g0 + group].sum() / group
+    return out
+
+
+def lmem(logp, rounds, reward, group: int):
+    """Eq. 4 written out.  logp: [R, L, B, H] log-probabilities of the eviction decisions (round, layer,
+    rollout, KV head: the decision of a layer is the joint one over its heads, so their log-probabilities
+    add); rounds[i] = number of rounds that fired for rollout i.  The expectation is the mean over the
+    prompts of the batch.  Returns (per-layer losses [L], total loss)."""
+    lp = np.asarray(logp, np.float64)
+    R, L, B, H = lp.shape
+    adv = advantages(reward, group)
+    prompts = B // group
+    per_layer = np.zeros(L, np.float64)
+    for l in range(L):
+        acc = 0.0
+        for p in range(prompts):
+            inner = 0.0
+            for i in range(p * group, (p + 1) * group):
+                n = int(rounds[i])
+                if n == 0:
+                    continue
+                mean_rounds = 0.0
+                for t in range(n):
+                    for h in range(H):
+                        mean_rounds += lp[t, l, i, h]
+                inner += (mean_rounds / n) * adv[i]
+            acc += inner / group
+        per_layer[l] = -acc / prompts
+    return per_layer, float(per_layer.sum())
+
+
 # ------------------------------------------------------------ compaction --
 
 def compact_rows(rows_u16, kept, block: int = 1) -> np.ndarray:

@@ -147,3 +147,48 @@ def test_gradient_invariants():
     assert np.abs(g1 - want).max() < 1e-14
     # the last pick of a full permutation has zero gradient contribution beyond itself
     assert orc.logprob_grad(s[:5], [0, 1, 2, 3, 4]).sum() == pytest.approx(0.0, abs=1e-12)
+
+
+# ------------------------------------------------ eviction loss (Eq. 4) ----
+
+def test_lmem_by_hand():
+    # one layer, one head, one prompt of two rollouts: rewards 1 and 0 -> advantages +1/2, -1/2.
+    # rollout 0 fired two rounds (log-probs -1, -3), rollout 1 one round (-4; its second entry is unused)
+    lp = np.array([[[[-1.0], [-4.0]]], [[[-3.0], [99.0]]]])          # [R=2, L=1, B=2, H=1]
+    per_layer, total = orc.lmem(lp, [2, 1], [1.0, 0.0], group=2)
+    want = -0.5 * (((-1.0 - 3.0) / 2) * 0.5 + (-4.0) * (-0.5))       # -(1/G) sum_i mean_t(logp) * A_i
+    assert per_layer.tolist() == pytest.approx([want]) and total == pytest.approx(want)
+    assert want == pytest.approx(-0.5)
+
+
+def test_lmem_invariants():
+    rng = np.random.default_rng(16)
+    R, L, B, H, G = 5, 3, 8, 2, 4
+    lp = -10.0 * rng.random((R, L, B, H))
+    rounds = rng.integers(0, R + 1, size=B)
+    rounds[0] = 0                                                    # a rollout that ended before its first round
+    reward = rng.integers(0, 2, size=B).astype(np.float64)
+    per_layer, total = orc.lmem(lp, rounds, reward, G)
+    assert total == pytest.approx(per_layer.sum())
+    # advantages are centred per prompt: a bonus to every rollout of a prompt changes nothing
+    shifted = reward.copy()
+    shifted[:G] += 3.0
+    assert orc.lmem(lp, rounds, shifted, G)[1] == pytest.approx(total, abs=1e-12)
+    assert orc.advantages(reward, G).reshape(-1, G).sum(axis=1) == pytest.approx(np.zeros(B // G), abs=1e-15)
+    # equal rewards: no signal
+    assert orc.lmem(lp, rounds, np.ones(B), G)[1] == 0.0
+    # entries of rounds that never fired do not matter
+    junk = lp.copy()
+    for i in range(B):
+        junk[rounds[i]:, :, i, :] = 1e6
+    assert orc.lmem(junk, rounds, reward, G)[1] == pytest.approx(total, abs=1e-12)
+    # the loss is linear in the log-probabilities: d loss / d logp[t, l, i, h] = -A_i / (B * rounds_i)
+    adv = orc.advantages(reward, G)
+    t, l, i, h = 1, 2, int(np.flatnonzero(rounds >= 2)[0]), 1
+    bumped = lp.copy()
+    bumped[t, l, i, h] += 1.0
+    assert orc.lmem(bumped, rounds, reward, G)[1] - total == pytest.approx(-adv[i] / (B * rounds[i]), abs=1e-12)
+    # vectorised numpy evaluation of the same formula
+    w = np.where(np.arange(R)[:, None] < rounds[None, :], 1.0 / np.maximum(rounds, 1)[None, :], 0.0)   # [R, B]
+    want = -(lp * w[:, None, :, None] * adv[None, None, :, None]).sum(axis=(0, 2, 3)) / B
+    assert per_layer == pytest.approx(want, abs=1e-12)
