@@ -469,6 +469,25 @@ def main():
         bwd = {"what": "ngc_subset_logprob_backward for every segment of the round (n = budget + delta)",
                "us": bw_us, "bytes": bw_bytes, "hbm_frac": bw_bytes / (bw_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
         del grad
+        # Eq. 4 itself: loss, advantages and the weights of 8 rounds' log-probabilities (latency bound: tiny)
+        R_l, G_l = 8, min(16, w.B)
+        lp_all = -1000.0 * torch.rand(R_l, w.L, w.B, w.Hkv, generator=g, device=dev)
+        rounds_l = torch.randint(1, R_l + 1, (w.B,), generator=g, device=dev, dtype=torch.int32)
+        reward_l = torch.randint(0, 2, (w.B,), generator=g, device=dev).to(torch.float32)
+        loss_layer = torch.empty(w.L, dtype=torch.float32, device=dev)
+        loss_l = torch.empty(1, dtype=torch.float32, device=dev)
+        gout_l = torch.empty_like(lp_all)
+        lm_ms = []
+        for rep in range(4):
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            ngc.ngc_lmem(lp_all, rounds_l, reward_l, R_l, w.L, w.B, w.Hkv, G_l, None, loss_layer, loss_l, gout_l)
+            e1.record()
+            torch.cuda.synchronize()
+            lm_ms.append(e0.elapsed_time(e1))
+        bwd["lmem_us"] = 1e3 * float(np.mean(lm_ms[1:]))
+        bwd["lmem_what"] = f"ngc_lmem: Eq. 4 over {R_l} rounds x {w.L} layers x {w.B} rollouts x {w.Hkv} heads, groups of {G_l}"
 
     # ---- config 4, other reading: one budget per sequence pooled over its KV heads
     pooled = None

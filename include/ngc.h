@@ -11,6 +11,8 @@
  *                        of everything else                  (Sec. 4.1, 4.3, Eq. 2)
  *   ngc_subset_logprob   Eq. 2 for caller-supplied sampled actions (Sec. 4.3-4.4)
  *   ngc_subset_logprob_backward  its gradient w.r.t. the logits (Eq. 4)
+ *   ngc_lmem             the eviction loss of Eq. 4 and the weights it puts on
+ *                        every round's log-probability             (Sec. 4.4)
  *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
@@ -203,6 +205,26 @@ int ngc_subset_logprob_backward(const float *logits, const int32_t *n_items,
                                 int64_t logit_stride, int32_t sigma_stride, int32_t max_keep,
                                 const float *gout, float *grad_out,
                                 void *ws, size_t ws_bytes, void *stream);
+
+/* The eviction loss of Eq. 4 and its derivative with respect to every
+ * log-probability that enters it:
+ *     A_i   = reward[i] - mean of reward over the `group` rollouts of i's prompt
+ *             (rollouts of a prompt are consecutive; B is a multiple of group),
+ *     L^l   = -(1/B) sum_i A_i (1/n_i) sum_{t < n_i} sum_h logp[t][l][i][h],   n_i = rounds[i]
+ *             (mean over a rollout's rounds, over the rollouts of a prompt and
+ *             over the prompts of the batch; a layer's decision is the joint one
+ *             of its KV heads, whose log-probabilities add; n_i == 0 adds nothing),
+ *     loss  = sum_l L^l,
+ *     gout[t][l][i][h] = d loss / d logp[t][l][i][h] = -A_i / (B n_i)  for t < n_i, else 0
+ *             -- round t's slice gout[t] is what ngc_subset_logprob_backward takes.
+ *   logp        fp32 [R][L][B][Hkv]  log-probabilities as ngc_evict wrote them, round by round
+ *   rounds      int32 [B], clamped to [0, R]
+ *   reward      fp32 [B]
+ *   adv_out     fp32 [B] or NULL;  loss_layer fp32 [L];  loss fp32 [1];  gout as logp, or NULL
+ * Accumulation is fp64 in a fixed order (same inputs, same bits).  B <= 8192. */
+int ngc_lmem(const float *logp, const int32_t *rounds, const float *reward,
+             int32_t R, int32_t L, int32_t B, int32_t Hkv, int32_t group,
+             float *adv_out, float *loss_layer, float *loss, float *gout, void *stream);
 
 /* Append one new row per (sequence, head) of `layer` (-1 = all layers) at row
  * len and add 1 to len (Sec. 4.1: between rounds the cache grows as usual).

@@ -38,7 +38,7 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
-           "ngc_paged_score_keys", "ngc_probe_stream")
+           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem")
 PROBE_READ, PROBE_COPY, PROBE_READ_NT, PROBE_COPY_NT = 0, 1, 2, 3
 
 
@@ -118,6 +118,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_paged_decode_attn.restype = C.c_int
     lib.ngc_paged_score_keys.argtypes = [gp, i32, vp, vp, i32, f32, C.c_uint32, i32, vp, vp, sz, vp]
     lib.ngc_paged_score_keys.restype = C.c_int
+    lib.ngc_lmem.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.ngc_lmem.restype = C.c_int
     lib.ngc_probe_stream.argtypes = [i32, vp, vp, sz, vp]
     lib.ngc_probe_stream.restype = C.c_int
     if path == LIB_PATH:
@@ -357,3 +359,9 @@ def ngc_paged_score_keys(pc: PagedCache, layer: int, q_recent, w: int, scale: fl
 
 def ngc_probe_stream(kind: int, src, dst, nbytes: int, stream=None):
     _check(load_library().ngc_probe_stream(kind, _ptr(src), _ptr(dst), nbytes, _stream(stream)), "ngc_probe_stream")
+
+
+def ngc_lmem(logp, rounds, reward, R: int, L: int, B: int, Hkv: int, group: int, adv_out, loss_layer, loss,
+             gout, stream=None):
+    _check(load_library().ngc_lmem(_ptr(logp), _ptr(rounds), _ptr(reward), R, L, B, Hkv, group, _ptr(adv_out),
+                                   _ptr(loss_layer), _ptr(loss), _ptr(gout), _stream(stream)), "ngc_lmem")

@@ -243,6 +243,75 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(Logpro
     }
 }
 
+// ------------------------------------------- eviction loss (Eq. 4) --------
+//
+// L^l = -(1/P) sum_prompts (1/G) sum_{i in prompt} A_i (1/n_i) sum_{t < n_i} sum_h logp[t][l][i][h],
+// A_i = r_i - mean of r over the G rollouts of the prompt, n_i = rounds that fired for rollout i.
+// One workgroup per layer; advantages and 1/n_i in LDS; fp64 accumulation in a fixed order (the
+// advantages of a prompt sum to zero, so the terms cancel heavily).  Also writes d loss / d logp,
+// the upstream weights of subset_logprob_backward_kernel.
+
+struct LmemArgs {
+    const float *logp;     // [R][L][B][H]
+    const int32_t *rounds; // [B]
+    const float *reward;   // [B]
+    float *adv_out;        // [B] or nullptr
+    float *loss_layer;     // [L]
+    float *gout;           // [R][L][B][H] or nullptr
+    int R, L, B, H, group;
+};
+
+constexpr int LMEM_THREADS = 256;
+constexpr int LMEM_MAX_B = 8192;
+
+__global__ __launch_bounds__(LMEM_THREADS) void lmem_layer_kernel(LmemArgs a)
+{
+    __shared__ float weight[LMEM_MAX_B];      // A_i / n_i (0 when no round fired)
+    __shared__ int nrounds[LMEM_MAX_B];
+    __shared__ double red[LMEM_THREADS];
+    const int l = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < a.B; i += LMEM_THREADS) {
+        const int g0 = (i / a.group) * a.group;
+        double mean = 0.0;
+        for (int j = 0; j < a.group; ++j) mean += (double)a.reward[g0 + j];
+        mean /= (double)a.group;
+        const double adv = (double)a.reward[i] - mean;
+        int n = a.rounds[i];
+        n = n < 0 ? 0 : (n > a.R ? a.R : n);
+        nrounds[i] = n;
+        weight[i] = n > 0 ? (float)(adv / (double)n) : 0.f;
+        if (l == 0 && a.adv_out) a.adv_out[i] = (float)adv;
+    }
+    __syncthreads();
+    const int BH = a.B * a.H;
+    double acc = 0.0;
+    for (int t = 0; t < a.R; ++t) {
+        const size_t base = ((size_t)t * a.L + l) * BH;
+        for (int e = tid; e < BH; e += LMEM_THREADS) {
+            const int i = e / a.H;
+            const bool live = t < nrounds[i];
+            if (live) acc += (double)a.logp[base + e] * (double)weight[i];
+            if (a.gout) a.gout[base + e] = live ? -weight[i] / (float)a.B : 0.f;
+        }
+    }
+    red[tid] = acc;
+    __syncthreads();
+    for (int s = LMEM_THREADS / 2; s > 0; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) a.loss_layer[l] = (float)(-red[0] / (double)a.B);
+}
+
+__global__ void lmem_total_kernel(const float *loss_layer, int L, float *loss)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double s = 0.0;
+        for (int l = 0; l < L; ++l) s += (double)loss_layer[l];
+        *loss = (float)s;
+    }
+}
+
 // --------------------------------------------------------- compaction -----
 //
 // In place: the row that ends at slot j comes from a slot >= j, so a
@@ -952,6 +1021,22 @@ extern "C" int ngc_cache_append(const ngc_cache *c, int32_t layer, const void *k
         hipLaunchKernelGGL(append_kernel<256>, dim3(nseg), dim3(64), 0, (hipStream_t)stream, aa);
     else
         hipLaunchKernelGGL(append_kernel<128>, dim3(nseg), dim3(64), 0, (hipStream_t)stream, aa);
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_lmem(const float *logp, const int32_t *rounds, const float *reward,
+                        int32_t R, int32_t L, int32_t B, int32_t Hkv, int32_t group,
+                        float *adv_out, float *loss_layer, float *loss, float *gout, void *stream)
+{
+    if (!logp || !rounds || !reward || !loss_layer || !loss) return NGC_EINVAL;
+    if (R < 1 || L < 1 || B < 1 || Hkv < 1 || group < 1 || B % group != 0) return NGC_EINVAL;
+    if (B > LMEM_MAX_B) return NGC_EUNSUPPORTED;
+    LmemArgs la{logp, rounds, reward, adv_out, loss_layer, gout, R, L, B, Hkv, group};
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(lmem_layer_kernel, dim3(L), dim3(LMEM_THREADS), 0, st, la);
+    NGC_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(lmem_total_kernel, dim3(1), dim3(64), 0, st, (const float *)loss_layer, (int)L, loss);
     NGC_HIP_CHECK(hipGetLastError());
     return NGC_OK;
 }
