@@ -8,9 +8,11 @@ sample + ordered-subset log-probability + in-place compaction, all layers)
 that brings every segment back to its budget.  Inputs are synthetic, seeded,
 and resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see the design doc for every field).  `value` is tokens/s of
-the whole cycle; the attention-only rate, the round-0 eviction time at peak
-cache and the roofline fractions are reported beside it.
+Prints ONE JSON line.  `value` is tokens/s of the whole cycle; the
+attention-only rate, the round-0 eviction time at peak cache, the roofline
+fractions (against the 8 TB/s vendor figure and against read / copy ceilings
+measured in the same job), the other entry points' timings, the same cycle
+over the paged layout and the CPU oracle's rate are reported beside it.
 """
 from __future__ import annotations
 
@@ -165,7 +167,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; every rollout is independent, so more GPUs would only "
-              "replicate this run on disjoint sequences (see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+              "replicate this run on disjoint sequences. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2604_18002_amd import binding as ngc
