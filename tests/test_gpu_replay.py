@@ -134,3 +134,31 @@ def test_replay_equals_the_rollout():
     assert all(x == 0 for x in ngc.read_status(ws))
     got = _run(q, k, v, death.cpu().numpy(), Hq, Hkv, D, True, scale)
     assert np.abs(got - outs.cpu().numpy()).max() <= 5e-5
+
+
+def _sweep_cases():
+    rng = np.random.default_rng(4518002)
+    out = []
+    for i in range(14):
+        Hkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 4, 6, 7]))
+        out.append(dict(i=i, T=int(rng.choice([1, 31, 64, 65, 127, 129, 257, 500, 777, 1025])), Hkv=Hkv, Hq=Hkv * G,
+                        D=int(rng.choice([64, 128])), period=int(rng.choice([16, 50, 128, 350])),
+                        keep=float(rng.choice([0.1, 0.5, 0.9])), per_head=bool(rng.integers(0, 2)),
+                        block=int(rng.choice([1, 1, 32])), B=int(rng.integers(1, 3))))
+    return out
+
+
+@pytest.mark.parametrize("c", _sweep_cases(), ids=lambda c: f"{c['i']}-T{c['T']}-D{c['D']}-p{c['period']}")
+def test_replay_sweep(c):
+    rng = np.random.default_rng(c["i"])
+    B, T, Hq, Hkv, D = c["B"], c["T"], c["Hq"], c["Hkv"], c["D"]
+    q, k, v = _rand_bf16(rng, (B, T, Hq, D)), _rand_bf16(rng, (B, T, Hkv, D)), _rand_bf16(rng, (B, T, Hkv, D))
+    if c["per_head"]:
+        death = np.stack([np.stack([_random_death(rng, T, c["period"], c["keep"], c["block"]) for _ in range(Hkv)])
+                          for _ in range(B)])
+    else:
+        death = np.stack([_random_death(rng, T, c["period"], c["keep"], c["block"]) for _ in range(B)])
+    scale = 1.0 / np.sqrt(D)
+    got = _run(q, k, v, death.astype(np.int32), Hq, Hkv, D, c["per_head"], scale)
+    _check(q, k, v, death, Hq, Hkv, D, c["per_head"], scale, got)
