@@ -247,8 +247,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
             const uint32_t b0 = __float_as_uint(p[2 * e2]), b1 = __float_as_uint(p[2 * e2 + 1]);
             const float r0 = p[2 * e2] - __uint_as_float(b0 & 0xFFFF0000u);
             const float r1 = p[2 * e2 + 1] - __uint_as_float(b1 & 0xFFFF0000u);
-            ph[e2] = (b0 >> 16) | (b1 & 0xFFFF0000u);
-            pl[e2] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+            ph[e2] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);                     // upper halves of b0, b1
+            pl[e2] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
         }
         const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
         const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
@@ -261,8 +261,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
             for (int e2 = 0; e2 < 4; ++e2) {
                 const uint32_t w0 = vcur[2 * e2][c >> 1];       // row e = 2*e2,   d pair c/2
                 const uint32_t w1 = vcur[2 * e2 + 1][c >> 1];   // row e = 2*e2+1
-                va[e2] = (c & 1) ? ((w0 >> 16) | (w1 & 0xFFFF0000u))
-                                 : ((w0 & 0xFFFFu) | (w1 << 16));
+                // 2x2 transpose of 16-bit elements: one byte permute per output word
+                va[e2] = (c & 1) ? __builtin_amdgcn_perm(w1, w0, 0x07060302u)
+                                 : __builtin_amdgcn_perm(w1, w0, 0x05040100u);
             }
             const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{va[0], va[1], va[2], va[3]});
             oacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi, oacc[c], 0, 0, 0);
