@@ -154,6 +154,17 @@ int ngc_perturbed_keys(const ngc_cache *c, int32_t layer, const float *logits,
                        const ngc_evict_params *p, float *keys_out,
                        void *ws, size_t ws_bytes, void *stream);
 
+/* Keep counts from a retention rate, computed where the lengths live (Sec. 4.1:
+ * every round keeps the fraction 1 - eps = num / den of what is cached): for
+ * segments seg0 .. seg0 + nseg - 1
+ *     N = ceil(min(max(len, 0), cap) / block),
+ *     keep_out[seg] = min(N, max(1, min_keep, ceil(N * num / den)))   (0 when N == 0)
+ * in exact integer arithmetic.  len, keep_out: int32, indexed by segment (for a
+ * paged cache pass cap = max_pages * page_rows and block = page_rows).
+ * 0 <= num <= den, den >= 1. */
+int ngc_keep_counts(const int32_t *len, int32_t seg0, int32_t nseg, int32_t cap, int32_t block,
+                    int32_t num, int32_t den, int32_t min_keep, int32_t *keep_out, void *stream);
+
 /* One eviction round (Sec. 4.1, 4.3) for every segment of `layer` (-1 = all).
  *   logits    fp32 [L][B][Hkv][cap]; item t of a segment at offset t of its
  *             row.  NaN is treated as -inf.

@@ -38,7 +38,7 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
-           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem")
+           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem", "ngc_keep_counts")
 PROBE_READ, PROBE_COPY, PROBE_READ_NT, PROBE_COPY_NT = 0, 1, 2, 3
 
 
@@ -120,6 +120,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_paged_score_keys.restype = C.c_int
     lib.ngc_lmem.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.ngc_lmem.restype = C.c_int
+    lib.ngc_keep_counts.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.ngc_keep_counts.restype = C.c_int
     lib.ngc_probe_stream.argtypes = [i32, vp, vp, sz, vp]
     lib.ngc_probe_stream.restype = C.c_int
     if path == LIB_PATH:
@@ -365,3 +367,9 @@ def ngc_lmem(logp, rounds, reward, R: int, L: int, B: int, Hkv: int, group: int,
              gout, stream=None):
     _check(load_library().ngc_lmem(_ptr(logp), _ptr(rounds), _ptr(reward), R, L, B, Hkv, group, _ptr(adv_out),
                                    _ptr(loss_layer), _ptr(loss), _ptr(gout), _stream(stream)), "ngc_lmem")
+
+
+def ngc_keep_counts(len_t, seg0: int, nseg: int, cap: int, block: int, num: int, den: int, min_keep: int, keep_out,
+                    stream=None):
+    _check(load_library().ngc_keep_counts(_ptr(len_t), seg0, nseg, cap, block, num, den, min_keep, _ptr(keep_out),
+                                          _stream(stream)), "ngc_keep_counts")

@@ -765,6 +765,27 @@ __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
     if (threadIdx.x == 0) a.len_out[seg] = rows_new;
 }
 
+// --------------------------------------------------------- keep counts ----
+//
+// The fraction rule of Sec. 4.1 evaluated where the lengths live: K = ceil(N * num / den) items of the
+// N = ceil(len / block) a segment has, in exact integer arithmetic, at least `min_keep` (and at least 1
+// for a non-empty segment), at most N.  Saves the host a read-back of the ragged lengths per round.
+__global__ __launch_bounds__(256) void keep_counts_kernel(const int32_t *__restrict__ len, int32_t *__restrict__ keep,
+                                                          int seg0, int nseg, int cap, int block,
+                                                          int64_t num, int64_t den, int min_keep)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= nseg) return;
+    int n = len[seg0 + i];
+    n = n < 0 ? 0 : (n > cap ? cap : n);
+    const int64_t N = (n + block - 1) / block;
+    int64_t K = (N * num + den - 1) / den;
+    if (K < min_keep) K = min_keep;
+    if (K < 1) K = 1;
+    if (K > N) K = N;
+    keep[seg0 + i] = (int32_t)K;
+}
+
 // -------------------------------------------------------------- append ----
 
 struct AppendArgs {
@@ -1037,6 +1058,18 @@ extern "C" int ngc_lmem(const float *logp, const int32_t *rounds, const float *r
     hipLaunchKernelGGL(lmem_layer_kernel, dim3(L), dim3(LMEM_THREADS), 0, st, la);
     NGC_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(lmem_total_kernel, dim3(1), dim3(64), 0, st, (const float *)loss_layer, (int)L, loss);
+    NGC_HIP_CHECK(hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_keep_counts(const int32_t *len, int32_t seg0, int32_t nseg, int32_t cap, int32_t block,
+                               int32_t num, int32_t den, int32_t min_keep, int32_t *keep_out, void *stream)
+{
+    if (!len || !keep_out) return NGC_EINVAL;
+    if (seg0 < 0 || nseg < 0 || cap < 1 || block < 1 || num < 0 || den < 1 || num > den || min_keep < 0) return NGC_EINVAL;
+    if (nseg == 0) return NGC_OK;
+    hipLaunchKernelGGL(keep_counts_kernel, dim3((nseg + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                       len, keep_out, (int)seg0, (int)nseg, (int)cap, (int)block, (int64_t)num, (int64_t)den, (int)min_keep);
     NGC_HIP_CHECK(hipGetLastError());
     return NGC_OK;
 }

@@ -576,3 +576,26 @@ def test_max_keep_larger_than_capacity_and_tiny_segments():
     torch.cuda.synchronize()
     _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 0)
     assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_keep_counts_on_the_device():
+    """The fraction rule evaluated on the GPU equals the oracle's scalar rule (exact integers)."""
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(77)
+    lens = np.concatenate([[0, 1, 2, 31, 32, 33, 8192, 9000, -5], rng.integers(0, 8193, size=500)]).astype(np.int32)
+    d_len = torch.from_numpy(lens).cuda()
+    for (num, den, block, min_keep) in [(1, 2, 1, 0), (1, 3, 1, 0), (2, 5, 32, 0), (9, 10, 7, 0), (0, 1, 1, 0),
+                                        (1, 1, 1, 0), (1, 50, 32, 4), (333, 1000, 1, 16)]:
+        keep = torch.full((lens.size,), -7, dtype=torch.int32, device="cuda")
+        ngc.ngc_keep_counts(d_len, 3, lens.size - 3, 8192, block, num, den, min_keep, keep)
+        torch.cuda.synchronize()
+        got = keep.cpu().numpy()
+        assert got[:3].tolist() == [-7, -7, -7]                       # segments before seg0 are not touched
+        for i in range(3, lens.size):
+            n = min(max(int(lens[i]), 0), 8192)
+            N = (n + block - 1) // block
+            want = 0 if N == 0 else min(N, max(orc.keep_count(N, num, den), min_keep, 1))
+            assert got[i] == want, (lens[i], num, den, block, min_keep)
+    with pytest.raises(ngc.NgcError):
+        ngc.ngc_keep_counts(d_len, 0, 4, 8192, 1, 3, 2, 0, keep)      # a rate above 1
