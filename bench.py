@@ -762,6 +762,15 @@ def main():
         "eviction_pooled_heads": pooled,
         "replay_attn": replay,
         "paged_layout": paged,
+        "cache_schedule": {
+            "what": "rows cached per (layer, head), mean over sequences, after the workload's decode_steps tokens: "
+                    "without eviction, and the peak with it (budget rule); the paper's peak-KV-reduction figure "
+                    "(Sec. 5.1) for this synthetic schedule, context only",
+            "rows_without_eviction": float(np.mean(lens + w.decode_steps)),
+            "peak_rows_with_eviction": float(np.mean(np.maximum(lens, keep_h.mean(axis=(0, 2)) + w.delta))),
+            "peak_reduction": float(np.mean((lens + w.decode_steps) /
+                                            np.maximum(lens, keep_h.mean(axis=(0, 2)) + w.delta))),
+        },
         "measured_ceilings": ceilings,
         "setup_s": t_setup,
     }

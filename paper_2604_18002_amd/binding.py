@@ -77,6 +77,12 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     if _lib is not None and path is None:
         return _lib
     path = path or LIB_PATH
+    # PyTorch ships its own copy of the HIP runtime.  It has to be in the process before this library
+    # pulls in the system's, or the two runtimes would not share streams and launches on torch's streams fail.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it first (python -m paper_2604_18002_amd._build); "
                            "there is no fallback path")
