@@ -110,7 +110,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
 
     if (n == 0) {
         if (split == 0) {
-            if (a.lse_out && threadIdx.x < G) a.lse_out[((size_t)lb * a.Hkv + h) * G + threadIdx.x] = -INFINITY;
+            if (a.lse_out && (int)threadIdx.x < G) a.lse_out[((size_t)lb * a.Hkv + h) * G + threadIdx.x] = -INFINITY;
             for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) out_seg[i] = 0.f;
             if (threadIdx.x == 0) atomicAdd(&a.status[NGC_STATUS_EMPTY_ATTN], 1);
         }
