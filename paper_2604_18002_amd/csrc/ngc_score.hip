@@ -96,7 +96,10 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
 
     unsigned char *wlds = lds + wv * WAVE_LDS;
     u32x4 kbuf[K_LOADS];
-    auto load_tile = [&](int tile) {
+    // Unconditional: a tile past the end re-reads the last tile, so that the number of loads in flight is
+    // the same on every path and the wait for the current tile never also waits for the prefetch.
+    auto load_tile = [&](int tile_raw) {
+        const int tile = tile_raw < tiles ? tile_raw : tiles - 1;
         const int row0 = tile * SC_TILE;
         const unsigned char *kt = kseg;
         int first = 0;   // row number at offset 0 of kt
@@ -143,11 +146,12 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
     for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
     {
         int tile = wv;
-        if (tile < tiles) load_tile(tile);
+        load_tile(tile);
         for (; tile < tiles; tile += SC_WAVES) {
             stage_tile();
             const int row0 = tile * SC_TILE;
-            if (tile + SC_WAVES < tiles) load_tile(tile + SC_WAVES);
+            load_tile(tile + SC_WAVES);
+            __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_wave_barrier();
             bf16x8 kop[2][KCH];
 #pragma unroll
@@ -232,11 +236,12 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
     const float inv_rows = 1.0f / (float)R;
     {
         int tile = wv;
-        if (tile < tiles) load_tile(tile);
+        load_tile(tile);
         for (; tile < tiles; tile += SC_WAVES) {
             stage_tile();
             const int row0 = tile * SC_TILE;
-            if (tile + SC_WAVES < tiles) load_tile(tile + SC_WAVES);
+            load_tile(tile + SC_WAVES);
+            __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_wave_barrier();
             bf16x8 kop[2][KCH];
 #pragma unroll

@@ -164,3 +164,38 @@ def test_trajectories():
     assert t == [4096, 1366 + 256, 1366 + 256, 1366 + 256, 1366 + 256, 1366 + 256]
     # memory saving at 50 % eviction with cadence 256 and ~1k-token completions is a bit over 2x
     assert 2.0 < schedule.peak_reduction(100, 1024, 256, 1, 2) < 2.8
+
+
+# ------------------------------------------------ independence of the two sides ----
+
+def test_product_and_oracle_do_not_know_each_other():
+    """The HIP path and the oracle share no code: neither imports, includes or loads the other; only the
+    seeded input generators (synth, which holds none of the method's arithmetic) serve both."""
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2604_18002_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+                assert "ngc_oracle" not in text and "libngc_oracle" not in text, f
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(root, "oracle", f)).read()
+            assert "paper_2604_18002_amd" not in text, f
+            assert "libngc.so" not in text and "hip" not in text.lower().replace("relationship", ""), f
+    # the header is the only thing the C ABI shares, and the oracle does not include it
+    assert '#include "ngc.h"' not in open(os.path.join(root, "oracle", "ngc_oracle.c")).read()
+    # synth holds generators only: none of the method's building blocks is named there
+    segments = open(os.path.join(pkg, "synth.py")).read().split('"""')[0::2]          # text outside docstrings
+    synth_code = "\n".join(line.split("#")[0] for seg in segments for line in seg.split("\n")).lower()
+    for word in ("gumbel(", "philox", "softmax(", "logsumexp", "argsort", "topk", "exp("):
+        assert word not in synth_code, word
+
+
+def test_missing_library_is_an_error_not_a_fallback(tmp_path):
+    from paper_2604_18002_amd import binding
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.load_library(str(tmp_path / "no_such_libngc.so"))
