@@ -473,6 +473,7 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     if (!aligned16(c->k) || !aligned16(c->v) || !aligned16(q) || !aligned16(out) || !aligned16(ws)) return NGC_EINVAL;
     if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
     if (c->D != 64 && c->D != 128) return NGC_EINVAL;
+    if ((long long)c->cap * c->D * 2 > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;   // 32-bit byte offsets inside a segment
     if (c->Hq % c->Hkv != 0 || c->Hq / c->Hkv > 16) return NGC_EINVAL;
     if (layer < -1 || layer >= c->L || max_len_hint < 0) return NGC_EINVAL;
     if (!(scale == scale)) return NGC_EINVAL;

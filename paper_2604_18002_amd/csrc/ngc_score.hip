@@ -349,6 +349,7 @@ int launch_score(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, c
     if ((reinterpret_cast<uintptr_t>(c->k) | reinterpret_cast<uintptr_t>(q_recent)) & 15u) return NGC_EINVAL;
     if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
     if (c->D != 64 && c->D != 128) return NGC_EINVAL;
+    if ((long long)c->cap * c->D * 2 > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;   // 32-bit byte offsets inside a segment
     if (c->Hq % c->Hkv != 0 || w < 1 || block < 1 || !(scale == scale)) return NGC_EINVAL;
     if (layer < -1 || layer >= c->L) return NGC_EINVAL;
     if (ws_bytes < NGC_STATUS_WORDS * sizeof(int32_t)) return NGC_ENOSPC;

@@ -126,6 +126,9 @@ def test_contiguous_argument_checks_need_no_gpu(lib):
     assert lib.ngc_decode_attn(C.byref(good), -1, A, float("nan"), 0, A, None, A, need, None) == binding.NGC_EINVAL
     assert lib.ngc_decode_attn(C.byref(good), -1, A, 0.1, -5, A, None, A, need, None) == binding.NGC_EINVAL
     assert lib.ngc_score_keys(C.byref(good), -1, A, None, 0, 0.1, 0, 1, A, A, need, None) == binding.NGC_EINVAL
+    huge = cache(cap=1 << 24)                                             # 4 GiB per segment: beyond 32-bit offsets
+    assert lib.ngc_decode_attn(C.byref(huge), -1, A, 0.1, 0, A, None, A, 1 << 40, None) == binding.NGC_EUNSUPPORTED
+    assert lib.ngc_score_keys(C.byref(huge), -1, A, None, 5, 0.1, 0, 1, A, A, 1 << 40, None) == binding.NGC_EUNSUPPORTED
     assert lib.ngc_subset_logprob_backward(A, A, A, A, 4, 10, 10, 40000, None, A, A, need, None) == binding.NGC_EUNSUPPORTED
     assert lib.ngc_replay_attn(A, A, A, A, 1, 70000, 12, 2, 128, 0, 0.1, A, A, 1 << 30, None) != binding.NGC_OK
 
