@@ -120,6 +120,7 @@ struct SelectArgs {
     NoiseArgs na;
 };
 
+constexpr int SMALL_ITEMS = 256;             // at most this many items: selection by ranking
 constexpr int SORT_BITS = 9;                 // digit width of the sigma sort
 constexpr int SORT_BINS = 1 << SORT_BITS;
 
@@ -256,175 +257,242 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
 
-    // ---- 2. radix select of the K-th largest code -------------------------
-    uint32_t prefix = 0, pmask = 0;
-    int need = K;   // how many of the items matching `prefix` are still to take
-    {
-        const int shifts[3] = {21, 10, 0};
-        const int widths[3] = {11, 11, 10};
-#pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = shifts[pass], nb = 1 << widths[pass];
-            for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
-            __syncthreads();
-            for (int t = tid; t < N; t += THREADS) {
-                const uint32_t u = code[t];
-                if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
-            }
-            __syncthreads();
-            // bins in descending digit order; each thread owns `per` of them
-            const int per = (nb + THREADS - 1) / THREADS;
-            int mine = 0;
-            for (int i = 0; i < per; ++i) {
-                const int p = tid * per + i;
-                if (p < nb) mine += (int)hist[nb - 1 - p];
-            }
-            int total;
-            int above = block_excl_scan_i<THREADS>(mine, misc, &total);
-            if (above < need && need <= above + mine) {
+    // Large segments: radix select, ballot compaction, radix sort (steps 2-4).  Segments of at most
+    // SMALL_ITEMS items (blocks or pages as items, the paper's own sizes): ranking by counting instead.
+    uint16_t *src = idxA;   // the kept items in sampled order, once known
+    float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
+    if (N > SMALL_ITEMS) {
+        // ---- 2. radix select of the K-th largest code -------------------------
+        uint32_t prefix = 0, pmask = 0;
+        int need = K;   // how many of the items matching `prefix` are still to take
+        {
+            const int shifts[3] = {21, 10, 0};
+            const int widths[3] = {11, 11, 10};
+    #pragma unroll
+            for (int pass = 0; pass < 3; ++pass) {
+                const int shift = shifts[pass], nb = 1 << widths[pass];
+                for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+                __syncthreads();
+                for (int t = tid; t < N; t += THREADS) {
+                    const uint32_t u = code[t];
+                    if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
+                }
+                __syncthreads();
+                // bins in descending digit order; each thread owns `per` of them
+                const int per = (nb + THREADS - 1) / THREADS;
+                int mine = 0;
                 for (int i = 0; i < per; ++i) {
                     const int p = tid * per + i;
-                    const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
-                    if (need <= above + c) {
-                        misc[32] = nb - 1 - p;   // digit of the K-th largest
-                        misc[33] = above;        // matching items with a larger digit
-                        break;
-                    }
-                    above += c;
+                    if (p < nb) mine += (int)hist[nb - 1 - p];
                 }
+                int total;
+                int above = block_excl_scan_i<THREADS>(mine, misc, &total);
+                if (above < need && need <= above + mine) {
+                    for (int i = 0; i < per; ++i) {
+                        const int p = tid * per + i;
+                        const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
+                        if (need <= above + c) {
+                            misc[32] = nb - 1 - p;   // digit of the K-th largest
+                            misc[33] = above;        // matching items with a larger digit
+                            break;
+                        }
+                        above += c;
+                    }
+                }
+                __syncthreads();
+                const uint32_t digit = (uint32_t)misc[32];
+                need -= misc[33];
+                prefix |= digit << shift;
+                pmask |= (uint32_t)(nb - 1) << shift;
+                __syncthreads();
             }
-            __syncthreads();
-            const uint32_t digit = (uint32_t)misc[32];
-            need -= misc[33];
-            prefix |= digit << shift;
-            pmask |= (uint32_t)(nb - 1) << shift;
-            __syncthreads();
         }
-    }
-    const uint32_t thr = prefix;   // code of the K-th largest key; `need` items equal to it are kept
+        const uint32_t thr = prefix;   // code of the K-th largest key; `need` items equal to it are kept
 
-    // ---- 3. kept list, ascending ------------------------------------------
-    const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-    const int w_begin = wv * per_wave;
-    const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
-    {
-        int gt = 0, eq = 0;
+        // ---- 3. kept list, ascending ------------------------------------------
+        const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+        const int w_begin = wv * per_wave;
+        const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
+        {
+            int gt = 0, eq = 0;
+            for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
+                const int t = t0 + lane;
+                const uint32_t u = (t < w_end) ? code[t] : 0u;
+                gt += __popcll(__ballot(t < w_end && u > thr));
+                eq += __popcll(__ballot(t < w_end && u == thr));
+            }
+            if (lane == 0) { misc[wv] = gt; misc[16 + wv] = eq; }
+        }
+        __syncthreads();
+        int gt_base = 0, eq_base = 0;
+        for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
+        unpicked = 0.f;
+        int32_t *kept_row = a.kept_out + (size_t)seg * a.max_keep;
         for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
             const int t = t0 + lane;
-            const uint32_t u = (t < w_end) ? code[t] : 0u;
-            gt += __popcll(__ballot(t < w_end && u > thr));
-            eq += __popcll(__ballot(t < w_end && u == thr));
+            const bool in = t < w_end;
+            const uint32_t u = in ? code[t] : 0u;
+            const bool is_gt = in && u > thr, is_eq = in && u == thr;
+            const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
+            const int gt_before = gt_base + popc_below(bgt);
+            const int eq_before = eq_base + popc_below(beq);
+            const bool sel = is_gt || (is_eq && eq_before < need);
+            if (sel) {
+                const int slot = gt_before + (eq_before < need ? eq_before : need);
+                kept_row[slot] = t;
+                if (want_sort || fill_holes) idxA[slot] = (uint16_t)t;
+                if (slot == K - 1) misc[34] = t;   // highest kept index
+            } else if (in && want_logp) {
+                float x = row[t];
+                if (x != x) x = -INFINITY;
+                unpicked += expf(x - smax);
+            }
+            gt_base += __popcll(bgt);
+            eq_base += __popcll(beq);
         }
-        if (lane == 0) { misc[wv] = gt; misc[16 + wv] = eq; }
-    }
-    __syncthreads();
-    int gt_base = 0, eq_base = 0;
-    for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
-    float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
-    int32_t *kept_row = a.kept_out + (size_t)seg * a.max_keep;
-    for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
-        const int t = t0 + lane;
-        const bool in = t < w_end;
-        const uint32_t u = in ? code[t] : 0u;
-        const bool is_gt = in && u > thr, is_eq = in && u == thr;
-        const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
-        const int gt_before = gt_base + popc_below(bgt);
-        const int eq_before = eq_base + popc_below(beq);
-        const bool sel = is_gt || (is_eq && eq_before < need);
-        if (sel) {
-            const int slot = gt_before + (eq_before < need ? eq_before : need);
-            kept_row[slot] = t;
-            if (want_sort || fill_holes) idxA[slot] = (uint16_t)t;
-            if (slot == K - 1) misc[34] = t;   // highest kept index
-        } else if (in && want_logp) {
-            float x = row[t];
-            if (x != x) x = -INFINITY;
-            unpicked += expf(x - smax);
+        __syncthreads();
+        if (tid == 0) {
+            const int last_item = misc[34];
+            const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
+            misc[MISC_KEPT] = K;
+            misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
         }
-        gt_base += __popcll(bgt);
-        eq_base += __popcll(beq);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        const int last_item = misc[34];
-        const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
-        misc[MISC_KEPT] = K;
-        misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
-    }
-    if (fill_holes) {
-        // idxA still holds the kept list in ascending order (the sort below permutes it)
-        const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
-        fill_holes_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
-                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
-                                                  a.pos ? a.pos + (size_t)seg * a.g.cap : nullptr, idxA, K);
+        if (fill_holes) {
+            // idxA still holds the kept list in ascending order (the sort below permutes it)
+            const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
+            fill_holes_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                      reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                      a.pos ? a.pos + (size_t)seg * a.g.cap : nullptr, idxA, K);
+        }
+        if (want_sort) {
+
+            // ---- 4. sigma: stable sort of the kept indices by descending code ------
+            // Sort key = cmax - code (ascending), which for kept items lies in
+            // [0, cmax - thr]: only the bits of that range are sorted, SORT_BITS at a time.
+            const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+            const int k_begin = wv * per_wave_k;
+            const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
+            uint16_t *cur = idxA, *dst = idxB;
+            volatile uint32_t *vh = hist;
+            const uint32_t range = cmax - thr;
+            const int range_bits = range ? 32 - __clz(range) : 0;
+            const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
+        #pragma unroll 1
+            for (int pass = 0; pass < passes; ++pass) {
+                const int shift = SORT_BITS * pass;
+                for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
+                __syncthreads();
+                // per-wave digit counts over the wave's own contiguous range
+                for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+                    const int j = j0 + lane;
+                    if (j < k_end) {
+                        const uint32_t d = ((cmax - code[cur[j]]) >> shift) & (SORT_BINS - 1);
+                        atomicAdd(&hist[wv * SORT_BINS + d], 1u);
+                    }
+                }
+                __syncthreads();
+                // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
+                {
+                    constexpr int PER = SORT_BINS * NW / THREADS;
+                    int vals[PER], sum = 0;
+        #pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const int e = tid * PER + i;
+                        vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
+                        sum += vals[i];
+                    }
+                    int total;
+                    int run = block_excl_scan_i<THREADS>(sum, misc, &total);
+        #pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const int e = tid * PER + i;
+                        hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
+                        run += vals[i];
+                    }
+                }
+                __syncthreads();
+                // scatter in order: rank within the batch + running offset of (wave, digit)
+                for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+                    const int j = j0 + lane;
+                    const bool in = j < k_end;
+                    const uint16_t idx = in ? cur[j] : (uint16_t)0;
+                    const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
+                    const uint64_t peers = match_digit(d, __ballot(in));
+                    const int rank = popc_below(peers);
+                    uint32_t base = 0;
+                    if (in) base = vh[wv * SORT_BINS + d];
+                    __builtin_amdgcn_wave_barrier();
+                    if (in) {
+                        dst[base + rank] = idx;
+                        if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+                __syncthreads();
+                uint16_t *tmp = cur; cur = dst; dst = tmp;
+            }
+            src = cur;
+        }
+    } else {
+        // ---- 2'-4'. few items: rank every key by counting ---------------------
+        // rank_t = number of keys that precede key t in the total order (larger code, or equal code and
+        // smaller index).  rank < K <=> kept, and sigma[rank] = t directly: no select passes, no sort.
+        // N * N / THREADS compares, each thread streaming the codes from LDS four at a time.
+        for (int t = N + tid; t < ((N + 3) & ~3); t += THREADS) code[t] = 0;   // padding never outranks anything
+        __syncthreads();
+        int32_t *kept_row = a.kept_out + (size_t)seg * a.max_keep;
+        int kept_so_far = 0;
+        for (int t0 = 0; t0 < N; t0 += THREADS) {
+            const int t = t0 + tid;
+            const bool in = t < N;
+            int rank = 0;
+            if (in) {
+                const uint32_t c = code[t];
+                for (int u = 0; u < N; u += 4) {
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(&code[u]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) rank += (v[i] > c || (v[i] == c && u + i < t)) ? 1 : 0;
+                }
+            }
+            const bool sel = in && rank < K;
+            const uint64_t bal = __ballot(sel);
+            if (lane == 0) misc[wv] = __popcll(bal);
+            __syncthreads();
+            int before = kept_so_far, total = 0;
+            for (int w = 0; w < NW; ++w) {
+                const int c = misc[w];
+                if (w < wv) before += c;
+                total += c;
+            }
+            if (sel) {
+                const int slot = before + popc_below(bal);
+                kept_row[slot] = t;
+                idxA[slot] = (uint16_t)t;        // ascending (the unordered arrangement reads it)
+                idxB[rank] = (uint16_t)t;        // sampled order
+                if (slot == K - 1) misc[34] = t; // highest kept index
+            } else if (in && want_logp) {
+                float x = row[t];
+                if (x != x) x = -INFINITY;
+                unpicked += expf(x - smax);
+            }
+            kept_so_far += total;
+            __syncthreads();
+        }
+        if (tid == 0) {
+            const int last_item = misc[34];
+            const int last_rows = (last_item == N - 1) ? (n - (N - 1) * a.g.block) : a.g.block;
+            misc[MISC_KEPT] = K;
+            misc[MISC_ROWS] = (K - 1) * a.g.block + last_rows;
+        }
+        if (fill_holes) {
+            const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
+            fill_holes_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                      reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                      a.pos ? a.pos + (size_t)seg * a.g.cap : nullptr, idxA, K);
+        }
+        src = idxB;
     }
     if (!want_sort) return;
-
-    // ---- 4. sigma: stable sort of the kept indices by descending code ------
-    // Sort key = cmax - code (ascending), which for kept items lies in
-    // [0, cmax - thr]: only the bits of that range are sorted, SORT_BITS at a time.
-    const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-    const int k_begin = wv * per_wave_k;
-    const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
-    uint16_t *src = idxA, *dst = idxB;
-    volatile uint32_t *vh = hist;
-    const uint32_t range = cmax - thr;
-    const int range_bits = range ? 32 - __clz(range) : 0;
-    const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
-#pragma unroll 1
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = SORT_BITS * pass;
-        for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
-        __syncthreads();
-        // per-wave digit counts over the wave's own contiguous range
-        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-            const int j = j0 + lane;
-            if (j < k_end) {
-                const uint32_t d = ((cmax - code[src[j]]) >> shift) & (SORT_BINS - 1);
-                atomicAdd(&hist[wv * SORT_BINS + d], 1u);
-            }
-        }
-        __syncthreads();
-        // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
-        {
-            constexpr int PER = SORT_BINS * NW / THREADS;
-            int vals[PER], sum = 0;
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid * PER + i;
-                vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
-                sum += vals[i];
-            }
-            int total;
-            int run = block_excl_scan_i<THREADS>(sum, misc, &total);
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid * PER + i;
-                hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
-                run += vals[i];
-            }
-        }
-        __syncthreads();
-        // scatter in order: rank within the batch + running offset of (wave, digit)
-        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-            const int j = j0 + lane;
-            const bool in = j < k_end;
-            const uint16_t idx = in ? src[j] : (uint16_t)0;
-            const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
-            const uint64_t peers = match_digit(d, __ballot(in));
-            const int rank = popc_below(peers);
-            uint32_t base = 0;
-            if (in) base = vh[wv * SORT_BINS + d];
-            __builtin_amdgcn_wave_barrier();
-            if (in) {
-                dst[base + rank] = idx;
-                if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-        __syncthreads();
-        uint16_t *tmp = src; src = dst; dst = tmp;
-    }
     // the sorted list is in `src` (idxA or idxB, depending on the number of passes)
     if (a.sigma_out) {
         int32_t *sig_row = a.sigma_out + (size_t)seg * a.max_keep;

@@ -599,3 +599,30 @@ def test_keep_counts_on_the_device():
             assert got[i] == want, (lens[i], num, den, block, min_keep)
     with pytest.raises(ngc.NgcError):
         ngc.ngc_keep_counts(d_len, 0, 4, 8192, 1, 3, 2, 0, keep)      # a rate above 1
+
+
+@pytest.mark.parametrize("n", [1, 5, 64, 65, 255, 256, 257, 300, 700])
+def test_tied_logits_on_both_sides_of_the_ranking_threshold(n):
+    """Segments of at most 256 items are selected by ranking, larger ones by radix select + sort: both must
+    break ties by index exactly as the oracle does.  Logits take only three values, so almost everything ties
+    (greedy), and with noise the ties are at least broken identically."""
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, L=1, B=3, n_lo=n, n_hi=n)
+    case = host_case(w)
+    rng = np.random.default_rng(n)
+    for seg in case.segs:
+        case.logits[seg] = rng.integers(-1, 2, size=n).astype(np.float32)
+    for K in sorted({1, max(1, n // 3), max(1, n - 1), n}):
+        case.keep[:] = K
+        for tau in (0.0, 1.0):
+            cache, kept, sigma, logp, ws = _run_evict(case, tau=tau, rnd=2)
+            _check_against_oracle(case, cache, kept, sigma, logp, tau, 2)
+            assert all(x == 0 for x in ngc.read_status(ws))
+    # blocks as items: 4 rows per item, the last one short
+    case_b = host_case(w, block=4)
+    for seg in case_b.segs:
+        case_b.logits[seg] = rng.integers(0, 2, size=(n + 3) // 4).astype(np.float32)
+    case_b.keep[:] = max(1, ((n + 3) // 4) // 2)
+    cache, kept, sigma, logp, ws = _run_evict(case_b, tau=0.0, rnd=0, block=4)
+    _check_against_oracle(case_b, cache, kept, sigma, logp, 0.0, 0, block=4)
