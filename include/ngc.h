@@ -13,7 +13,7 @@
  *   ngc_subset_logprob_backward  its gradient w.r.t. the logits (Eq. 4)
  *   ngc_lmem             the eviction loss of Eq. 4 and the weights it puts on
  *                        every round's log-probability             (Sec. 4.4)
- *   ngc_cache_append     "the cache grows as usual" between rounds (Sec. 4.1)
+ *   ngc_cache_append     one new entry per token between rounds   (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
  *   ngc_replay_attn      training-time attention under the replay mask (Sec. 4.5)
@@ -238,7 +238,7 @@ int ngc_lmem(const float *logp, const int32_t *rounds, const float *reward,
              float *adv_out, float *loss_layer, float *loss, float *gout, void *stream);
 
 /* Append one new row per (sequence, head) of `layer` (-1 = all layers) at row
- * len and add 1 to len (Sec. 4.1: between rounds the cache grows as usual).
+ * len and add 1 to len (Sec. 4.1: between rounds every new token adds its entry).
  *   k_new, v_new  bf16 [B][Hkv][D]  (or [L][B][Hkv][D] for layer = -1)
  *   new_pos       int32 [B] token index stored into pos, or NULL
  * A full segment (len == cap) is skipped and counted. */

@@ -25,8 +25,8 @@
  *   orc_select          keep the K largest perturbed values     (Sec. 4.3)
  *   orc_logprob_literal Eq. 2 evaluated term by term, K logsumexps
  *   orc_logprob_suffix  the same value by one reverse running sum (the
- *                       "prefix sum trick" remark after Eq. 2, in the
- *                       cancellation-free arrangement)
+ *                       running-sum shortcut the paper mentions after
+ *                       Eq. 2, in the cancellation-free arrangement)
  *   orc_logprob_grad_literal  d(Eq. 2)/d(logits), term by term (Eq. 4 needs it)
  *   orc_compact         permanent removal of evicted entries    (Sec. 4.1,
  *                       Eq. 7: next alive set = kept entries + new tokens)
