@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0
 # reads for a plain 1 GiB copy (summaries under profiles/).  Keyed by
 # (config, L, B); other shapes report null.
 MEASURED_TRAFFIC = {
-    (2, 28, 64): {"decode": 2.7624e9, "evict": 5.132e9},
-    (3, 28, 128): {"decode": 19.6677e9, "evict": 36.150e9},
+    (2, 28, 64): {"decode": 2.7623e9, "evict": 5.132e9},
+    (3, 28, 128): {"decode": 19.6671e9, "evict": 36.150e9},
     (4, 4, 256): {"decode": 12.5546e9, "evict": 23.463e9},
 }
 
