@@ -168,3 +168,31 @@ def test_evict_append_attend_sequence(idx, over):
                 diff = np.abs(got[l, b, h * w.G:(h + 1) * w.G] - want).max()
                 assert diff <= ATOL, ((l, b, h), diff)
     assert all(x == 0 for x in ngc.read_status(ws))
+
+
+def test_one_very_long_segment_uses_the_maximum_split():
+    """A single sequence of 65024 rows: 2 segments, so every segment is cut into the maximum number of splits
+    (64) and merged; both layouts' entry points, against the oracle."""
+    import torch
+    ngc = _ngc()
+    w = synth.workload(3, L=1, B=1, Hkv=2, Hq=14, n_lo=65024, n_hi=65024)
+    case = host_case(w)
+    cache, _, _ = upload(case)
+    q = synth.queries(w, 0, 5)
+    scale = 1.0 / np.sqrt(w.D)
+    got, ws = _attend(ngc, cache, q, 0, scale, hint=0)
+    want = _oracle_attend(w, from_bf16_tensor(cache.k), from_bf16_tensor(cache.v), cache.len.cpu().numpy(), q, 0, scale)
+    assert np.abs(got - want).max() <= 2e-3
+    # the same rows seen as a paged cache with an identity table: bit-identical to the contiguous call
+    P = 128
+    mp = w.cap // P                                    # 65024 = 508 pages of 128 rows
+    nseg = w.Hkv
+    table = (torch.arange(nseg, dtype=torch.int32, device="cuda")[:, None] * mp +
+             torch.arange(mp, dtype=torch.int32, device="cuda")[None]).view(1, 1, w.Hkv, mp).contiguous()
+    pc = ngc.PagedCache(cache.k.view(nseg * mp, P, w.D), cache.v.view(nseg * mp, P, w.D), None, table, cache.len,
+                        torch.zeros(nseg * mp, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, dtype=torch.int32, device="cuda"), w.Hq)
+    out = torch.zeros(1, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    ngc.ngc_paged_decode_attn(pc, 0, to_bf16_tensor(q, "cuda"), scale, 0, out, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), got)
