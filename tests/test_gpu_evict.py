@@ -626,3 +626,38 @@ def test_tied_logits_on_both_sides_of_the_ranking_threshold(n):
     case_b.keep[:] = max(1, ((n + 3) // 4) // 2)
     cache, kept, sigma, logp, ws = _run_evict(case_b, tau=0.0, rnd=0, block=4)
     _check_against_oracle(case_b, cache, kept, sigma, logp, 0.0, 0, block=4)
+
+
+def test_logprob_and_gradient_at_the_item_limit():
+    """65536 items (the limit of ngc_subset_logprob and its gradient), heavy-tailed logits: K = 2000 against the
+    oracle's literal gradient, K = 32768 (the gradient's limit) against the oracle's log-probability and the
+    properties of the gradient that hold at any size."""
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(65536)
+    n = 65536
+    x = rng.standard_normal(n).astype(np.float32)
+    tail = rng.random(n) < 0.05
+    x = np.where(tail, rng.laplace(0, 4, n), x).astype(np.float32)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ws = torch.zeros(ngc.STATUS_WORDS * 4, dtype=torch.uint8, device="cuda")
+    n_items = d(np.array([n], np.int32))
+    for K in (2000, 32768):
+        _, sg = orc.evict_select(x, K, 1.0, 3, 0, 0, 0, 0)
+        out = torch.zeros(1, dtype=torch.float32, device="cuda")
+        grad = torch.zeros(1, n, dtype=torch.float32, device="cuda")
+        keep = d(np.array([K], np.int32))
+        print(f"[logprob] 65536 items, K={K}", flush=True)
+        ngc.ngc_subset_logprob(d(x[None]), n_items, d(sg[None]), keep, 1, n, K, out, ws)
+        ngc.ngc_subset_logprob_backward(d(x[None]), n_items, d(sg[None]), keep, 1, n, K, K, None, grad, ws)
+        torch.cuda.synchronize()
+        assert float(out) == pytest.approx(orc.logprob_suffix(x, sg), rel=LOGP_RTOL)
+        g = grad.cpu().numpy()[0].astype(np.float64)
+        assert abs(g.sum()) <= 2e-2                                # shift invariance (fp32, 65536 terms)
+        picked = np.zeros(n, bool)
+        picked[sg] = True
+        assert (g[~picked] < 0).all() and (g[picked] <= 1.0).all()
+        if K == 2000:
+            want = orc.logprob_grad(x, sg)
+            assert np.abs(g - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+    assert all(v == 0 for v in ngc.read_status(ws))
