@@ -201,26 +201,30 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(Logpro
     };
     const int chunk = (K + THREADS - 1) / THREADS;
     const int nchunks = (K + chunk - 1) / chunk;
-    // reverse pass: thread 0 owns the last chunk
+    // The masses of the picked items are gathered into LDS first, all loads in flight at once; the two
+    // scans then run on LDS and never wait for a gather inside their serial chunk loops.
+    for (int j = tid; j < K; j += THREADS) inv_r[j] = mass_of(j);
+    __syncthreads();
+    // reverse pass: thread 0 owns the last chunk; mass -> 1 / R in place
     {
         const int cidx = nchunks - 1 - tid;
         const int j_lo = cidx * chunk;
         const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
         float mass = 0.f;
         if (cidx >= 0)
-            for (int j = j_lo; j < j_hi; ++j) mass += mass_of(j);
+            for (int j = j_lo; j < j_hi; ++j) mass += inv_r[j];
         float total;
         const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total);
         if (cidx >= 0) {
             float R = U + after;
             for (int j = j_hi - 1; j >= j_lo; --j) {
-                R += mass_of(j);
+                R += inv_r[j];
                 inv_r[j] = 1.0f / R;
             }
         }
     }
     __syncthreads();
-    // forward pass: thread i owns chunk i
+    // forward pass: thread i owns chunk i; 1 / R -> C in place
     float c_all;
     {
         const int j_lo = tid * chunk;
@@ -231,9 +235,13 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(Logpro
         float C = before;
         for (int j = j_lo; j < j_hi; ++j) {
             C += inv_r[j];
-            const int t = sig[j];
-            if (t >= 0 && t < N) grow[t] = g * (1.0f - mass_of(j) * C);
+            inv_r[j] = C;
         }
+    }
+    __syncthreads();
+    for (int j = tid; j < K; j += THREADS) {
+        const int t = sig[j];
+        if (t >= 0 && t < N) grow[t] = g * (1.0f - mass_of(j) * inv_r[j]);
     }
     for (int t = tid; t < N; t += THREADS) {
         if (picked[t >> 5] & (1u << (t & 31))) continue;

@@ -509,22 +509,26 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     const int cidx = nchunks - 1 - tid;
     const int j_lo = cidx * chunk;
     const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+    // The logits of the picked items, minus the maximum, are gathered into LDS first (over the key codes,
+    // which are no longer needed), all loads in flight at once: the serial chunk loops below then never wait
+    // for a gather.
+    float *ds = reinterpret_cast<float *>(code);
+    for (int j = tid; j < K; j += THREADS) {
+        float x = row[src[j]];
+        if (x != x) x = -INFINITY;
+        ds[j] = x - smax;
+    }
+    __syncthreads();
     float mass = 0.f;
     if (cidx >= 0)
-        for (int j = j_lo; j < j_hi; ++j) {
-            float x = row[src[j]];
-            if (x != x) x = -INFINITY;
-            mass += expf(x - smax);
-        }
+        for (int j = j_lo; j < j_hi; ++j) mass += expf(ds[j]);
     float total_mass;
     const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
     float acc = 0.f;
     if (cidx >= 0) {
         float R = U + after;
         for (int j = j_hi - 1; j >= j_lo; --j) {
-            float x = row[src[j]];
-            if (x != x) x = -INFINITY;
-            const float d = x - smax;
+            const float d = ds[j];
             R += expf(d);
             acc += d - logf(R);
         }
