@@ -46,12 +46,14 @@ struct LogprobArgs {
     int32_t *status;
     int64_t logit_stride;
     int sigma_stride;
+    int stage_cap;   // floats of dynamic LDS for the picked items' terms
 };
 
 // One workgroup per segment; LDS bitmap of picked items (65536 bits).
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
 {
+    extern __shared__ float staged[];         // stage_cap floats
     __shared__ uint32_t picked[2048];
     __shared__ float fmisc[32];
     const int tid = threadIdx.x;
@@ -105,16 +107,24 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
         float x = row[t];
         return (x != x) ? -INFINITY : x;
     };
+    // When they fit, the picked items' terms are gathered into LDS first (all loads in flight at once), so
+    // that the serial chunk loops do not wait for one gather after another.
+    const bool use_stage = K <= a.stage_cap;
+    if (use_stage) {
+        for (int j = tid; j < K; j += THREADS) staged[j] = logit_of(j) - smax;
+        __syncthreads();
+    }
+    auto term = [&](int j) { return use_stage ? staged[j] : logit_of(j) - smax; };
     float mass = 0.f;
     if (cidx >= 0)
-        for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of(j) - smax);
+        for (int j = j_lo; j < j_hi; ++j) mass += expf(term(j));
     float total_mass;
     const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
     float acc = 0.f;
     if (cidx >= 0) {
         float R = U + after;
         for (int j = j_hi - 1; j >= j_lo; --j) {
-            const float d = logit_of(j) - smax;
+            const float d = term(j);
             R += expf(d);
             acc += d - logf(R);
         }
@@ -1004,10 +1014,15 @@ extern "C" int ngc_subset_logprob(const float *logits, const int32_t *n_items,
     if (nseg < 0 || logit_stride < 0 || sigma_stride < 0) return NGC_EINVAL;
     if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
     if (nseg == 0) return NGC_OK;
+    const int stage_cap = sigma_stride < 16384 ? sigma_stride : 16384;     // at most 64 KB of LDS
     LogprobArgs la{logits, n_items, sigma, keep, logp_out, reinterpret_cast<int32_t *>(ws),
-                   logit_stride, sigma_stride};
-    hipLaunchKernelGGL(subset_logprob_kernel<512>, dim3(nseg), dim3(512), 0, (hipStream_t)stream, la);
-    NGC_HIP_CHECK(hipGetLastError());
+                   logit_stride, sigma_stride, stage_cap};
+    const size_t lds = (size_t)stage_cap * sizeof(float);
+    const void *fn = reinterpret_cast<const void *>(&subset_logprob_kernel<512>);
+    if (lds > 48 * 1024)
+        NGC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    void *kargs[] = {&la};
+    NGC_HIP_CHECK(hipLaunchKernel(fn, dim3(nseg), dim3(512), kargs, lds, (hipStream_t)stream));
     return NGC_OK;
 }
 
