@@ -54,7 +54,9 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (0 = the workload's)")
     ap.add_argument("--evict-reps", type=int, default=5, help="timed repetitions of the round-0 eviction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--per-layer", action="store_true", help="also time decode attention launched layer by layer")
+    ap.add_argument("--per-layer", action="store_true", default=True,
+                    help="also time decode attention launched layer by layer, eagerly and from a HIP graph (default)")
+    ap.add_argument("--no-per-layer", dest="per_layer", action="store_false", help="skip the layer-by-layer timing")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout section")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming read / copy probes")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -729,7 +731,8 @@ def main():
             "workload": f"{'configs[%d]' % w.index if w.index < 5 else 'extra (paper-shaped, not a BASELINE config)'} {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} "
                         f"peak cache {w.n_lo}..{w.n_hi} rows, keep {w.keep_num}/{w.keep_den} (budget rule), "
                         f"delta={w.delta}, logits {w.logits_kind}, log-prob {'on' if w.with_logprob else 'off'}",
-            "step": f"{w.delta} x (append + decode attention, all {w.L} layers in one launch) + 1 eviction round",
+            "step": f"{w.delta} x (append + decode attention, all {w.L} layers in one launch) + 1 eviction round "
+                    "(one launch per layer is timed separately: decode_attn_per_layer_launches)",
             "tokens_per_step": w.B * w.delta,
         },
         "decode_attn_tokens_per_s": w.B * n_attn / (attn_ms * 1e-3),
