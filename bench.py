@@ -775,6 +775,15 @@ def main():
                                             np.maximum(lens, keep_h.mean(axis=(0, 2)) + w.delta))),
         },
         "measured_ceilings": ceilings,
+        "paper_context": {
+            "what": "figures the paper reports, context only (no throughput, latency or bandwidth is published for "
+                    "this path; the paper names neither its hardware nor its precision)",
+            "peak_kv_cache_reduction": {"countdown_50pct_eviction_per_round": 2.4, "aime2025_50pct_eviction_per_round": 4.6,
+                                        "math_benchmarks_range": [3, 5]},
+            "countdown_accuracy_pct": {"ngc": 49.6, "best_heuristic_eviction_baseline": 21.2},
+            "method_constants": {"block": 32, "recent_queries_w": 5, "cadence_delta": [256, 350]},
+            "hardware": "not stated",
+        },
         "setup_s": t_setup,
     }
     if per_layer:
