@@ -332,20 +332,25 @@ __global__ void lmem_total_kernel(const float *loss_layer, int L, float *loss)
 
 // --------------------------------------------------------- compaction -----
 //
-// In place: the row that ends at slot j comes from a slot >= j, so a
-// workgroup that walks a segment front to back, reads a whole tile into
-// registers, waits for the tile's reads (barrier) and only then writes, never
-// overwrites a row it (or a later tile) still has to read.  16-byte loads and
-// stores, one full row per ROW_BYTES/16 consecutive lanes; rows that stay
-// where they are are neither read nor written.  K and V tiles travel together
-// so that twice as many loads are in flight.
-
-__device__ __forceinline__ int source_row(const int32_t *kept, int r, int block)
-{
-    if (block == 1) return kept[r];
-    const int item = r / block;
-    return kept[item] * block + (r - item * block);
-}
+// In place: the row that ends at slot j comes from a slot >= j, and once one
+// kept row has moved every later one moves too (the kept list is ascending).
+// A workgroup walks the rows from the first one that moves (row_start) to the
+// end in tiles of TILE_ROWS destination rows.  The stores of a tile may only
+// follow a workgroup barrier that every wave reached after issuing its loads of
+// that tile (a row of the tile can be the source of another row of the same
+// tile); they never touch a row that a later tile still has to read (the
+// sources of tile i+1 lie at or beyond its first row), and earlier tiles are
+// done with their reads.  So the loop is software-pipelined over two register
+// buffers: after the barrier of tile i the loads of tile i+1 are issued, then
+// the index fetches of tile i+2, then the stores of tile i.  Every memory
+// operation inside the loop is unconditional (indices are clamped to the last
+// row, so a tile past the end re-reads rows that exist; full tiles store all
+// their rows), which lets the wait before the stores leave the younger loads in
+// flight: loads, index fetches and stores of three tiles overlap.  Only the
+// last, partial tile is stored under a row test.  16-byte accesses, one full
+// row per ROW_BYTES/16 consecutive lanes, K and V together; all of them carry
+// the nontemporal hint (every row is touched once).  Offsets inside a segment
+// are 32-bit (the host checks cap * ROW_BYTES < 2^31).
 
 template <int ROW_BYTES, int THREADS, int UNROLL>
 __device__ __forceinline__ void compact_kv_inplace(unsigned char *kbase, unsigned char *vbase,
@@ -354,34 +359,77 @@ __device__ __forceinline__ void compact_kv_inplace(unsigned char *kbase, unsigne
     constexpr int PIECES = ROW_BYTES / 16;           // 16-byte pieces per row
     constexpr int ROWS_PER_STEP = THREADS / PIECES;  // rows covered by one load per thread
     constexpr int TILE_ROWS = ROWS_PER_STEP * UNROLL;
-    const int piece = threadIdx.x % PIECES, rsub = threadIdx.x / PIECES;
-    for (int tile = (row_start / TILE_ROWS) * TILE_ROWS; tile < rows_new; tile += TILE_ROWS) {
-        u32x4 kb[UNROLL], vb[UNROLL];
-        bool moves[UNROLL];
+    const int rsub = threadIdx.x / PIECES;
+    const uint32_t col = (uint32_t)(threadIdx.x % PIECES) * 16u;
+    const int last = rows_new - 1;
+    if (row_start >= rows_new) return;   // workgroup-uniform
+
+    // source rows of this thread's rows of a tile; rows past the end take the last row's source
+    auto sources = [&](int tile, int (&src)[UNROLL]) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int r = tile + u * ROWS_PER_STEP + rsub;
-            const int s = (r < rows_new) ? source_row(kept, r, block) : r;
-            moves[u] = (s != r);
-            kb[u] = u32x4{0u, 0u, 0u, 0u};
-            vb[u] = u32x4{0u, 0u, 0u, 0u};
-            if (moves[u]) {
-                const size_t off = (size_t)s * ROW_BYTES + piece * 16;
-                kb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kbase + off));
-                vb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vbase + off));
-            }
+            int r = tile + u * ROWS_PER_STEP + rsub;
+            r = r < last ? r : last;
+            const int item = r / block;
+            src[u] = kept[item] * block + (r - item * block);
         }
-        __syncthreads();   // every read of this tile has landed
+    };
+    auto load = [&](const int (&src)[UNROLL], u32x4 (&kb)[UNROLL], u32x4 (&vb)[UNROLL]) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t off = (uint32_t)src[u] * ROW_BYTES + col;
+            kb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kbase + off));
+            vb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vbase + off));
+        }
+    };
+    auto store_full = [&](int tile, const u32x4 (&kb)[UNROLL], const u32x4 (&vb)[UNROLL]) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t off = (uint32_t)(tile + u * ROWS_PER_STEP + rsub) * ROW_BYTES + col;
+            __builtin_nontemporal_store(kb[u], reinterpret_cast<u32x4 *>(kbase + off));
+            __builtin_nontemporal_store(vb[u], reinterpret_cast<u32x4 *>(vbase + off));
+        }
+    };
+    auto store_tail = [&](int tile, const u32x4 (&kb)[UNROLL], const u32x4 (&vb)[UNROLL]) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int r = tile + u * ROWS_PER_STEP + rsub;
-            if (moves[u]) {
-                const size_t off = (size_t)r * ROW_BYTES + piece * 16;
+            if (r < rows_new) {
+                const uint32_t off = (uint32_t)r * ROW_BYTES + col;
                 __builtin_nontemporal_store(kb[u], reinterpret_cast<u32x4 *>(kbase + off));
                 __builtin_nontemporal_store(vb[u], reinterpret_cast<u32x4 *>(vbase + off));
             }
         }
+    };
+
+    int src[UNROLL];
+    int tile = row_start;
+    u32x4 ka[UNROLL], va[UNROLL], kb[UNROLL], vb[UNROLL];
+    sources(tile, src);
+    load(src, ka, va);
+    sources(tile + TILE_ROWS, src);
+    // one copy of the step per buffer, so that each buffer is named by constants and stays in registers
+    while (true) {
+        __syncthreads();                       // every wave has issued its loads of `tile`
+        if (tile + TILE_ROWS > rows_new) { store_tail(tile, ka, va); break; }
+        load(src, kb, vb);                     // tile + 1
+        sources(tile + 2 * TILE_ROWS, src);    // tile + 2
+        store_full(tile, ka, va);
+        tile += TILE_ROWS;
+        __syncthreads();
+        if (tile + TILE_ROWS > rows_new) { store_tail(tile, kb, vb); break; }
+        load(src, ka, va);
+        sources(tile + 2 * TILE_ROWS, src);
+        store_full(tile, kb, vb);
+        tile += TILE_ROWS;
     }
+}
+
+__device__ __forceinline__ int source_row(const int32_t *kept, int r, int block)
+{
+    if (block == 1) return kept[r];
+    const int item = r / block;
+    return kept[item] * block + (r - item * block);
 }
 
 template <int THREADS>
@@ -741,7 +789,7 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
 // One workgroup per segment: sample, score, then move the survivors.  While a
 // workgroup is in its (ALU/LDS bound) selection phase, the other workgroups of
 // the grid keep the memory system busy with their compaction phase.
-template <int THREADS, int ROW_BYTES>
+template <int THREADS, int ROW_BYTES, int UNROLL>
 __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
 {
     constexpr int NW = THREADS / NGC_WAVE;
@@ -774,9 +822,9 @@ __global__ __launch_bounds__(THREADS) void evict_kernel(SelectArgs a)
     if (first < K) {
         const int row_start = first * a.g.block;
         const size_t seg_off = (size_t)seg * a.g.cap * ROW_BYTES;
-        compact_kv_inplace<ROW_BYTES, THREADS, 4>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
-                                                  reinterpret_cast<unsigned char *>(a.v) + seg_off,
-                                                  kept, rows_new, row_start, a.g.block);
+        compact_kv_inplace<ROW_BYTES, THREADS, UNROLL>(reinterpret_cast<unsigned char *>(a.k) + seg_off,
+                                                       reinterpret_cast<unsigned char *>(a.v) + seg_off,
+                                                       kept, rows_new, row_start, a.g.block);
         if (a.pos)
             compact_pos_inplace<THREADS>(a.pos + (size_t)seg * a.g.cap, kept, rows_new, row_start, a.g.block);
     }
@@ -917,6 +965,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     if (rc) return rc;
     if (!logits || !keep || !p || !kept_out || !ws || p->block < 1 || max_keep < 1) return NGC_EINVAL;
     if ((p->flags & NGC_EVICT_UNORDERED) && p->block != 1) return NGC_EUNSUPPORTED;
+    if ((long long)c->cap * c->D * 2 > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;   // 32-bit byte offsets inside a segment
     int seg0, nseg;
     rc = layer_range(c, layer, &seg0, &nseg);
     if (rc) return rc;
@@ -968,7 +1017,9 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     int keep_cap = max_keep < items_cap ? max_keep : items_cap;
     keep_cap = (keep_cap + 7) & ~7;
     const int items_cap_al = (items_cap + 3) & ~3;
-    const int threads = items_cap > 8192 ? 1024 : (items_cap > 2048 ? 512 : 256);   // measured on configs 2-4
+    // workgroup size and rows in flight per thread, measured on configs 2-4 (selection wants few large workgroups
+    // for large segments; the copy wants as many bytes in flight per compute unit as registers allow)
+    const int threads = items_cap > 4096 ? 1024 : (items_cap > 2048 ? 512 : 256);
     const size_t lds = select_lds_bytes(threads, items_cap_al, keep_cap);
     if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
 
@@ -989,15 +1040,12 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
 
     hipStream_t st = (hipStream_t)stream;
     const void *fn;
-    if (threads == 1024)
-        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<1024, 256>)
-                           : reinterpret_cast<const void *>(&evict_kernel<1024, 128>);
-    else if (threads == 512)
-        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<512, 256>)
-                           : reinterpret_cast<const void *>(&evict_kernel<512, 128>);
-    else
-        fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<256, 256>)
-                           : reinterpret_cast<const void *>(&evict_kernel<256, 128>);
+#define NGC_PICK(T, U) ((c->D == 128) ? reinterpret_cast<const void *>(&evict_kernel<T, 256, U>) \
+                                      : reinterpret_cast<const void *>(&evict_kernel<T, 128, U>))
+    if (threads == 1024) fn = NGC_PICK(1024, 4);
+    else if (threads == 512) fn = NGC_PICK(512, 2);
+    else fn = NGC_PICK(256, 4);
+#undef NGC_PICK
     if (lds > 64 * 1024)
         NGC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     void *kargs[] = {&sa};
