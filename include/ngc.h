@@ -264,6 +264,33 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
                     int32_t max_len_hint, float *out, float *lse_out,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* ngc_decode_attn for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same computation, same kernels and same results as
+ * ngc_decode_attn; the split partials live in a fixed array of
+ * NGC_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU,
+ * held until the process ends) instead of a workspace.
+ *   status   optional int32 [NGC_STATUS_WORDS] device buffer of the caller for
+ *            the anomaly counters (zeroed by the caller, only added to), or
+ *            NULL to drop them.
+ * Returns NGC_ENOSPC, and enqueues nothing, when the call would need more than
+ * the fixed array: the partials take
+ *     256 + 8 * L * B * Hkv + S * nseg * (Hq / Hkv) * (D + 2) * 4 bytes (plus
+ *     alignment), nseg = segments of the launch, S = splits per segment (1 when
+ *     nseg >= 512 or the rows per segment <= 1023, else up to min(ceil(512 /
+ *     nseg), rows / 512, 64)).
+ * The call itself allocates nothing and calls no allocating routine; the first
+ * call on a device looks up the array's address (make that call outside graph
+ * capture).  All calls on one GPU share the array: calls that overlap in time
+ * on the same GPU (different streams) race on the partials and must be
+ * serialised by the caller.  Nothing in the array has to survive between
+ * calls, and nothing in it has to be cleared: every partial a launch reads was
+ * written by that launch. */
+#define NGC_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const void *q, float scale,
+                           int32_t max_len_hint, float *out, float *lse_out,
+                           int32_t *status, void *stream);
+
 /* Key importance scores for the eviction policy (Sec. 4.2): for every segment
  * of `layer` (-1 = all layers), with the queries of the w most recent tokens
  * (whose keys are the last w rows of the segment),

@@ -35,6 +35,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/ngc.h"
 #include "ngc_device.h"
 
@@ -446,7 +448,7 @@ extern "C" const char *ngc_strerror(int code)
     switch (code) {
     case NGC_OK: return "ok";
     case NGC_EINVAL: return "invalid argument (null or misaligned pointer, bad shape or parameter)";
-    case NGC_ENOSPC: return "workspace too small";
+    case NGC_ENOSPC: return "workspace too small (ngc_decode_attn_static: the call needs more than its fixed scratch array)";
     case NGC_EHIP: return "a HIP runtime call failed";
     case NGC_EUNSUPPORTED: return "request outside the limits of this entry point";
     default: return "unknown error code";
@@ -467,7 +469,8 @@ namespace {
 // Shared by both layouts.  `c` carries the logical geometry (for the paged
 // layout: cap = max_pages * page_rows, k / v = the pools).
 int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
-                  int32_t max_len_hint, float *out, float *lse_out, void *ws, size_t ws_bytes, void *stream)
+                  int32_t max_len_hint, float *out, float *lse_out, int32_t *status, void *ws, size_t ws_bytes,
+                  void *stream)
 {
     if (!c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
     if (!aligned16(c->k) || !aligned16(c->v) || !aligned16(q) || !aligned16(out) || !aligned16(ws)) return NGC_EINVAL;
@@ -496,7 +499,7 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     aa.part_o = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off);
     aa.part_ml = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + off +
                                            partial_o_bytes(c, nseg, S));
-    aa.status = reinterpret_cast<int32_t *>(ws);
+    aa.status = status ? status : reinterpret_cast<int32_t *>(ws);
     aa.seg0 = seg0;
     aa.lb0 = layer < 0 ? 0 : layer * c->B;
     aa.S = S; aa.G = c->Hq / c->Hkv; aa.Hkv = c->Hkv; aa.cap = c->cap;
@@ -534,7 +537,49 @@ extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q,
                                void *ws, size_t ws_bytes, void *stream)
 {
     if (!c) return NGC_EINVAL;
-    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, ws, ws_bytes, stream);
+    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
+}
+
+// ---- the same call for callers that cannot allocate ------------------------
+//
+// The split partials (and, when the caller passes no status buffer, the status
+// words) live in a fixed array inside the library's device image instead of a
+// caller-provided workspace.  Every GPU holds its own copy of the array; its
+// address on a device is looked up once, with that device current, and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = NGC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` per device, nullptr until looked up
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return NGC_EHIP;
+    if (dev < 0 || dev >= MAX_DEVICES) return NGC_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NGC_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return NGC_OK;
+}
+}  // namespace
+
+extern "C" int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const void *q, float scale,
+                                      int32_t max_len_hint, float *out, float *lse_out,
+                                      int32_t *status, void *stream)
+{
+    if (!c) return NGC_EINVAL;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc) return rc;
+    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, status, ws,
+                         STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
@@ -549,5 +594,5 @@ extern "C" int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, c
     c.k = pc->k_pool; c.v = pc->v_pool; c.len = pc->len; c.pos = nullptr;
     c.L = pc->L; c.B = pc->B; c.Hkv = pc->Hkv; c.Hq = pc->Hq; c.D = pc->D;
     c.cap = pc->max_pages * pc->page_rows;
-    return launch_decode(&c, pc, layer, q, scale, max_len_hint, out, lse_out, ws, ws_bytes, stream);
+    return launch_decode(&c, pc, layer, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
 }
