@@ -28,7 +28,10 @@
  *     structs themselves (ngc_cache, ngc_evict_params) live in HOST memory and
  *     are read during the call only.
  *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls and never synchronises: each call only enqueues
+ *     state between calls (the workspace holds, besides the status words, per-
+ *     segment tickets that every launch leaves at zero: zero the workspace once
+ *     before its first use and do not share it between calls that overlap in
+ *     time) and never synchronises: each call only enqueues
  *     kernels on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  Ragged lengths and keep counts are read on the device.
  *   - Return value: NGC_OK or a negative NGC_E* code; nothing is enqueued when
@@ -264,6 +267,19 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
                     int32_t max_len_hint, float *out, float *lse_out,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* One decode step of a layer in one launch (Sec. 4.1: between rounds every new
+ * token adds its entry to the cache, and the token attends to the surviving
+ * entries, its own included): exactly ngc_cache_append(c, layer, k_new, v_new,
+ * new_pos) followed by ngc_decode_attn(c, layer, q, ...), same results, same
+ * status counts (a full segment is not appended to, is counted, and is
+ * attended to as it is).  max_len_hint bounds the lengths after the append.
+ *   k_new, v_new  bf16 [B][Hkv][D]  (or [L][B][Hkv][D] for layer = -1), 16-byte aligned
+ *   new_pos       int32 [B] or NULL
+ * Other arguments as in ngc_decode_attn. */
+int ngc_decode_step(const ngc_cache *c, int32_t layer, const void *k_new, const void *v_new,
+                    const int32_t *new_pos, const void *q, float scale, int32_t max_len_hint,
+                    float *out, float *lse_out, void *ws, size_t ws_bytes, void *stream);
+
 /* ngc_decode_attn for callers that cannot allocate device memory or pass a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same computation, same kernels and same results as
@@ -275,7 +291,7 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
  *            NULL to drop them.
  * Returns NGC_ENOSPC, and enqueues nothing, when the call would need more than
  * the fixed array: the partials take
- *     256 + 8 * L * B * Hkv + S * nseg * (Hq / Hkv) * (D + 2) * 4 bytes (plus
+ *     256 + 12 * L * B * Hkv + S * nseg * (Hq / Hkv) * (D + 2) * 4 bytes (plus
  *     alignment), nseg = segments of the launch, S = splits per segment (1 when
  *     nseg >= 512 or the rows per segment <= 1023, else up to min(ceil(512 /
  *     nseg), rows / 512, 64)).
@@ -283,9 +299,9 @@ int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q, float scal
  * call on a device looks up the array's address (make that call outside graph
  * capture).  All calls on one GPU share the array: calls that overlap in time
  * on the same GPU (different streams) race on the partials and must be
- * serialised by the caller.  Nothing in the array has to survive between
- * calls, and nothing in it has to be cleared: every partial a launch reads was
- * written by that launch. */
+ * serialised by the caller.  Nothing in the array has to be cleared by anyone:
+ * every partial a launch reads was written by that launch, and the per-segment
+ * tickets (zero when the image is loaded) are back at zero when a launch ends. */
 #define NGC_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
 int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const void *q, float scale,
                            int32_t max_len_hint, float *out, float *lse_out,

@@ -38,7 +38,7 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
-           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem", "ngc_keep_counts", "ngc_decode_attn_static")
+           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem", "ngc_keep_counts", "ngc_decode_attn_static", "ngc_decode_step")
 STATIC_SCRATCH_BYTES = 16 << 20
 PROBE_READ, PROBE_COPY, PROBE_READ_NT, PROBE_COPY_NT = 0, 1, 2, 3
 
@@ -106,6 +106,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_cache_append.restype = C.c_int
     lib.ngc_decode_attn.argtypes = [cp, i32, vp, f32, i32, vp, vp, vp, sz, vp]
     lib.ngc_decode_attn.restype = C.c_int
+    lib.ngc_decode_step.argtypes = [cp, i32, vp, vp, vp, vp, f32, i32, vp, vp, vp, sz, vp]
+    lib.ngc_decode_step.restype = C.c_int
     lib.ngc_decode_attn_static.argtypes = [cp, i32, vp, f32, i32, vp, vp, vp, vp]
     lib.ngc_decode_attn_static.restype = C.c_int
     lib.ngc_subset_logprob_backward.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, sz, vp]
@@ -252,12 +254,20 @@ def ngc_decode_attn(cache: Cache, layer: int, q, scale: float, max_len_hint: int
                                           _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)), "ngc_decode_attn")
 
 
+def ngc_decode_step(cache: Cache, layer: int, k_new, v_new, new_pos, q, scale: float, max_len_hint: int, out, ws,
+                    stream=None, lse_out=None):
+    v = cache.view()
+    _check(load_library().ngc_decode_step(C.byref(v), layer, _ptr(k_new), _ptr(v_new), _ptr(new_pos), _ptr(q), scale,
+                                          max_len_hint, _ptr(out), _ptr(lse_out), _ptr(ws), ws.numel(),
+                                          _stream(stream)), "ngc_decode_step")
+
+
 def ngc_decode_attn_static(cache: Cache, layer: int, q, scale: float, max_len_hint: int, out, stream=None,
                            lse_out=None, status=None):
     v = cache.view()
     _check(load_library().ngc_decode_attn_static(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
                                                  _ptr(lse_out), _ptr(status), _stream(stream)),
-           "ngc_decode_attn_static")
+           "ngc_decode_attn_static", "ngc_decode_step")
 
 
 def ngc_score_keys(cache: Cache, layer: int, q_recent, w: int, scale: float, flags: int, block: int,

@@ -25,7 +25,17 @@
 //      product is accurate to ~2^-16 relative, not bf16's 2^-8.
 //
 // Long segments are split over several workgroups (flash-decode); each writes
-// an unnormalised partial (max, sum, O) and a second kernel merges them.
+// an unnormalised partial (max, sum, O) and takes a ticket of its segment; the
+// workgroup that takes the last ticket merges the partials.  One launch per
+// call.  The partials and tickets cross workgroups (and the L2 caches of
+// different XCDs) through device-scope atomic stores and loads, which go to
+// memory; the only wait is each writer's own wait for its stores before the
+// workgroup's ticket -- no cache-wide write-back or invalidate is involved.
+//
+// The same kernel can first append the new token's K/V row (Sec. 4.1: the cache
+// grows by one entry per token): the wave that owns the last tile writes the
+// row before it loads that tile, and the length is stored by whichever
+// workgroup of the segment finishes last, after every other one has read it.
 //
 // Paged layout (PAGED = true): a 32-row tile never straddles a page (pages hold
 // a power-of-two number of rows >= 32), so only the tile's base address changes:
@@ -44,6 +54,7 @@ namespace ngc {
 
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_TILE = 32;   // rows per wave step
+constexpr int MAX_SPLITS = 64;  // workgroups per segment at most
 
 struct AttnArgs {
     const unsigned char *k;
@@ -65,7 +76,28 @@ struct AttnArgs {
     int max_pages;
     int num_pages;
     int tpp_shift;          // log2(tiles per page)
+    int32_t *ticket;        // [segments of the cache] workgroups of a segment that are done; 0 between launches
+    // fused append (APPEND kernels only)
+    unsigned char *k_rw;    // the cache again, writable
+    unsigned char *v_rw;
+    int32_t *len_rw;
+    int32_t *pos;           // or nullptr
+    const unsigned char *k_new;   // [launch segments][D] bf16
+    const unsigned char *v_new;
+    const int32_t *new_pos;       // [B] or nullptr
+    int B;
 };
+
+// Loads and stores that other workgroups' data travels through: relaxed, device scope (served by memory, not by
+// an XCD's own L2).
+__device__ __forceinline__ void st_device(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_device(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Tiles [t_lo, t_hi) of split s when `tiles` tiles are cut into at most S
 // nearly equal runs; s_eff = number of non-empty splits.
@@ -77,8 +109,8 @@ __device__ __forceinline__ void split_range(int tiles, int S, int s, int &t_lo, 
     t_hi = t_lo + per < tiles ? t_lo + per : tiles;
 }
 
-template <int D, bool PAGED>
-__global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs a)
+template <int D, bool PAGED, bool APPEND>
+__global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
 {
     constexpr int ROW_BYTES = D * 2;
     constexpr int DPL = D / 16;                 // bf16 per lane in a V row (8 or 4)
@@ -93,6 +125,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     __shared__ float red_m[ATT_WAVES][16];
     __shared__ float red_l[ATT_WAVES][16];
     __shared__ float fin_l[16];
+    __shared__ int is_last;
 
     const int lane = lane_id(), wv = wave_id();
     const int li = lane & 15, kg = lane >> 4;
@@ -106,9 +139,39 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
         if (threadIdx.x == 0 && split == 0) atomicAdd(&a.status[NGC_STATUS_LEN_CLAMPED], 1);
         n = n < 0 ? 0 : a.cap;
     }
+    // fused append: this call's row goes to slot n and takes part in the attention
+    bool grew = false;
+    if constexpr (APPEND) {
+        if (n < a.cap) {
+            grew = true;
+            n += 1;
+        } else if (threadIdx.x == 0 && split == 0) {
+            atomicAdd(&a.status[NGC_STATUS_APPEND_FULL], 1);
+        }
+    }
     const int h = seg % a.Hkv;
     const int lb = seg / a.Hkv - a.lb0;   // (layer * B + sequence) relative to q / out
     float *out_seg = a.out + ((size_t)lb * a.Hkv + h) * G * D;   // [G][D] of this KV head
+
+    // Every workgroup of a split segment takes a ticket when it is done (right away if its split is empty); the
+    // one that takes the last ticket returns true here, all others false.  Whole workgroup calls it.
+    auto took_last_ticket = [&]() -> bool {
+        __syncthreads();   // this workgroup's partial stores have been waited for by their threads
+        if (threadIdx.x == 0) {
+            const int old = __hip_atomic_fetch_add(&a.ticket[seg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (old == a.S - 1) ? 1 : 0;
+        }
+        __syncthreads();
+        return is_last != 0;
+    };
+    // What the last workgroup of a segment does besides merging: the tickets return to 0 for the next launch and
+    // the appended row becomes part of the segment.
+    auto close_segment = [&]() {
+        if (threadIdx.x == 0) {
+            if (a.S > 1) __hip_atomic_store(&a.ticket[seg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (APPEND && grew) a.len_rw[seg] = n;
+        }
+    };
 
     if (n == 0) {
         if (split == 0) {
@@ -121,7 +184,56 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     const int tiles = (n + ATT_TILE - 1) / ATT_TILE;
     int t_lo, t_hi, s_eff;
     split_range(tiles, a.S, split, t_lo, t_hi, s_eff);
-    if (t_lo >= t_hi) return;   // whole workgroup: nothing to do for this split
+    const float *seg_po = a.part_o + (size_t)seg_local * a.S * G * D;
+    const float *seg_pml = a.part_ml + (size_t)seg_local * a.S * G * 2;
+    // Merge of the s_eff partials of this segment: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).  Three
+    // rounds of loads in all (the partials' (max, sum) pairs, then the O values four splits at a time), each round
+    // issued as one batch.  Uses the K staging area, which no wave needs any more.
+    auto merge_partials = [&]() {
+        __asm__ volatile("" ::: "memory");
+        float *ml_s = reinterpret_cast<float *>(lds);          // [s_eff][G][2] -> (weight, sum)
+        float *den_s = ml_s + MAX_SPLITS * 16 * 2;             // [G]
+        const int n_ml = s_eff * G * 2;
+        for (int i = threadIdx.x; i < n_ml; i += ATT_WAVES * 64) ml_s[i] = ld_device(&seg_pml[i]);
+        __syncthreads();
+        if ((int)threadIdx.x < G) {
+            const int qi = threadIdx.x;
+            float M = -INFINITY;
+            for (int sp = 0; sp < s_eff; ++sp) M = fmaxf(M, ml_s[(sp * G + qi) * 2]);
+            float den = 0.f;
+            for (int sp = 0; sp < s_eff; ++sp) {
+                const float wgt = fast_exp2(ml_s[(sp * G + qi) * 2] - M);
+                den += ml_s[(sp * G + qi) * 2 + 1] * wgt;
+                ml_s[(sp * G + qi) * 2] = wgt;
+            }
+            den_s[qi] = den;
+            if (a.lse_out) a.lse_out[((size_t)lb * a.Hkv + h) * G + qi] = (M + __log2f(den)) * 0.6931471805599453f;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
+            const int qi = i / D;
+            float num = 0.f;
+            for (int sp0 = 0; sp0 < s_eff; sp0 += 4) {
+                float o[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sp = (sp0 + u < s_eff) ? sp0 + u : s_eff - 1;
+                    o[u] = ld_device(&seg_po[(size_t)sp * G * D + i]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (sp0 + u < s_eff) num += o[u] * ml_s[((sp0 + u) * G + qi) * 2];
+            }
+            out_seg[i] = num / den_s[qi];
+        }
+    };
+    if (t_lo >= t_hi) {   // whole workgroup: no rows for this split
+        if (took_last_ticket()) {
+            close_segment();
+            if (s_eff > 1) merge_partials();
+        }
+        return;
+    }
 
     const unsigned char *kseg = PAGED ? a.k : a.k + (size_t)seg * a.cap * ROW_BYTES;
     const unsigned char *vseg = PAGED ? a.v : a.v + (size_t)seg * a.cap * ROW_BYTES;
@@ -280,6 +392,24 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
     // tile past the end only re-reads the last row, which every load clamps to)
     // so that the number of loads in flight is the same on every path and the
     // wait for the current tile's data does not also wait for the prefetch.
+    if constexpr (APPEND) {
+        // The wave that owns the last tile stores the new row before it loads that tile, and waits for the store.
+        // No other wave or workgroup uses that row (prefetches past a split's end are never computed on).
+        const int last_tile = tiles - 1;
+        if (grew && last_tile >= t_lo && last_tile < t_hi && ((last_tile - t_lo) % ATT_WAVES) == wv) {
+            if (lane < 2 * K_PIECES) {
+                const bool is_v = lane >= K_PIECES;
+                const int piece = is_v ? lane - K_PIECES : lane;
+                const size_t src_off = (size_t)seg_local * ROW_BYTES + piece * 16;
+                const size_t dst_off = ((size_t)seg * a.cap + (n - 1)) * ROW_BYTES + piece * 16;
+                const u32x4 row = *reinterpret_cast<const u32x4 *>((is_v ? a.v_new : a.k_new) + src_off);
+                *reinterpret_cast<u32x4 *>((is_v ? a.v_rw : a.k_rw) + dst_off) = row;
+            }
+            if (lane == 0 && a.pos && a.new_pos) a.pos[(size_t)seg * a.cap + (n - 1)] = a.new_pos[(seg / a.Hkv) % a.B];
+            __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+    }
+
     u32x4 v_a[8], v_b[8];
     int tile = t_lo + (PAGED ? wv_u : wv);
     size_t base1 = 0, base2 = 0;   // paged: bases of the next tile and of the one after it
@@ -337,56 +467,37 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_partial_kernel(AttnArgs
                 ost[(wv * 16 + li) * D + DPL * (4 * kg + r) + c] = oacc[c][r] * f;
     }
     __syncthreads();
-    const bool direct = (s_eff == 1);   // the only split of its segment: finish here
-    float *dst_o = direct ? out_seg : a.part_o + ((size_t)seg_local * a.S + split) * G * D;
+    const bool direct = (s_eff == 1);   // the only split of its segment with rows: finish here
+    if (direct) {
+        for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
+            const int qi = i / D, d = i - qi * D;
+            float acc = 0.f;
+#pragma unroll
+            for (int w = 0; w < ATT_WAVES; ++w) acc += ost[(w * 16 + qi) * D + d];
+            out_seg[i] = acc / fin_l[qi];
+        }
+        if (a.lse_out && wv == 0 && kg == 0 && li < G)
+            a.lse_out[((size_t)lb * a.Hkv + h) * G + li] = (m_all + __log2f(l_all)) * 0.6931471805599453f;
+        if (a.S == 1 || took_last_ticket()) close_segment();
+        return;
+    }
+    float *dst_o = a.part_o + ((size_t)seg_local * a.S + split) * G * D;
     for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
         const int qi = i / D, d = i - qi * D;
         float acc = 0.f;
 #pragma unroll
         for (int w = 0; w < ATT_WAVES; ++w) acc += ost[(w * 16 + qi) * D + d];
-        if (direct) acc /= fin_l[qi];
-        dst_o[i] = acc;
+        st_device(&dst_o[i], acc);
     }
-    if (!direct && wv == 0 && kg == 0 && li < G) {
+    if (wv == 0 && kg == 0 && li < G) {
         float *ml = a.part_ml + (((size_t)seg_local * a.S + split) * G + li) * 2;
-        ml[0] = m_all;
-        ml[1] = l_all;
+        st_device(&ml[0], m_all);
+        st_device(&ml[1], l_all);
     }
-    if (direct && a.lse_out && wv == 0 && kg == 0 && li < G)
-        a.lse_out[((size_t)lb * a.Hkv + h) * G + li] = (m_all + __log2f(l_all)) * 0.6931471805599453f;
-}
-
-// Merge of the split partials: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
-template <int D>
-__global__ __launch_bounds__(256) void decode_combine_kernel(AttnArgs a)
-{
-    const int seg_local = blockIdx.x;
-    const int seg = a.seg0 + seg_local;
-    const int G = a.G;
-    int n = a.len[seg];
-    n = n < 0 ? 0 : (n > a.cap ? a.cap : n);
-    const int tiles = (n + ATT_TILE - 1) / ATT_TILE;
-    int t_lo, t_hi, s_eff;
-    split_range(tiles, a.S, 0, t_lo, t_hi, s_eff);
-    if (s_eff <= 1) return;   // written directly by the first kernel (or empty)
-    const int h = seg % a.Hkv;
-    const int lb = seg / a.Hkv - a.lb0;
-    float *out_seg = a.out + ((size_t)lb * a.Hkv + h) * G * D;
-    const float *po = a.part_o + (size_t)seg_local * a.S * G * D;
-    const float *pml = a.part_ml + (size_t)seg_local * a.S * G * 2;
-    for (int i = threadIdx.x; i < G * D; i += 256) {
-        const int qi = i / D;
-        float M = -INFINITY;
-        for (int s = 0; s < s_eff; ++s) M = fmaxf(M, pml[(s * G + qi) * 2]);
-        float num = 0.f, den = 0.f;
-        for (int s = 0; s < s_eff; ++s) {
-            const float w = fast_exp2(pml[(s * G + qi) * 2] - M);
-            num += po[(size_t)s * G * D + i] * w;
-            den += pml[(s * G + qi) * 2 + 1] * w;
-        }
-        out_seg[i] = num / den;
-        if (a.lse_out && i == qi * D)
-            a.lse_out[((size_t)lb * a.Hkv + h) * G + qi] = (M + __log2f(den)) * 0.6931471805599453f;
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial stores have reached memory
+    if (took_last_ticket()) {
+        close_segment();
+        merge_partials();
     }
 }
 
@@ -399,33 +510,50 @@ using namespace ngc;
 namespace {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
-// Split only as far as needed to give every workgroup slot of the chip (256
-// CUs x 2 resident workgroups) one piece of work: measured on MI355X, fewer and
-// longer workgroups beat finer splits (partials and the merge kernel cost more
-// than the tail they save).
-constexpr int TARGET_WORKGROUPS = 512;
-constexpr int MAX_SPLITS = 64;
-constexpr int MIN_TILES_PER_SPLIT = 16;   // 512 rows
+// How many workgroups share a segment.  Measured on MI355X: a workgroup (4 waves, one 32-row tile in flight per
+// wave beyond the one in use) streams ~68 GB/s when nothing else limits it (one tile per wave per memory round
+// trip of ~0.9 us); the chip delivers ~6.5 TB/s to this kernel; and a split segment pays ~6 us on top for the
+// chain partial stores -> ticket -> merge loads.  The split count minimises the modelled time
+//     (S > 1 ? 6 us : 0) + max(bytes of the launch / 6.5 TB/s, rounds * bytes of the longest segment / S / 68 GB/s),
+// rounds = how often the launch refills the 512 resident workgroup slots.  Launches with many segments come out
+// unsplit; a layer's launch over few, long segments is cut up to 64 ways; a split keeps at least 128 rows.
+constexpr int RESIDENT_WORKGROUPS = 512;
+constexpr int MIN_TILES_PER_SPLIT = 4;
+constexpr double CHIP_BYTES_PER_S = 6.5e12, WORKGROUP_BYTES_PER_S = 68e9, SPLIT_CHAIN_S = 6e-6;
 
-int splits_for(int nseg_launch, int max_len)
+int splits_for(int nseg_launch, int max_len, int row_bytes)
 {
-    const int target = TARGET_WORKGROUPS, min_tiles = MIN_TILES_PER_SPLIT;
-    int s = (target + nseg_launch - 1) / nseg_launch;
     const int tiles = (max_len + ATT_TILE - 1) / ATT_TILE;
-    int by_len = tiles / min_tiles;
-    if (by_len < 1) by_len = 1;
-    if (s > by_len) s = by_len;
-    if (s > MAX_SPLITS) s = MAX_SPLITS;
-    if (s < 1) s = 1;
-    return s;
+    const double seg_bytes = 2.0 * row_bytes * max_len;          // K and V
+    const double total = seg_bytes * nseg_launch;
+    int best = 1;
+    double best_t = 0.0;
+    for (int s = 1; s <= MAX_SPLITS; ++s) {
+        if (s > 1 && tiles / s < MIN_TILES_PER_SPLIT) break;
+        const long long wgs = (long long)nseg_launch * s;
+        const double rounds = (double)((wgs + RESIDENT_WORKGROUPS - 1) / RESIDENT_WORKGROUPS);
+        const double per_wg = rounds * seg_bytes / s / WORKGROUP_BYTES_PER_S;
+        const double stream = total / CHIP_BYTES_PER_S;
+        const double t = (s > 1 ? SPLIT_CHAIN_S : 0.0) + (per_wg > stream ? per_wg : stream);
+        if (s == 1 || t < best_t * 0.97) {   // a finer split has to buy at least 3 %
+            best = s;
+            best_t = t;
+        }
+    }
+    return best;
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// workspace layout: [status][seg_meta: nseg_total * 2 int32][partial O][partial (max, sum)]
+// workspace layout: [status][per segment of the cache: 2 int32 of the paged layout's pool bookkeeping]
+//                   [per segment of the cache: ticket][partial O][partial (max, sum)]
+size_t ticket_offset(const ngc_cache *c)
+{
+    return STATUS_BYTES + (size_t)c->L * c->B * c->Hkv * 2 * sizeof(int32_t);
+}
 size_t attn_offset(const ngc_cache *c)
 {
-    return align256(STATUS_BYTES + (size_t)c->L * c->B * c->Hkv * 2 * sizeof(int32_t));
+    return align256(ticket_offset(c) + (size_t)c->L * c->B * c->Hkv * sizeof(int32_t));
 }
 size_t partial_o_bytes(const ngc_cache *c, int nseg_launch, int S)
 {
@@ -460,18 +588,32 @@ extern "C" size_t ngc_workspace_bytes(const ngc_cache *c, int32_t max_keep)
     (void)max_keep;
     if (!c || c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return 0;
     const int per_layer = c->B * c->Hkv;
-    const size_t one = attn_partial_bytes(c, per_layer, splits_for(per_layer, c->cap));
-    const size_t all = attn_partial_bytes(c, per_layer * c->L, splits_for(per_layer * c->L, c->cap));
-    return attn_offset(c) + (one > all ? one : all);
+    // the most any launch can ask for: one layer or all layers, any length hint (a launch that finds less
+    // workspace than its preferred split needs falls back to fewer splits, so this is a guarantee, not a limit)
+    size_t most = 0;
+    for (int hint = c->cap; hint >= 1; hint = hint / 2) {
+        const size_t one = attn_partial_bytes(c, per_layer, splits_for(per_layer, hint, c->D * 2));
+        const size_t all = attn_partial_bytes(c, per_layer * c->L, splits_for(per_layer * c->L, hint, c->D * 2));
+        most = one > most ? one : most;
+        most = all > most ? all : most;
+    }
+    return attn_offset(c) + most;
 }
 
 namespace {
 // Shared by both layouts.  `c` carries the logical geometry (for the paged
 // layout: cap = max_pages * page_rows, k / v = the pools).
-int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,
-                  int32_t max_len_hint, float *out, float *lse_out, int32_t *status, void *ws, size_t ws_bytes,
-                  void *stream)
+struct NewRows {            // fused append: the new token's rows, or all null
+    const void *k_new;
+    const void *v_new;
+    const int32_t *new_pos;
+};
+
+int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const NewRows *nr, const void *q,
+                  float scale, int32_t max_len_hint, float *out, float *lse_out, int32_t *status, void *ws,
+                  size_t ws_bytes, void *stream)
 {
+    if (nr && (!nr->k_new || !nr->v_new || !aligned16(nr->k_new) || !aligned16(nr->v_new) || pc)) return NGC_EINVAL;
     if (!c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
     if (!aligned16(c->k) || !aligned16(c->v) || !aligned16(q) || !aligned16(out) || !aligned16(ws)) return NGC_EINVAL;
     if (c->L <= 0 || c->B <= 0 || c->Hkv <= 0 || c->Hq <= 0 || c->cap <= 0) return NGC_EINVAL;
@@ -484,9 +626,10 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     const int seg0 = layer < 0 ? 0 : layer * per_layer;
     const int nseg = layer < 0 ? c->L * per_layer : per_layer;
     const int max_len = (max_len_hint > 0 && max_len_hint < c->cap) ? max_len_hint : c->cap;
-    const int S = splits_for(nseg, max_len);
+    int S = splits_for(nseg, max_len, c->D * 2);
     const size_t off = attn_offset(c);
-    if (ws_bytes < off + attn_partial_bytes(c, nseg, S)) return NGC_ENOSPC;
+    if (ws_bytes < off) return NGC_ENOSPC;
+    while (S > 1 && ws_bytes < off + attn_partial_bytes(c, nseg, S)) --S;   // fewer splits: same result, less scratch
     if ((long long)nseg * S > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;
 
     AttnArgs aa;
@@ -504,6 +647,15 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     aa.lb0 = layer < 0 ? 0 : layer * c->B;
     aa.S = S; aa.G = c->Hq / c->Hkv; aa.Hkv = c->Hkv; aa.cap = c->cap;
     aa.scale_log2e = scale * 1.4426950408889634f;
+    aa.ticket = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) + ticket_offset(c));
+    aa.k_rw = reinterpret_cast<unsigned char *>(c->k);
+    aa.v_rw = reinterpret_cast<unsigned char *>(c->v);
+    aa.len_rw = c->len;
+    aa.pos = c->pos;
+    aa.k_new = nr ? reinterpret_cast<const unsigned char *>(nr->k_new) : nullptr;
+    aa.v_new = nr ? reinterpret_cast<const unsigned char *>(nr->v_new) : nullptr;
+    aa.new_pos = nr ? nr->new_pos : nullptr;
+    aa.B = c->B;
     aa.table = nullptr; aa.max_pages = 0; aa.num_pages = 0; aa.tpp_shift = 0;
     if (pc) {
         aa.table = pc->table; aa.max_pages = pc->max_pages; aa.num_pages = pc->num_pages;
@@ -514,20 +666,16 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(nseg * S), block(ATT_WAVES * 64);
     if (pc) {
-        if (c->D == 128) hipLaunchKernelGGL((decode_partial_kernel<128, true>), grid, block, 0, st, aa);
-        else             hipLaunchKernelGGL((decode_partial_kernel<64, true>), grid, block, 0, st, aa);
+        if (c->D == 128) hipLaunchKernelGGL((decode_kernel<128, true, false>), grid, block, 0, st, aa);
+        else             hipLaunchKernelGGL((decode_kernel<64, true, false>), grid, block, 0, st, aa);
+    } else if (nr) {
+        if (c->D == 128) hipLaunchKernelGGL((decode_kernel<128, false, true>), grid, block, 0, st, aa);
+        else             hipLaunchKernelGGL((decode_kernel<64, false, true>), grid, block, 0, st, aa);
     } else {
-        if (c->D == 128) hipLaunchKernelGGL((decode_partial_kernel<128, false>), grid, block, 0, st, aa);
-        else             hipLaunchKernelGGL((decode_partial_kernel<64, false>), grid, block, 0, st, aa);
+        if (c->D == 128) hipLaunchKernelGGL((decode_kernel<128, false, false>), grid, block, 0, st, aa);
+        else             hipLaunchKernelGGL((decode_kernel<64, false, false>), grid, block, 0, st, aa);
     }
     NGC_HIP_CHECK(hipGetLastError());
-    if (S > 1) {
-        if (c->D == 128)
-            hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(nseg), dim3(256), 0, st, aa);
-        else
-            hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(nseg), dim3(256), 0, st, aa);
-        NGC_HIP_CHECK(hipGetLastError());
-    }
     return NGC_OK;
 }
 }  // namespace
@@ -537,14 +685,25 @@ extern "C" int ngc_decode_attn(const ngc_cache *c, int32_t layer, const void *q,
                                void *ws, size_t ws_bytes, void *stream)
 {
     if (!c) return NGC_EINVAL;
-    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
+    return launch_decode(c, nullptr, layer, nullptr, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes,
+                         stream);
+}
+
+extern "C" int ngc_decode_step(const ngc_cache *c, int32_t layer, const void *k_new, const void *v_new,
+                               const int32_t *new_pos, const void *q, float scale, int32_t max_len_hint,
+                               float *out, float *lse_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!c) return NGC_EINVAL;
+    const NewRows nr{k_new, v_new, new_pos};
+    return launch_decode(c, nullptr, layer, &nr, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
 }
 
 // ---- the same call for callers that cannot allocate ------------------------
 //
-// The split partials (and, when the caller passes no status buffer, the status
-// words) live in a fixed array inside the library's device image instead of a
-// caller-provided workspace.  Every GPU holds its own copy of the array; its
+// The split partials and tickets (and, when the caller passes no status buffer,
+// the status words) live in a fixed array inside the library's device image
+// instead of a caller-provided workspace.  The array starts out zeroed when the
+// image is loaded and every launch leaves the tickets at zero again.  Every GPU holds its own copy of the array; its
 // address on a device is looked up once, with that device current, and kept.
 constexpr size_t STATIC_SCRATCH_BYTES = NGC_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
@@ -578,7 +737,7 @@ extern "C" int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const v
     void *ws = nullptr;
     const int rc = static_scratch(&ws);
     if (rc) return rc;
-    return launch_decode(c, nullptr, layer, q, scale, max_len_hint, out, lse_out, status, ws,
+    return launch_decode(c, nullptr, layer, nullptr, q, scale, max_len_hint, out, lse_out, status, ws,
                          STATIC_SCRATCH_BYTES, stream);
 }
 
@@ -594,5 +753,5 @@ extern "C" int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, c
     c.k = pc->k_pool; c.v = pc->v_pool; c.len = pc->len; c.pos = nullptr;
     c.L = pc->L; c.B = pc->B; c.Hkv = pc->Hkv; c.Hq = pc->Hq; c.D = pc->D;
     c.cap = pc->max_pages * pc->page_rows;
-    return launch_decode(&c, pc, layer, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
+    return launch_decode(&c, pc, layer, nullptr, q, scale, max_len_hint, out, lse_out, nullptr, ws, ws_bytes, stream);
 }

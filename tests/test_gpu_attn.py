@@ -196,3 +196,74 @@ def test_one_very_long_segment_uses_the_maximum_split():
     ngc.ngc_paged_decode_attn(pc, 0, to_bf16_tensor(q, "cuda"), scale, 0, out, ws)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), got)
+
+
+@pytest.mark.parametrize("idx,over", [
+    (0, {}),                                             # one workgroup per segment
+    (1, dict(B=3, n_lo=31, n_hi=97)),                    # appended row opens a new tile for some segments (n = 32, 64, 96)
+    (1, dict(B=2, n_lo=3000, n_hi=4000)),                # split segments: the last workgroup to finish stores the length
+    (3, dict(L=2, B=4, n_lo=1500, n_hi=2600)),           # G = 7, two layers, ragged, split
+])
+def test_decode_step_equals_append_then_attend_and_the_oracle(idx, over):
+    """ngc_decode_step (one launch) against ngc_cache_append + ngc_decode_attn on a copy of the cache, bit for bit
+    (cache bytes, lengths, positions, outputs, log-sum-exp), and against the oracle on the grown cache."""
+    import torch
+    ngc = _ngc()
+    w = synth.workload(idx, **over)
+    case = host_case(w)
+    cache, _, _ = upload(case, with_pos=True, cap=w.cap + 8)       # room for the appended rows
+    ref = ngc.Cache(cache.k.clone(), cache.v.clone(), cache.len.clone(), cache.pos.clone(), cache.Hq)
+    scale = 1.0 / np.sqrt(w.D)
+    ws = ngc.allocate_workspace(cache, 1)
+    ws_ref = ngc.allocate_workspace(ref, 1)
+    for step in range(3):                                # lengths grow across tile boundaries step by step
+        for l in range(w.L):
+            nk, nv = synth.new_token_kv(w, l, step)
+            q = synth.queries(w, l, 10 + step)
+            tk, tv, tq = to_bf16_tensor(nk, "cuda"), to_bf16_tensor(nv, "cuda"), to_bf16_tensor(q, "cuda")
+            new_pos = torch.full((w.B,), 100000 + step, dtype=torch.int32, device="cuda")
+            out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float32, device="cuda")
+            lse = torch.full((w.B, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
+            out_ref, lse_ref = torch.zeros_like(out), torch.zeros_like(lse)
+            print(f"[step] workload={w.name} step={step} layer={l}", flush=True)
+            ngc.ngc_decode_step(cache, l, tk, tv, new_pos, tq, scale, 0, out, ws, lse_out=lse)
+            ngc.ngc_cache_append(ref, l, tk, tv, new_pos, ws_ref)
+            ngc.ngc_decode_attn(ref, l, tq, scale, 0, out_ref, ws_ref, lse_out=lse_ref)
+            torch.cuda.synchronize()
+            assert torch.equal(cache.len, ref.len)
+            assert torch.equal(out, out_ref) and torch.equal(lse, lse_ref)
+            hk, hv, hlen = from_bf16_tensor(cache.k), from_bf16_tensor(cache.v), cache.len.cpu().numpy()
+            want = _oracle_attend(w, hk, hv, hlen, q, l, scale)
+            assert np.abs(out.cpu().numpy() - want).max() <= ATOL
+            for b in range(w.B):
+                for h in range(w.Hkv):
+                    n = int(hlen[l, b, h])
+                    assert n == case.k[(l, b, h)].shape[0] + step + 1
+                    assert hk[l, b, h, n - 1].tobytes() == nk[b, h].tobytes()
+                    assert hv[l, b, h, n - 1].tobytes() == nv[b, h].tobytes()
+    assert torch.equal(cache.k, ref.k) and torch.equal(cache.v, ref.v) and torch.equal(cache.pos, ref.pos)
+    assert all(x == 0 for x in ngc.read_status(ws))
+    # the tickets of every segment are back at zero
+    nseg = w.L * w.B * w.Hkv
+    assert int(ws[ngc.STATUS_WORDS * 4:ngc.STATUS_WORDS * 4 + 12 * nseg].view(torch.int32).abs().sum()) == 0
+
+
+def test_decode_step_on_a_full_segment_attends_without_appending():
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, B=2, n_lo=640, n_hi=640)
+    case = host_case(w)
+    cache, _, _ = upload(case, cap=640)                 # every segment is full
+    q = synth.queries(w, 0)
+    nk, nv = synth.new_token_kv(w, 0, 0)
+    scale = 1.0 / np.sqrt(w.D)
+    ws = ngc.allocate_workspace(cache, 1)
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    before = cache.k.clone()
+    ngc.ngc_decode_step(cache, 0, to_bf16_tensor(nk, "cuda"), to_bf16_tensor(nv, "cuda"), None, to_bf16_tensor(q, "cuda"),
+                        scale, 0, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(cache.k, before) and int(cache.len.min()) == 640 and int(cache.len.max()) == 640
+    assert ngc.read_status(ws)[ngc.STATUS_APPEND_FULL] == w.B * w.Hkv
+    want = _oracle_attend(w, from_bf16_tensor(cache.k), from_bf16_tensor(cache.v), cache.len.cpu().numpy(), q, 0, scale)
+    assert np.abs(out.cpu().numpy() - want).max() <= ATOL
