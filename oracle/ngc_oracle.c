@@ -199,11 +199,24 @@ int orc_select(const float *keys, int32_t n_items, int32_t K,
 
 /* ---------------------------------------------------------- log-prob ---- */
 
+/* A pick of a masked entry (logit -inf: weight exp(-inf) = 0 in Eq. 2) has
+ * probability zero, so the whole sequence has log-probability -inf.  This also
+ * fixes the one case the formula leaves as 0/0: a masked pick at a step where
+ * every entry still available is masked.  (Masked entries that are never picked
+ * simply add nothing to any sum.) */
+static int picks_a_masked_entry(const float *logits, const int32_t *sigma, int32_t K)
+{
+    for (int32_t j = 0; j < K; ++j)
+        if (logits[sigma[j]] == -INFINITY) return 1;
+    return 0;
+}
+
 /* Eq. 2, term by term: for j = 1..K the logit of the j-th pick minus the
  * logsumexp over every item not picked before it. O(nK). */
 double orc_logprob_literal(const float *logits, int32_t n_items,
                            const int32_t *sigma, int32_t K)
 {
+    if (picks_a_masked_entry(logits, sigma, K)) return -INFINITY;
     unsigned char *gone = (unsigned char *)calloc((size_t)(n_items > 0 ? n_items : 1), 1);
     if (!gone) return NAN;
     double total = 0.0;
@@ -229,6 +242,7 @@ double orc_logprob_literal(const float *logits, int32_t n_items,
 double orc_logprob_suffix(const float *logits, int32_t n_items,
                           const int32_t *sigma, int32_t K)
 {
+    if (picks_a_masked_entry(logits, sigma, K)) return -INFINITY;
     unsigned char *picked = (unsigned char *)calloc((size_t)(n_items > 0 ? n_items : 1), 1);
     if (!picked) return NAN;
     double mx = -INFINITY;

@@ -192,3 +192,47 @@ def test_lmem_invariants():
     w = np.where(np.arange(R)[:, None] < rounds[None, :], 1.0 / np.maximum(rounds, 1)[None, :], 0.0)   # [R, B]
     want = -(lp * w[:, None, :, None] * adv[None, None, :, None]).sum(axis=(0, 2, 3)) / B
     assert per_layer == pytest.approx(want, abs=1e-12)
+
+
+def test_masked_entries():
+    """Entries with logit -inf (masked keys): never picked, they drop out of every sum; picked, the sequence has
+    probability zero.  Pinned to scipy's log-softmax (K = 1), to the same problem with the masked entries deleted,
+    to the limit of very negative finite logits, and to the enumeration still summing to one."""
+    s = np.array([0.3, -np.inf, 1.2, -0.7, -np.inf, 0.1], np.float32)
+    ls = log_softmax(s.astype(np.float64))
+    for t in range(s.size):
+        assert orc.logprob_literal(s, [t]) == ls[t] or orc.logprob_literal(s, [t]) == pytest.approx(ls[t], rel=1e-13)
+    assert orc.logprob_literal(s, [1]) == -np.inf and orc.logprob_suffix(s, [4]) == -np.inf
+    # masked entries that are not picked change nothing: same value as with those entries deleted
+    finite = np.array([0, 2, 3, 5])
+    dense = s[finite]
+    for seq in ((2, 0), (3, 1, 0), (0, 1, 2, 3)):
+        full_seq = [int(finite[i]) for i in seq]
+        assert orc.logprob_literal(s, full_seq) == pytest.approx(orc.logprob_literal(dense, seq), rel=1e-13)
+        assert orc.logprob_suffix(s, full_seq) == pytest.approx(orc.logprob_suffix(dense, seq), rel=1e-13)
+    # picked after every finite entry (also where only masked entries are left, the 0/0 case): -inf, never NaN
+    for seq in ([0, 2, 3, 5, 1], [0, 2, 3, 5, 1, 4], [2, 1]):
+        assert orc.logprob_literal(s, seq) == -np.inf
+        assert orc.logprob_suffix(s, seq) == -np.inf
+    # limit: a very negative finite logit in place of -inf gives a hugely negative value
+    t = s.copy()
+    t[[1, 4]] = -1e30
+    assert orc.logprob_suffix(t, [2, 1]) < -1e29
+    # the probabilities of all ordered pairs still sum to one
+    total = sum(math.exp(orc.logprob_literal(s, seq)) for seq in itertools.permutations(range(s.size), 2))
+    assert total == pytest.approx(1.0, abs=1e-12)
+    # an all-masked segment: any pick has log-probability -inf
+    m = np.full(5, -np.inf, np.float32)
+    assert orc.logprob_literal(m, [3]) == -np.inf and orc.logprob_suffix(m, [0, 1]) == -np.inf
+
+
+def test_selection_puts_masked_entries_last():
+    """Masked entries are taken only after every finite one, lowest index first, with or without noise."""
+    s = np.array([0.3, -np.inf, 1.2, -0.7, -np.inf, 0.1, -np.inf], np.float32)
+    for tau in (0.0, 1.0):
+        kept, sigma = orc.evict_select(s, 6, tau, 99, 0, 0, 0, 0)
+        assert sorted(sigma[:4].tolist()) == [0, 2, 3, 5]
+        assert sigma[4:].tolist() == [1, 4]
+        assert kept.tolist() == [0, 1, 2, 3, 4, 5]
+    kept, sigma = orc.evict_select(np.full(9, -np.inf, np.float32), 4, 1.0, 5, 0, 0, 0, 0)
+    assert kept.tolist() == [0, 1, 2, 3] and sigma.tolist() == [0, 1, 2, 3]
