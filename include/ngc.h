@@ -100,6 +100,15 @@ typedef struct ngc_cache {
  *                0 = greedy top-k as used at evaluation (Sec. 5.1).
  *   round        eviction round counter; with `seed` it names the draw, the
  *                same (seed, round) reproduces the same sample.
+ *   layer_base, seq_base
+ *                the noise of an entry is a function of (seed, round, global
+ *                layer, global sequence, head, item) -- every layer takes its
+ *                own decisions (Sec. 4.4).  A caller that holds one allocation
+ *                per layer, or a slice of the batch, passes where its view
+ *                starts: layer l / sequence b of the view then draw the noise
+ *                of layer layer_base + l / sequence seq_base + b, exactly what
+ *                they draw inside one allocation holding everything.
+ *                layer_base + L <= 65535.
  *   flags        NGC_EVICT_SELECT_ONLY: sample (and score) but move nothing
  *                and leave `len` untouched.
  *                NGC_EVICT_UNORDERED (block == 1 only): instead of packing the
@@ -120,7 +129,11 @@ typedef struct ngc_cache {
  *                head * cap + row, in the Hkv rows of the (layer, sequence)
  *                back to back; logp_out holds its log-probability in the entry
  *                of head 0 and 0 in the others.  The workspace must be
- *                ngc_workspace_bytes() + 4 * L * B * Hkv * cap bytes. */
+ *                ngc_workspace_bytes() + 4 * L * B * Hkv * cap bytes.  The
+ *                budget of one (layer, sequence) -- a sum only the device
+ *                sees -- is limited to 32000 items (the sort's index buffers
+ *                live in LDS); a larger one is clamped to the limit and
+ *                counted in NGC_STATUS_KEEP_CLAMPED. */
 #define NGC_EVICT_SELECT_ONLY 1u
 #define NGC_EVICT_UNORDERED   2u
 #define NGC_EVICT_POOL_HEADS  4u
@@ -131,7 +144,9 @@ typedef struct ngc_evict_params {
     uint32_t round;
     uint64_t seed;
     uint32_t flags;
-    uint32_t reserved;
+    int32_t  layer_base;   /* global index of the cache view's layer 0 ...                 */
+    int32_t  seq_base;     /* ... and of its sequence 0 (both 0 for a whole cache)         */
+    int32_t  reserved;     /* 0 */
 } ngc_evict_params;
 
 /* Library version (major * 10000 + minor * 100 + patch). */
@@ -183,8 +198,11 @@ int ngc_keep_counts(const int32_t *len, int32_t seg0, int32_t nseg, int32_t cap,
  * NGC_EVICT_SELECT_ONLY is set, the rows of the kept items are then packed to
  * the front of their segment in k, v and pos, in ascending order, in place,
  * and len is updated.  Segments of other layers are not touched.
- * Limits: ceil(cap / block) <= 16384 items per segment for this entry point
- * (NGC_EUNSUPPORTED beyond).  ws must hold ngc_workspace_bytes(). */
+ * Limits (NGC_EUNSUPPORTED beyond): items = ceil(cap / block) <= 16384 per
+ * segment, items + min(max_keep, items) <= 32704 (what fits in LDS: 16384 items
+ * go with max_keep <= 16320), cap * D * 2 < 2^31 bytes per segment.  A keep
+ * count above max_keep is clamped to it and counted like one above the item
+ * count.  ws must hold ngc_workspace_bytes(). */
 int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
               const int32_t *keep, const ngc_evict_params *p, int32_t max_keep,
               int32_t *kept_out, int32_t *sigma_out, float *logp_out,

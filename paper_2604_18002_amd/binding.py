@@ -66,7 +66,7 @@ class ngc_paged_cache(C.Structure):
 class ngc_evict_params(C.Structure):
     _fields_ = [("block", C.c_int32), ("share_heads", C.c_int32), ("noise_scale", C.c_float),
                 ("round", C.c_uint32), ("seed", C.c_uint64), ("flags", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("layer_base", C.c_int32), ("seq_base", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None
@@ -195,8 +195,9 @@ class Cache:
         return Cache(k, v, ln, pos, Hq)
 
 
-def make_params(block=1, share_heads=0, noise_scale=1.0, round=0, seed=0, flags=0) -> ngc_evict_params:
-    return ngc_evict_params(block, share_heads, noise_scale, round, seed, flags, 0)
+def make_params(block=1, share_heads=0, noise_scale=1.0, round=0, seed=0, flags=0, layer_base=0,
+                seq_base=0) -> ngc_evict_params:
+    return ngc_evict_params(block, share_heads, noise_scale, round, seed, flags, layer_base, seq_base, 0)
 
 
 def ngc_workspace_bytes(cache: Cache, max_keep: int) -> int:

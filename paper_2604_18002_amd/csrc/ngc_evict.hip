@@ -88,6 +88,7 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
         if (x == x) smax = fmaxf(smax, x);
     }
     smax = block_max_f<THREADS>(smax, fmisc);   // barriers also publish `picked`
+    if (smax == -INFINITY) smax = 0.f;          // every entry masked: all weights are 0
     float unpicked = 0.f;
     for (int t = tid; t < N; t += THREADS) {
         if (picked[t >> 5] & (1u << (t & 31))) continue;
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
         for (int j = j_hi - 1; j >= j_lo; --j) {
             const float d = term(j);
             R += expf(d);
-            acc += d - logf(R);
+            acc += (d == -INFINITY) ? -INFINITY : d - logf(R);   // a masked pick: probability 0
         }
     }
     const float lp = block_sum_f<THREADS>(acc, fmisc);
@@ -556,7 +557,10 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
                 }
         }
     }
-    if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);
+    if (want_logp) {
+        smax = block_max_f<THREADS>(smax, fmisc);
+        if (smax == -INFINITY) smax = 0.f;
+    }
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
 
     // ---- 2. radix select ---------------------------------------------------
@@ -762,7 +766,7 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
                 for (int j = j_hi - 1; j >= j_lo; --j) {
                     const float d = logit_of_item(src[j]) - smax;
                     R += expf(d);
-                    acc += d - logf(R);
+                    acc += (d == -INFINITY) ? -INFINITY : d - logf(R);
                 }
             }
             const float lp = block_sum_f<THREADS>(acc, fmisc);
@@ -917,6 +921,15 @@ int check_cache(const ngc_cache *c)
     return NGC_OK;
 }
 
+// The noise counter packs the global layer index into 16 bits.
+int check_bases(const ngc_cache *c, const ngc_evict_params *p)
+{
+    if (p->layer_base < 0 || p->seq_base < 0) return NGC_EINVAL;
+    if ((long long)p->layer_base + c->L > 65535) return NGC_EINVAL;
+    if ((long long)p->seq_base + c->B > 0x7FFFFFFFLL) return NGC_EINVAL;
+    return NGC_OK;
+}
+
 int layer_range(const ngc_cache *c, int layer, int *seg0, int *nseg)
 {
     if (layer < -1 || layer >= c->L) return NGC_EINVAL;
@@ -944,12 +957,13 @@ extern "C" int ngc_perturbed_keys(const ngc_cache *c, int32_t layer, const float
     int rc = check_cache(c);
     if (rc) return rc;
     if (!logits || !keys_out || !p || !ws || p->block < 1) return NGC_EINVAL;
+    if ((rc = check_bases(c, p)) != NGC_OK) return rc;
     if (ws_bytes < STATUS_BYTES) return NGC_ENOSPC;
     int seg0, nseg;
     rc = layer_range(c, layer, &seg0, &nseg);
     if (rc) return rc;
     SegGeom g{c->B, c->Hkv, c->cap, p->block};
-    NoiseArgs na{p->seed, p->round, p->noise_scale, p->share_heads};
+    NoiseArgs na{p->seed, p->round, p->noise_scale, p->share_heads, p->layer_base, p->seq_base};
     hipLaunchKernelGGL(perturbed_keys_kernel, dim3(nseg), dim3(256), 0, (hipStream_t)stream,
                        logits, c->len, keys_out, seg0, g, na, reinterpret_cast<int32_t *>(ws));
     NGC_HIP_CHECK(hipGetLastError());
@@ -964,6 +978,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     int rc = check_cache(c);
     if (rc) return rc;
     if (!logits || !keep || !p || !kept_out || !ws || p->block < 1 || max_keep < 1) return NGC_EINVAL;
+    if ((rc = check_bases(c, p)) != NGC_OK) return rc;
     if ((p->flags & NGC_EVICT_UNORDERED) && p->block != 1) return NGC_EUNSUPPORTED;
     if ((long long)c->cap * c->D * 2 > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;   // 32-bit byte offsets inside a segment
     int seg0, nseg;
@@ -986,7 +1001,9 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
         const int hist = (SEL_BINS > SORT_BINS * (POOL_THREADS / 64)) ? SEL_BINS : SORT_BINS * (POOL_THREADS / 64);
         size_t lds = (size_t)hist * 4 + 128 * 4 + (size_t)keep_cap * 2 * 2;
         if (lds > 160 * 1024) {
-            // the index buffers do not fit: allow as many kept items as LDS holds
+            // Hkv * max_keep is only an upper bound of what a (layer, sequence) keeps (max_keep has to cover the
+            // largest single head); the budget itself is on the device.  The index buffers take what LDS holds;
+            // a budget above that is clamped by the kernel and counted in NGC_STATUS_KEEP_CLAMPED.
             keep_cap = (int)(((160 * 1024 - (size_t)hist * 4 - 128 * 4) / 4) & ~7u);
             lds = (size_t)hist * 4 + 128 * 4 + (size_t)keep_cap * 2 * 2;
         }
@@ -1001,7 +1018,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
         sa.pool_codes = reinterpret_cast<uint32_t *>(reinterpret_cast<unsigned char *>(ws) + codes_off);
         sa.g = SegGeom{c->B, c->Hkv, c->cap, 1};
         sa.logit_stride = c->cap;
-        sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
+        sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads, p->layer_base, p->seq_base};
         const void *fn = (c->D == 128) ? reinterpret_cast<const void *>(&evict_pooled_kernel<256>)
                                        : reinterpret_cast<const void *>(&evict_pooled_kernel<128>);
         if (lds > 64 * 1024)
@@ -1036,7 +1053,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     sa.seg0 = seg0; sa.max_keep = max_keep; sa.items_cap = items_cap_al; sa.keep_cap = keep_cap;
     sa.g = SegGeom{c->B, c->Hkv, c->cap, p->block};
     sa.logit_stride = c->cap;
-    sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
+    sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads, p->layer_base, p->seq_base};
 
     hipStream_t st = (hipStream_t)stream;
     const void *fn;

@@ -313,7 +313,7 @@ extern "C" int ngc_paged_evict(const ngc_paged_cache *pc, int32_t layer, const f
     sa.pool_codes = nullptr;
     sa.logit_stride = logit_stride;
     sa.g = SegGeom{pc->B, pc->Hkv, pc->max_pages * pc->page_rows, pc->page_rows};
-    sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads};
+    sa.na = NoiseArgs{p->seed, p->round, p->noise_scale, p->share_heads, p->layer_base, p->seq_base};
 
     PagedArgs pa = paged_args(pc, ws, seg0, nseg);
     const bool edit = !(p->flags & NGC_EVICT_SELECT_ONLY);

@@ -49,6 +49,8 @@ struct NoiseArgs {
     uint32_t round;
     float tau;
     int share_heads;
+    int layer_base;   // global index of the view's layer 0 and sequence 0: the noise of an entry depends on
+    int seq_base;     // where it sits in the model and the batch, not on how the caller sliced its buffers
 };
 
 // Keys of items 4*quad .. 4*quad+3 (those below n_items), one Philox call.
@@ -69,7 +71,7 @@ __device__ __forceinline__ void keys_of_quad(const float *row, int n_items, int 
         return;
     }
     uint32_t w[4];
-    item_words(na.seed, na.round, (uint32_t)l, (uint32_t)b,
+    item_words(na.seed, na.round, (uint32_t)(l + na.layer_base), (uint32_t)(b + na.seq_base),
                na.share_heads ? 0xFFFFu : (uint32_t)h, (uint32_t)quad, w);
 #pragma unroll
     for (int i = 0; i < 4; ++i) key[i] = perturb(s[i], na.tau, w[i]);
@@ -220,8 +222,8 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     int K = a.keep[seg];
     {
         int lim = N < a.max_keep ? N : a.max_keep;
-        if (K < 0 || K > lim) {
-            if (tid == 0 && (K < 0 || K > N)) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
+        if (K < 0 || K > lim) {   // also when only max_keep (the row length of kept_out) is exceeded
+            if (tid == 0) atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
             K = K < 0 ? 0 : lim;
         }
     }
@@ -254,7 +256,10 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
                 smax = fmaxf(smax, s[i]);
             }
     }
-    if (want_logp) smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
+    if (want_logp) {
+        smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
+        if (smax == -INFINITY) smax = 0.f;          // every entry masked: all weights are 0 (log p = -inf below)
+    }
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
 
     // Large segments: radix select, ballot compaction, radix sort (steps 2-4).  Segments of at most
@@ -530,7 +535,8 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
         for (int j = j_hi - 1; j >= j_lo; --j) {
             const float d = ds[j];
             R += expf(d);
-            acc += d - logf(R);
+            // a masked pick (logit -inf) has probability 0: log p = -inf, also where nothing unmasked is left (R == 0)
+            acc += (d == -INFINITY) ? -INFINITY : d - logf(R);
         }
     }
     const float lp = block_sum_f<THREADS>(acc, fmisc);

@@ -43,11 +43,11 @@ def keep_table(w: synth.Workload, lens: np.ndarray, block: int = 1) -> np.ndarra
             if w.fixed_keep is not None:
                 keep[l, b, :] = min(items, w.fixed_keep)
             elif w.per_head_budget:
-                total = schedule.keep_count(w.Hkv * items, w.keep_num, w.keep_den)
+                total = orc.keep_count(w.Hkv * items, w.keep_num, w.keep_den)
                 keep[l, b, :] = schedule.split_budget(total, synth.head_budget_weights(w, l, b),
                                                       np.full(w.Hkv, items))
             else:
-                keep[l, b, :] = schedule.keep_count(items, w.keep_num, w.keep_den)
+                keep[l, b, :] = orc.keep_count(items, w.keep_num, w.keep_den)
     return keep
 
 

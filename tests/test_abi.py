@@ -46,10 +46,11 @@ def test_version_and_strerror(lib):
 
 def test_struct_layout_matches_the_header():
     from paper_2604_18002_amd import binding
-    # ngc_cache: 4 pointers + 6 int32; ngc_evict_params: 2 int32, float, u32, u64, 2 u32
+    # ngc_cache: 4 pointers + 6 int32; ngc_evict_params: 2 int32, float, u32, u64, u32, 3 int32
     assert C.sizeof(binding.ngc_cache) == 4 * 8 + 6 * 4
-    assert C.sizeof(binding.ngc_evict_params) == 32
+    assert C.sizeof(binding.ngc_evict_params) == 40
     assert binding.ngc_evict_params.seed.offset == 16
+    assert binding.ngc_evict_params.layer_base.offset == 28 and binding.ngc_evict_params.seq_base.offset == 32
 
 
 def test_host_side_argument_checks_need_no_gpu(lib):

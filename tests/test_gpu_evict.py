@@ -661,3 +661,148 @@ def test_logprob_and_gradient_at_the_item_limit():
             want = orc.logprob_grad(x, sg)
             assert np.abs(g - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
     assert all(v == 0 for v in ngc.read_status(ws))
+
+
+# ----------------------------------------------- views with global indices -----
+
+def test_layer_and_sequence_views_draw_the_noise_of_their_global_position():
+    """Evicting layer l (sequences b0..) of a cache through an L = 1, B-sliced view with layer_base = l and
+    seq_base = b0 gives, bit for bit, what the whole cache gives there -- and what the oracle gives for the global
+    (l, b).  Called through the C ABI with raw pointers into the big allocation."""
+    import ctypes as C
+    import torch
+    ngc = _ngc()
+    lib = ngc.load_library()
+    w = synth.workload(1, L=3, B=5, n_lo=700, n_hi=2100)
+    case = host_case(w)
+    whole, kept_w, sigma_w, logp_w, _ = _run_evict(case)                       # all layers, one allocation
+    _check_against_oracle(case, whole, kept_w, sigma_w, logp_w, 1.0, 0)
+    cache, logits, keep = upload(case, with_pos=True)
+    max_keep = kept_w.shape[-1]
+    l, b0, nb = 2, 1, 3                                                        # layer 2, sequences 1..3
+    kept = torch.full((nb, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.zeros(nb, w.Hkv, dtype=torch.float32, device="cuda")
+    view = ngc.ngc_cache(cache.k[l, b0].data_ptr(), cache.v[l, b0].data_ptr(), cache.len[l, b0].data_ptr(),
+                         cache.pos[l, b0].data_ptr(), 1, nb, w.Hkv, w.Hq, w.D, cache.k.shape[3])
+    ws = torch.zeros(lib.ngc_workspace_bytes(C.byref(view), max_keep), dtype=torch.uint8, device="cuda")
+    p = ngc.make_params(noise_scale=1.0, round=0, seed=w.gumbel_seed, layer_base=l, seq_base=b0)
+    print(f"[view] layer_base={l} seq_base={b0} B={nb}", flush=True)
+    rc = lib.ngc_evict(C.byref(view), 0, logits[l, b0].data_ptr(), keep[l, b0].data_ptr(), C.byref(p), max_keep,
+                       kept.data_ptr(), sigma.data_ptr(), logp.data_ptr(), ws.data_ptr(), ws.numel(),
+                       torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    for j in range(nb):
+        for h in range(w.Hkv):
+            K = int(case.keep[l, b0 + j, h])
+            okept, osig = orc.evict_select(case.logits[(l, b0 + j, h)], K, 1.0, w.gumbel_seed, 0, l, b0 + j, h)
+            assert kept[j, h, :K].cpu().tolist() == okept.tolist()
+            assert sigma[j, h, :K].cpu().tolist() == osig.tolist()
+    assert torch.equal(kept, kept_w[l, b0:b0 + nb]) and torch.equal(sigma, sigma_w[l, b0:b0 + nb])
+    assert torch.equal(logp, logp_w[l, b0:b0 + nb])
+    assert torch.equal(cache.len[l, b0:b0 + nb], whole.len[l, b0:b0 + nb])
+    n_new = int(cache.len[l, b0:b0 + nb].max())
+    assert torch.equal(cache.k[l, b0:b0 + nb, :, :n_new], whole.k[l, b0:b0 + nb, :, :n_new]) or True
+    for j in range(nb):
+        for h in range(w.Hkv):
+            n = int(cache.len[l, b0 + j, h])
+            assert torch.equal(cache.k[l, b0 + j, h, :n], whole.k[l, b0 + j, h, :n])
+            assert torch.equal(cache.v[l, b0 + j, h, :n], whole.v[l, b0 + j, h, :n])
+    # the same view WITHOUT its bases draws the noise of (layer 0, sequence 0..): a different sample
+    cache2, logits2, keep2 = upload(case)
+    kept2 = torch.full_like(kept, -1)
+    view2 = ngc.ngc_cache(cache2.k[l, b0].data_ptr(), cache2.v[l, b0].data_ptr(), cache2.len[l, b0].data_ptr(),
+                          None, 1, nb, w.Hkv, w.Hq, w.D, cache2.k.shape[3])
+    p0 = ngc.make_params(noise_scale=1.0, round=0, seed=w.gumbel_seed)
+    rc = lib.ngc_evict(C.byref(view2), 0, logits2[l, b0].data_ptr(), keep2[l, b0].data_ptr(), C.byref(p0), max_keep,
+                       kept2.data_ptr(), None, None, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert not torch.equal(kept2, kept)
+    # host-side limits of the bases
+    bad = ngc.make_params(layer_base=65535)
+    assert lib.ngc_evict(C.byref(view), 0, logits.data_ptr(), keep.data_ptr(), C.byref(bad), max_keep, kept.data_ptr(),
+                         None, None, ws.data_ptr(), ws.numel(), None) == ngc.NGC_EINVAL
+
+
+# ----------------------------------------------- masked and invalid logits -----
+
+def _masked_case(kind):
+    """A small case whose logits hold -inf (masked keys) / NaN in known places; returns (case, gpu logits per
+    segment, the logits the oracle sees)."""
+    w = synth.workload(1, L=1, B=3, n_lo=300, n_hi=1400)
+    case = host_case(w)
+    rng = np.random.default_rng(77)
+    gpu_logits = {}
+    for seg in case.segs:
+        s = case.logits[seg].copy()
+        n = s.size
+        if kind == "some":                       # a third of the entries masked
+            s[rng.random(n) < 0.33] = -np.inf
+        elif kind == "most":                     # fewer finite entries than the keep count: masked ones get picked
+            s[rng.random(n) < 0.8] = -np.inf
+        elif kind == "all":
+            s[:] = -np.inf
+        g = s.copy()
+        if kind == "nan":                        # NaN is read as -inf by the kernel; the oracle is given -inf
+            bad = rng.random(n) < 0.7
+            g[bad] = np.nan
+            s[bad] = -np.inf
+        case.logits[seg] = s
+        gpu_logits[seg] = g
+    return case, gpu_logits
+
+
+@pytest.mark.parametrize("kind", ["some", "most", "all", "nan"])
+@pytest.mark.parametrize("tau", [1.0, 0.0])
+def test_masked_logits(kind, tau):
+    """-inf logits: taken only after every finite entry, lowest index first; a sequence that picks one has
+    log-probability -inf (never NaN); NaN logits count as -inf.  Indices, bytes and lengths stay bit-exact."""
+    import torch
+    ngc = _ngc()
+    case, gpu_logits = _masked_case(kind)
+    w = case.w
+    cache, logits, keep = upload(case, with_pos=True)
+    for (l, b, h), g in gpu_logits.items():
+        logits[l, b, h, :g.size] = torch.from_numpy(g).cuda()
+    max_keep = int(case.keep.max())
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.full((w.L, w.B, w.Hkv), float("nan"), dtype=torch.float32, device="cuda")
+    p = ngc.make_params(noise_scale=tau, round=3, seed=w.gumbel_seed)
+    print(f"[masked] kind={kind} tau={tau}", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    hlp = logp.cpu().numpy()
+    assert not np.isnan(hlp).any()
+    picked_masked = 0
+    for seg in case.segs:
+        l, b, h = seg
+        okept, osig, olp, ok, ov = oracle_evict_segment(case, seg, tau, w.gumbel_seed, 3)
+        K = okept.size
+        assert kept[l, b, h, :K].cpu().tolist() == okept.tolist(), seg
+        assert sigma[l, b, h, :K].cpu().tolist() == osig.tolist(), seg
+        if np.isinf(olp):
+            picked_masked += 1
+            assert hlp[l, b, h] == -np.inf, seg
+        else:
+            assert hlp[l, b, h] == pytest.approx(olp, rel=LOGP_RTOL, abs=1e-5), seg
+        assert int(cache.len[l, b, h]) == K
+        assert from_bf16_tensor(cache.k[l, b, h, :K]).tobytes() == ok.tobytes()
+        assert from_bf16_tensor(cache.v[l, b, h, :K]).tobytes() == ov.tobytes()
+    if kind in ("most", "all", "nan"):
+        assert picked_masked == len(case.segs)      # these cases are built so that masked entries are picked
+    # the separate log-probability entry point agrees on the same actions
+    nseg = w.L * w.B * w.Hkv
+    lp2 = torch.full((nseg,), float("nan"), dtype=torch.float32, device="cuda")
+    n_items = cache.len.new_tensor([case.k[s].shape[0] for s in case.segs])
+    ngc.ngc_subset_logprob(logits, n_items, sigma, keep.reshape(-1), nseg, logits.shape[-1], max_keep, lp2, ws)
+    torch.cuda.synchronize()
+    got2 = lp2.cpu().numpy()
+    assert not np.isnan(got2).any()
+    assert np.array_equal(np.isinf(got2), np.isinf(hlp.reshape(-1)))
+    fin = ~np.isinf(got2)
+    assert np.allclose(got2[fin], hlp.reshape(-1)[fin], rtol=2e-4)
+    assert all(x == 0 for x in ngc.read_status(ws))

@@ -27,7 +27,7 @@ def test_full_size_sampled_segments(idx):
     from paper_2604_18002_amd import binding as ngc
     ngc.load_library()
     w = synth.workload(idx)
-    segs = _sample_segments(w, 24, 100 + idx)
+    segs = _sample_segments(w, 64, 100 + idx)
     case = host_case(w, segs)
     keep_h = keep_table(w, case.lens)
     case.keep = keep_h
@@ -61,10 +61,9 @@ def test_full_size_sampled_segments(idx):
     v_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device="cuda").to(torch.bfloat16)
     q = torch.randn(w.L, w.B, w.Hq, w.D, generator=g, device="cuda").to(torch.bfloat16)
     out = torch.empty(w.L, w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
-    print("[full] append + decode attention, all layers", flush=True)
-    ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
+    print("[full] decode step (append + attention in one launch), all layers", flush=True)
     scale = 1.0 / np.sqrt(w.D)
-    ngc.ngc_decode_attn(cache, -1, q, scale, max_keep + w.delta, out, ws)
+    ngc.ngc_decode_step(cache, -1, k_new, v_new, None, q, scale, max_keep + w.delta, out, ws)
     torch.cuda.synchronize()
     assert all(x == 0 for x in ngc.read_status(ws))
     # lengths everywhere: budget + 1
@@ -100,3 +99,60 @@ def test_full_size_sampled_segments(idx):
     ksort = torch.where(valid, kept, torch.full_like(kept, 2 ** 30))
     assert torch.equal(ssort, ksort)
     assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(logp).all())
+
+
+@pytest.mark.parametrize("mode", ["unordered", "block32"])
+def test_full_size_config3_other_modes(mode):
+    """The two other compaction modes bench.py times at config 3's full size: hole filling (NGC_EVICT_UNORDERED)
+    and blocks of 32 rows with one noise draw per (layer, sequence); 32 sampled segments against the oracle."""
+    import torch
+    from paper_2604_18002_amd import binding as ngc
+    ngc.load_library()
+    w = synth.workload(3)
+    block = 32 if mode == "block32" else 1
+    segs = _sample_segments(w, 32, 300 + block)
+    case = host_case(w, segs, block=block)
+    keep_h = keep_table(w, case.lens, block)
+    case.keep = keep_h
+    max_keep = int(keep_h.max())
+    print(f"[full] config 3, mode={mode}, max_keep={max_keep}", flush=True)
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, w.cap)
+    synth.fill_normal_bf16_(cache.k, 1)
+    synth.fill_normal_bf16_(cache.v, 2)
+    logits = torch.empty(w.L, w.B, w.Hkv, w.cap, dtype=torch.float32, device="cuda")
+    synth.fill_logits_(logits, w, 3)
+    cache.len.copy_(torch.from_numpy(np.broadcast_to(case.lens[None, :, None], (w.L, w.B, w.Hkv)).copy()))
+    for seg in segs:
+        l, b, h = seg
+        n = case.k[seg].shape[0]
+        cache.k[l, b, h, :n] = to_bf16_tensor(case.k[seg], "cuda")
+        cache.v[l, b, h, :n] = to_bf16_tensor(case.v[seg], "cuda")
+        logits[l, b, h, :case.logits[seg].size] = torch.from_numpy(case.logits[seg]).cuda()
+    keep = torch.from_numpy(keep_h).cuda()
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.empty(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device="cuda")
+    sigma = torch.empty_like(kept)
+    logp = torch.empty(w.L, w.B, w.Hkv, dtype=torch.float32, device="cuda")
+    p = ngc.make_params(block=block, share_heads=1 if block > 1 else 0, noise_scale=1.0, round=0, seed=w.gumbel_seed,
+                        flags=ngc.EVICT_UNORDERED if mode == "unordered" else 0)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    for seg in segs:
+        l, b, h = seg
+        okept, osig, olp, ka, va = oracle_evict_segment(case, seg, 1.0, w.gumbel_seed, 0, block, block > 1)
+        K = okept.size
+        assert kept[l, b, h, :K].cpu().numpy().tolist() == okept.tolist(), seg
+        assert sigma[l, b, h, :K].cpu().numpy().tolist() == osig.tolist(), seg
+        assert float(logp[l, b, h]) == pytest.approx(olp, rel=1e-4), seg
+        if mode == "unordered":
+            ka = orc.compact_rows_unordered(case.k[seg], okept)
+            va = orc.compact_rows_unordered(case.v[seg], okept)
+        n_new = ka.shape[0]
+        assert int(cache.len[l, b, h]) == n_new, seg
+        assert bits(cache.k[l, b, h, :n_new]).tobytes() == ka.tobytes(), seg
+        assert bits(cache.v[l, b, h, :n_new]).tobytes() == va.tobytes(), seg
