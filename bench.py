@@ -2,17 +2,21 @@
 """Benchmark of the NGC hot path on one MI355X.
 
 A *step* is one grow-then-evict period of the whole batch: `delta` decode
-token-steps (append one K/V row per segment, then decode attention over the
-surviving rows, all layers) followed by one eviction round (Gumbel-top-k
-sample + ordered-subset log-probability + in-place compaction, all layers)
-that brings every segment back to its budget.  Inputs are synthetic, seeded,
-and resident in HBM before the timed region starts.
+token-steps, each of them L launches of ngc_decode_step (one per layer, the
+way a model has to call it: layer l + 1's query depends on layer l's output;
+every launch appends the new K/V row of its layer and attends over the
+surviving rows), followed by one eviction round (Gumbel-top-k sample +
+ordered-subset log-probability + in-place compaction, all layers in one
+launch) that brings every segment back to its budget.  Inputs are synthetic,
+seeded, and resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` is tokens/s of the whole cycle; the
 attention-only rate, the round-0 eviction time at peak cache, the roofline
 fractions (against the 8 TB/s vendor figure and against read / copy ceilings
-measured in the same job), the other entry points' timings, the same cycle
-over the paged layout and the CPU oracle's rate are reported beside it.
+measured in the same job), the same decode steps with all layers in one launch
+(secondary), the decode / eviction fractions of the other two configurations
+the target is quoted on, the other entry points' timings, the same cycle over
+the paged layout and the CPU oracle's rate are reported beside it.
 """
 from __future__ import annotations
 
@@ -32,15 +36,35 @@ if ROOT not in sys.path:
 METRIC = "decode-attn tokens/s + eviction-step µs over evicted cache; % HBM peak"
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per dispatch (bytes) measured with rocprofv3 --pmc FETCH_SIZE and
-# --pmc WRITE_SIZE on the unmodified workload, each counter scaled by what it
-# reads for a plain 1 GiB copy (summaries under profiles/).  Keyed by
-# (config, L, B); other shapes report null.
-MEASURED_TRAFFIC = {
-    (2, 28, 64): {"decode": 2.7623e9, "evict": 5.132e9},
-    (3, 28, 128): {"decode": 19.6671e9, "evict": 36.150e9},
-    (4, 4, 256): {"decode": 12.5546e9, "evict": 23.463e9},
+# HBM traffic per dispatch (bytes) from rocprofv3 --pmc FETCH_SIZE and --pmc
+# WRITE_SIZE runs of this command on the stock workloads, each counter scaled
+# by what it reads for a plain 1 GiB copy.  These are NOT counters of the run
+# that prints the line: they are copied from the committed summaries named
+# below and are reported together with that source.  Keyed by (config, L, B);
+# other shapes report null.  "decode" is one per-layer launch at the mean
+# length of a period.
+PROFILE_TRAFFIC = {
+    (2, 28, 64): {"file": "profiles/config2_kernels.txt"},
+    (3, 28, 128): {"file": "profiles/config3_kernels.txt"},
+    (4, 4, 256): {"file": "profiles/config4_kernels.txt"},
 }
+
+
+def profile_traffic(key, which):
+    """(bytes per dispatch, source) parsed from the committed summary, or (None, None)."""
+    ent = PROFILE_TRAFFIC.get(key)
+    if not ent:
+        return None, None
+    path = os.path.join(ROOT, ent["file"])
+    tag = {"decode": "bench-line traffic decode_per_layer:", "decode_batched": "bench-line traffic decode_batched:",
+           "evict": "bench-line traffic evict_round0:"}[which]
+    try:
+        for line in open(path):
+            if line.strip().startswith(tag):
+                return float(line.split(":", 1)[1].split()[0]), ent["file"]
+    except OSError:
+        pass
+    return None, None
 
 
 def parse_args():
@@ -59,6 +83,8 @@ def parse_args():
     ap.add_argument("--no-per-layer", dest="per_layer", action="store_false", help="skip the layer-by-layer timing")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout section")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming read / copy probes")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short eviction / decode measurement of the other configurations among configs[2..4]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy first (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -108,60 +134,210 @@ def evict_bytes(w, n_items: np.ndarray, keep: np.ndarray, moved_rows: float, wit
     return b
 
 
-def cpu_baseline(w, lens, keep, n_after_mid, budget_s=12.0):
-    """The oracle, as it stands, timed on segments of the workload until about
-    `budget_s` seconds of CPU work are spent: per segment one eviction round at
-    the steady-state size (select + log-prob + compaction) and one
-    decode-attention step at the mid-period length.  Scaled to a whole period
-    (delta token-steps, all segments)."""
+def layer_step_calls(ngc, cache, k_new, v_new, q, scale, hint, out, ws):
+    """A function that issues one ngc_decode_step per layer (append + attention), with the C arguments of every
+    layer built once."""
+    import ctypes as C
+    import torch
+    lib = ngc.load_library()
+    view = cache.view()
+    L = cache.k.shape[0]
+    stream = torch.cuda.current_stream().cuda_stream
+    fn = lib.ngc_decode_step
+    vref = C.byref(view)
+    calls = [(vref, l, k_new[l].data_ptr(), v_new[l].data_ptr(), None, q[l].data_ptr(), scale, hint,
+              out[l].data_ptr(), None, ws.data_ptr(), ws.numel(), stream) for l in range(L)]
+
+    def run():
+        for a in calls:
+            rc = fn(*a)
+            if rc != 0:
+                raise ngc.NgcError(rc, "ngc_decode_step")
+    run.keepalive = (view, k_new, v_new, q, out, ws)
+    return run
+
+
+def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
+    """Round-0 and steady-state eviction, and decode steps at `samples` lengths spread over a period (one launch
+    per layer, and all layers in one launch), of one workload; a few seconds."""
+    import torch
+    lens = synth.lengths(w)
+    keep_h = keep_budget(w, lens)
+    max_keep = int(keep_h.max())
+    nseg = w.L * w.B * w.Hkv
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, w.cap, device=dev)
+    synth.fill_normal_bf16_(cache.k, w.data_seed * 2 + 0)
+    synth.fill_normal_bf16_(cache.v, w.data_seed * 2 + 1)
+    logits = torch.empty(w.L, w.B, w.Hkv, w.cap, dtype=torch.float32, device=dev)
+    synth.fill_logits_(logits, w, w.data_seed * 2 + 2)
+    len0 = torch.from_numpy(np.broadcast_to(lens[None, :, None], (w.L, w.B, w.Hkv)).copy()).to(dev)
+    keep = torch.from_numpy(keep_h).to(dev)
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.empty(w.L, w.B, w.Hkv, max_keep, dtype=torch.int32, device=dev)
+    sigma = torch.empty_like(kept)
+    logp = torch.empty(w.L, w.B, w.Hkv, dtype=torch.float32, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.data_seed * 2 + 3)
+    q = torch.randn(w.L, w.B, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
+    k_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    v_new = torch.randn(w.L, w.B, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty(w.L, w.B, w.Hq, w.D, dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(w.D)
+    hint = max_keep + w.delta
+    slot = torch.arange(max_keep, device=dev, dtype=torch.int32)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def evict(rnd):
+        ngc.ngc_evict(cache, -1, logits, keep, ngc.make_params(noise_scale=1.0, round=rnd, seed=w.gumbel_seed),
+                      max_keep, kept, sigma if w.with_logprob else None, logp if w.with_logprob else None, ws)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    def moved_rows():
+        return float(((kept != slot) & (slot < keep.unsqueeze(-1))).sum().item())
+
+    p1 = []
+    for rep in range(evict_reps + 1):
+        cache.len.copy_(len0)
+        ms = timed(lambda: evict(0))
+        if rep:
+            p1.append(ms)
+    n0 = np.broadcast_to(lens[None, :, None], keep_h.shape)
+    p1_bytes = evict_bytes(w, n0, keep_h, moved_rows(), w.with_logprob, w.with_logprob)
+    steady = []
+    for rep in range(3):
+        cache.len.copy_(keep + w.delta)
+        steady.append(timed(lambda: evict(1 + rep)))
+    st_bytes = evict_bytes(w, keep_h + w.delta, keep_h, moved_rows(), w.with_logprob, w.with_logprob)
+    # decode steps at lengths spread over a period
+    step_call = layer_step_calls(ngc, cache, k_new, v_new, q, scale, hint, out, ws)
+    offs = sorted(set(int(round(x)) for x in np.linspace(0, w.delta - 1, samples)))
+    pl_ms = pl_b = ba_ms = ba_b = 0.0
+    for warm in (True, False):
+        for t in offs:
+            cache.len.copy_(keep + t)
+            ms = timed(step_call)
+            if not warm:
+                pl_ms += ms
+                pl_b += attn_bytes(w, int(keep_h.sum()) + (t + 1) * nseg, nseg)
+            cache.len.copy_(keep + t)
+            ms = timed(lambda: ngc.ngc_decode_step(cache, -1, k_new, v_new, None, q, scale, hint, out, ws))
+            if not warm:
+                ba_ms += ms
+                ba_b += attn_bytes(w, int(keep_h.sum()) + (t + 1) * nseg, nseg)
+            if warm and t >= offs[1]:
+                break
+    status = ngc.read_status(ws)
+    assert all(x == 0 for x in status), f"config {w.index}: device status words not clean: {status[:8]}"
+    p1_ms, st_ms = float(np.mean(p1)), float(np.mean(steady[1:]))
+    return {
+        "workload": f"configs[{w.index}] {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} peak cache "
+                    f"{w.n_lo}..{w.n_hi}, keep {w.keep_num}/{w.keep_den}, delta={w.delta}",
+        "eviction_step_us": 1e3 * p1_ms, "eviction_hbm_frac": p1_bytes / (p1_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "eviction_step_us_steady": 1e3 * st_ms, "eviction_steady_hbm_frac": st_bytes / (st_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "decode_per_layer_ms_per_token_step": pl_ms / len(offs),
+        "decode_per_layer_hbm_frac": pl_b / (pl_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "decode_per_layer_tokens_per_s": w.B * len(offs) / (pl_ms * 1e-3),
+        "decode_all_layers_per_launch_ms": ba_ms / len(offs),
+        "decode_all_layers_per_launch_hbm_frac": ba_b / (ba_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "what": f"eviction: mean of {evict_reps} round-0 launches at peak cache and of 2 steady-state rounds; decode: "
+                f"{len(offs)} token-steps at lengths spread over a period, HIP events around each token-step",
+    }
+
+
+def _cpu_segment_work(w, keep, n_after_mid, kbits, vbits, seg):
+    """One segment's share of a period on the oracle: (seconds of eviction, seconds of one decode-attention step)."""
     import oracle as orc
+    from paper_2604_18002_amd import synth
+    l, b, h = seg
+    K = int(keep[l, b, h])
+    n = K + w.delta
+    s = synth.segment_logits(w, l, b, h, n, rnd=1)
+    q = synth.queries(w, l)
+    t0 = time.perf_counter()
+    kept, sigma = orc.evict_select(s, K, 1.0, w.gumbel_seed, 1, l, b, h)
+    if w.with_logprob:
+        orc.logprob_suffix(s, sigma)
+    orc.compact_rows(kbits[:n], kept)
+    orc.compact_rows(vbits[:n], kept)
+    t_evict = time.perf_counter() - t0
+    m = int(n_after_mid[l, b, h])
+    t0 = time.perf_counter()
+    orc.decode_attn(q[b, h * w.G:(h + 1) * w.G], kbits[:m], vbits[:m], 1.0 / math.sqrt(w.D))
+    return t_evict, time.perf_counter() - t0
+
+
+def cpu_baseline(w, lens, keep, n_after_mid, budget_s=8.0):
+    """The oracle, as it stands, timed on segments of the workload: per segment one eviction round at the
+    steady-state size (select + log-prob + compaction) and one decode-attention step at the mid-period length,
+    scaled to a whole period (delta token-steps, all segments).  Two legs of about `budget_s` seconds each: one
+    thread, then one thread per host core given to this job (the oracle is C behind ctypes, which releases the
+    interpreter lock, so plain threads run it in parallel)."""
+    from concurrent.futures import ThreadPoolExecutor
     from paper_2604_18002_amd import synth
     rng = np.random.default_rng(w.data_seed)
     kmax = int(keep.max()) + w.delta
     kbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
     vbits = synth.f32_to_bf16_bits(rng.standard_normal((kmax, w.D), dtype=np.float32))
-    scale = 1.0 / math.sqrt(w.D)
+    segs = [(l, b, h) for l in range(w.L) for b in range(w.B) for h in range(w.Hkv)]
+    total_segs = len(segs)
+    # ---- one thread
     t_evict = t_attn = 0.0
-    nsegs = 0
-    done = False
-    for l in range(w.L):
-        q = synth.queries(w, l)
-        for b in range(w.B):
-            for h in range(w.Hkv):
-                K = int(keep[l, b, h])
-                n = K + w.delta
-                s = synth.segment_logits(w, l, b, h, n, rnd=1)
-                t0 = time.perf_counter()
-                kept, sigma = orc.evict_select(s, K, 1.0, w.gumbel_seed, 1, l, b, h)
-                if w.with_logprob:
-                    orc.logprob_suffix(s, sigma)
-                orc.compact_rows(kbits[:n], kept)
-                orc.compact_rows(vbits[:n], kept)
-                t_evict += time.perf_counter() - t0
-                m = int(n_after_mid[l, b, h])
-                t0 = time.perf_counter()
-                orc.decode_attn(q[b, h * w.G:(h + 1) * w.G], kbits[:m], vbits[:m], scale)
-                t_attn += time.perf_counter() - t0
-                nsegs += 1
-                done = (t_evict + t_attn) >= budget_s
-                if done:
-                    break
-            if done:
-                break
-        if done:
+    n1 = 0
+    for seg in segs:
+        te, ta = _cpu_segment_work(w, keep, n_after_mid, kbits, vbits, seg)
+        t_evict += te
+        t_attn += ta
+        n1 += 1
+        if t_evict + t_attn >= budget_s:
             break
-    total_segs = w.L * w.B * w.Hkv
-    per_seg_period = (t_evict + w.delta * t_attn) / nsegs      # seconds of CPU per segment and period
-    period = per_seg_period * total_segs
+    per_seg_period = (t_evict + w.delta * t_attn) / n1       # seconds of CPU per segment and period
+    one = w.B * w.delta / (per_seg_period * total_segs)
+    # ---- every core of this job (the GPU boxes give a one-GPU job 16 cores, whatever os.cpu_count() shows)
+    cores_total = os.cpu_count() or 1
+    try:
+        cores_total = min(cores_total, len(os.sched_getaffinity(0)))
+    except (AttributeError, OSError):
+        pass
+    workers = max(1, min(cores_total, 16))
+    per_seg_s = (t_evict + t_attn) / n1
+    nn = max(workers, min(total_segs - n1, int(budget_s * workers / max(per_seg_s, 1e-6))))
+    batch = segs[n1:n1 + nn] if n1 + nn <= total_segs else segs[:nn]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        res = list(ex.map(lambda sg: _cpu_segment_work(w, keep, n_after_mid, kbits, vbits, sg), batch))
+    wall = time.perf_counter() - t0
+    te_all, ta_all = sum(r[0] for r in res), sum(r[1] for r in res)
+    # wall time per segment with all workers busy, split between the two phases in proportion to their CPU time
+    wall_per_seg = wall / len(batch)
+    share_attn = ta_all / (te_all + ta_all)
+    period_all = (wall_per_seg * (1 - share_attn) + w.delta * wall_per_seg * share_attn) * total_segs
     return {
-        "value": w.B * w.delta / period, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-        "sample": f"{nsegs} of {total_segs} (layer, sequence, head) segments: per segment one eviction round "
-                  f"(select + log-prob + compaction, {'budget + delta -> budget'}) and one decode-attention step at "
+        "value": one, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": f"{n1} of {total_segs} (layer, sequence, head) segments: per segment one eviction round "
+                  f"(select + log-prob + compaction, budget + delta -> budget) and one decode-attention step at "
                   f"mid-period length; scaled to all segments and {w.delta} token-steps per period; "
                   f"fp64 single-threaded oracle",
-        "eviction_step_us": 1e6 * t_evict / nsegs * total_segs,
-        "decode_attn_tokens_per_s": w.B / (t_attn / nsegs * total_segs),
+        "eviction_step_us": 1e6 * t_evict / n1 * total_segs,
+        "decode_attn_tokens_per_s": w.B / (t_attn / n1 * total_segs),
         "cpu_seconds": t_evict + t_attn,
+        "cores_total": cores_total,
+        "all_cores": {
+            "value": w.B * w.delta / period_all, "unit": "tokens/s", "cores": workers, "kind": "oracle",
+            "sample": f"{len(batch)} further segments, same work per segment, {workers} threads (one per host core of "
+                      f"this job; {cores_total} visible), wall {wall:.1f} s",
+            "eviction_step_us": 1e6 * wall_per_seg * (1 - share_attn) * total_segs,
+            "decode_attn_tokens_per_s": w.B / (wall_per_seg * share_attn * total_segs),
+        },
     }
 
 
@@ -191,30 +367,11 @@ def main():
         del a, b
 
     # ------------------------------------------- streaming ceilings, same job
-    # (16 bytes per lane, grid-stride, 8 GiB: what this machine gives the plainest read and copy kernels)
+    # (libngc_probe.so: what this machine gives the plainest read, fill and copy kernels over 8 GiB)
     ceilings = None
     if not args.no_ceilings:
-        nb = 8 << 30
-        src = torch.empty(nb, dtype=torch.uint8, device=dev)
-        dst = torch.empty(nb, dtype=torch.uint8, device=dev)
-        src.fill_(1)
-        dst.fill_(2)
-        ceilings = {"bytes": nb, "what": "ngc_probe_stream over 8 GiB, best of 3 after a warm-up; copy counts read + write"}
-        for name, kind, factor in (("read", ngc.PROBE_READ, 1.0), ("read_nontemporal", ngc.PROBE_READ_NT, 1.0),
-                                   ("copy", ngc.PROBE_COPY, 2.0), ("copy_nontemporal", ngc.PROBE_COPY_NT, 2.0)):
-            best = None
-            for rep in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                ngc.ngc_probe_stream(kind, src, dst, nb)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep > 0:
-                    ms = e0.elapsed_time(e1)
-                    best = ms if best is None or ms < best else best
-            ceilings[name + "_GBs"] = factor * nb / (best * 1e-3) / 1e9
-        del src, dst
-        torch.cuda.empty_cache()
+        from paper_2604_18002_amd import probe
+        ceilings = probe.streaming_ceilings(8 << 30)
 
     # ---------------------------------------------------------------- inputs
     lens = synth.lengths(w)                                   # [B] peak rows per sequence
@@ -278,16 +435,19 @@ def main():
     p1_us = 1e3 * float(np.mean(p1_ms))
 
     # ------------------------------------------- steady-state periods (steps)
+    # One launch per layer and token-step.  The launches go through the library's C entry point directly with
+    # their arguments marshalled once (what the binding would build on every call), so that the host never is
+    # what the GPU waits for.
     rows_after = int(keep_h.sum())             # rows in use right after a round
+    step_call = layer_step_calls(ngc, cache, k_new, v_new, q, scale, hint, out, ws)
     attn_events = []
 
     def period(rnd, record):
         for t in range(w.delta):
-            ngc.ngc_cache_append(cache, -1, k_new, v_new, None, ws)
             if record:
                 e0, e1 = ev(), ev()
                 e0.record()
-            ngc.ngc_decode_attn(cache, -1, q, scale, hint, out, ws)
+            step_call()
             if record:
                 e1.record()
                 attn_events.append((e0, e1, rows_after + (t + 1) * nseg))
@@ -312,7 +472,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    attn_ms = sum(a.elapsed_time(b) for a, b, _ in attn_events)
+    attn_ms = sum(a.elapsed_time(b) for a, b, _ in attn_events)             # per token-step: L launches
     attn_b = sum(attn_bytes(w, rows, nseg) for _, _, rows in attn_events)
     n_attn = len(attn_events)
     steady_evict_ms = [a.elapsed_time(b) for a, b in evict_events]
@@ -324,6 +484,56 @@ def main():
     value = tokens / elapsed
     attn_gbs = attn_b / (attn_ms * 1e-3) / 1e9
     p1_gbs = p1_bytes / (p1_us * 1e-6) / 1e9
+
+    # ---- secondary: the same decode steps with all layers in ONE launch (what the kernel does when the launch is
+    # large; a model cannot issue it), over one period
+    batched_events = []
+    for t in range(w.delta):
+        e0, e1 = ev(), ev()
+        e0.record()
+        ngc.ngc_decode_step(cache, -1, k_new, v_new, None, q, scale, hint, out, ws)
+        e1.record()
+        batched_events.append((e0, e1, rows_after + (t + 1) * nseg))
+    evict(rnd)
+    rnd += 1
+    torch.cuda.synchronize()
+    bat_ms = sum(a.elapsed_time(b) for a, b, _ in batched_events)
+    bat_b = sum(attn_bytes(w, rows, nseg) for _, _, rows in batched_events)
+    bat_gbs = bat_b / (bat_ms * 1e-3) / 1e9
+
+    # ---- the per-layer token-step from a HIP graph (L launches captured once at the mid-period length)
+    graph_info = None
+    if args.per_layer:
+        cache.len.copy_(keep + w.delta // 2)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for l in range(w.L):
+                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        eager = out.clone()
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph):
+            for l in range(w.L):
+                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+        out.zero_()
+        gph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "graph replay differs from the eager launches"
+        reps = 20
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            gph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        gms = e0.elapsed_time(e1) / reps
+        mid_bytes = attn_bytes(w, rows_after + (w.delta // 2) * nseg, nseg)
+        graph_info = {"what": "L per-layer ngc_decode_attn launches at the mid-period length, captured once and replayed",
+                      "ms_per_token_step": gms, "hbm_frac": mid_bytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del gph
+        cache.len.copy_(keep)
 
     status = ngc.read_status(ws)
     assert all(x == 0 for x in status), f"device status words not clean: {status[:8]}"
@@ -497,7 +707,7 @@ def main():
     pooled = None
     if w.per_head_budget and w.Hkv * cap <= 65536:
         ws_p = torch.zeros(ngc.ngc_workspace_bytes(cache, cap) + 4 * nseg * cap, dtype=torch.uint8, device=dev)
-        kept_p = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.int32, device=dev)
+        kept_p = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.int32, device=dev)   # a head may keep more than its even share
         sigma_p = torch.empty_like(kept_p)
         pl_ms = []
         for rep in range(3):
@@ -576,47 +786,6 @@ def main():
 
     replay = {"what": "ngc_replay_attn, one layer, rounds every delta tokens, random survivors; bound: bf16 MFMA 2.5 PFLOP/s",
               "per_token_eviction": replay_case(1), "block32_eviction": replay_case(32)}
-
-    per_layer = None
-    if args.per_layer:
-        reps = 20
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for _ in range(reps):
-            for l in range(w.L):
-                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        per_layer = {"ms_per_token_step": ms, "tokens_per_s": w.B / (ms * 1e-3),
-                     "hbm_frac": attn_bytes(w, rows_after, nseg) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        # the same L launches captured once in a HIP graph and replayed (no per-launch host work)
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            for l in range(w.L):
-                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        eager = out.clone()
-        gph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gph):
-            for l in range(w.L):
-                ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
-        out.zero_()
-        gph.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(out, eager), "graph replay differs from the eager launches"
-        e0, e1 = ev(), ev()
-        e0.record()
-        for _ in range(reps):
-            gph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        gms = e0.elapsed_time(e1) / reps
-        per_layer["hip_graph_ms_per_token_step"] = gms
-        per_layer["hip_graph_hbm_frac"] = attn_bytes(w, rows_after, nseg) / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     # ---- the same cycle over the paged layout (pages of 32 rows = the paper's blocks): eviction edits page
     # tables, nothing moves; decode attention and append go through the table.  Runs last: the contiguous
@@ -714,6 +883,33 @@ def main():
             "rows_per_segment_after_round": rows_after_p / nseg,
         }
 
+    # ---- the other two configurations the target is quoted on: round-0 / steady-state eviction and a sampled
+    # period of per-layer and all-layer decode steps (the big buffers of the main workload are released first)
+    other = None
+    if not args.no_other_configs:
+        # (a `del` of a name the paged section already deleted raises; every name gets its own try)
+        try: del cache
+        except NameError: pass
+        try: del logits
+        except NameError: pass
+        try: del kept, sigma
+        except NameError: pass
+        try: del scores
+        except NameError: pass
+        try: del ws, step_call
+        except NameError: pass
+        try: del pc, plog, kept_p, sigma_p, ws_p, table0, stack0
+        except NameError: pass
+        try: del eager
+        except NameError: pass
+        torch.cuda.empty_cache()
+        other = {}
+        for idx in (2, 3, 4):
+            if idx == w.index:
+                continue
+            other[str(idx)] = quick_config(ngc, synth, synth.workload(idx), dev)
+            torch.cuda.empty_cache()
+
     line = {
         "metric": METRIC,
         "value": value,
@@ -731,8 +927,9 @@ def main():
             "workload": f"{'configs[%d]' % w.index if w.index < 5 else 'extra (paper-shaped, not a BASELINE config)'} {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} "
                         f"peak cache {w.n_lo}..{w.n_hi} rows, keep {w.keep_num}/{w.keep_den} (budget rule), "
                         f"delta={w.delta}, logits {w.logits_kind}, log-prob {'on' if w.with_logprob else 'off'}",
-            "step": f"{w.delta} x (append + decode attention, all {w.L} layers in one launch) + 1 eviction round "
-                    "(one launch per layer is timed separately: decode_attn_per_layer_launches)",
+            "step": f"{w.delta} token-steps x {w.L} launches of ngc_decode_step (one per layer: append + decode "
+                    "attention) + 1 eviction round (all layers in one launch); all layers per decode launch is "
+                    "timed separately: roofline_decode_all_layers_per_launch",
             "tokens_per_step": w.B * w.delta,
         },
         "decode_attn_tokens_per_s": w.B * n_attn / (attn_ms * 1e-3),
@@ -741,23 +938,39 @@ def main():
         "eviction_step_us_steady": steady_us,
         "eviction_steady_hbm_frac": steady_bytes / (steady_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
-            "kernel": "decode_partial_kernel<%d>" % w.D,
+            "kernel": "decode_kernel<%d, false, true>, one launch per layer (append fused)" % w.D,
             "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": attn_gbs / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("decode"),
-            "bytes_per_launch": attn_b / n_attn, "launch_ms": attn_ms / n_attn, "launches": n_attn,
+            "traffic": profile_traffic((w.index, w.L, w.B), "decode")[0],
+            "traffic_source": profile_traffic((w.index, w.L, w.B), "decode")[1],
+            "bytes_per_launch": attn_b / n_attn / w.L, "launch_ms": attn_ms / n_attn / w.L, "launches": n_attn * w.L,
+            "launch_ms_note": "HIP events around every token-step of the timed region (L back-to-back launches on the "
+                              "stream) divided by L: includes the gaps between launches",
             "frac_of_measured_read_ceiling": (attn_gbs / max(ceilings["read_GBs"], ceilings["read_nontemporal_GBs"])
                                               if ceilings else None),
         },
+        "roofline_decode_all_layers_per_launch": {
+            "what": "the same decode steps with all layers in one launch (a model cannot issue this; it shows the kernel "
+                    "when a launch is large), one period",
+            "kernel": "decode_kernel<%d, false, true>" % w.D,
+            "bound": "hbm", "achieved": bat_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bat_gbs / HBM_PEAK_GBS,
+            "traffic": profile_traffic((w.index, w.L, w.B), "decode_batched")[0],
+            "traffic_source": profile_traffic((w.index, w.L, w.B), "decode_batched")[1],
+            "bytes_per_launch": bat_b / len(batched_events), "launch_ms": bat_ms / len(batched_events),
+            "tokens_per_s": w.B * len(batched_events) / (bat_ms * 1e-3),
+        },
+        "decode_attn_per_layer_hip_graph": graph_info,
         "roofline_evict": {
             "kernels": "evict_kernel (selection + log-prob + in-place compaction fused; round 0 at peak cache)",
             "bound": "hbm", "achieved": p1_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": p1_gbs / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get((w.index, w.L, w.B), {}).get("evict"),
+            "traffic": profile_traffic((w.index, w.L, w.B), "evict")[0],
+            "traffic_source": profile_traffic((w.index, w.L, w.B), "evict")[1],
             "bytes_per_round": p1_bytes, "round_ms": p1_us / 1e3, "moved_rows": moved0,
-            "frac_of_measured_copy_ceiling": (p1_gbs / max(ceilings["copy_GBs"], ceilings["copy_nontemporal_GBs"])
-                                              if ceilings else None),
+            "frac_of_measured_copy_ceiling": (p1_gbs / max(ceilings["copy_GBs"], ceilings["copy_nontemporal_GBs"],
+                                                           ceilings["copy_best_shape_GBs"]) if ceilings else None),
         },
+        "other_configs": other,
         "eviction_unordered": unordered,
         "eviction_block32_shared_heads": block32,
         "scoring": scoring,
@@ -786,8 +999,6 @@ def main():
         },
         "setup_s": t_setup,
     }
-    if per_layer:
-        line["decode_attn_per_layer_launches"] = per_layer
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, lens, keep_h, n_mid)
     print(json.dumps(line), flush=True)

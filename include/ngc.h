@@ -456,20 +456,6 @@ int ngc_paged_score_keys(const ngc_paged_cache *pc, int32_t layer, const void *q
                          float scale, uint32_t flags, int32_t block, float *scores_out,
                          void *ws, size_t ws_bytes, void *stream);
 
-/* Diagnostic, not part of the method: stream `bytes` bytes (a multiple of 16,
- * both pointers 16-byte aligned) through the plainest kernels there are, so a
- * harness can time what this machine's memory system gives next to the
- * library's own kernels.
- *   NGC_PROBE_READ / _READ_NT   read src (plain / nontemporal loads); dst is
- *                               only a sink of >= 16 bytes that is (almost)
- *                               never written
- *   NGC_PROBE_COPY / _COPY_NT   dst[i] = src[i] (plain / nontemporal accesses) */
-#define NGC_PROBE_READ    0
-#define NGC_PROBE_COPY    1
-#define NGC_PROBE_READ_NT 2
-#define NGC_PROBE_COPY_NT 3
-int ngc_probe_stream(int32_t kind, const void *src, void *dst, size_t bytes, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -38,9 +38,8 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob", "ngc_cache_append", "ngc_decode_attn", "ngc_score_keys",
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
-           "ngc_paged_score_keys", "ngc_probe_stream", "ngc_lmem", "ngc_keep_counts", "ngc_decode_attn_static", "ngc_decode_step")
+           "ngc_paged_score_keys", "ngc_lmem", "ngc_keep_counts", "ngc_decode_attn_static", "ngc_decode_step")
 STATIC_SCRATCH_BYTES = 16 << 20
-PROBE_READ, PROBE_COPY, PROBE_READ_NT, PROBE_COPY_NT = 0, 1, 2, 3
 
 
 class NgcError(RuntimeError):
@@ -133,8 +132,6 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ngc_lmem.restype = C.c_int
     lib.ngc_keep_counts.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ngc_keep_counts.restype = C.c_int
-    lib.ngc_probe_stream.argtypes = [i32, vp, vp, sz, vp]
-    lib.ngc_probe_stream.restype = C.c_int
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -385,10 +382,6 @@ def ngc_paged_score_keys(pc: PagedCache, layer: int, q_recent, w: int, scale: fl
     _check(load_library().ngc_paged_score_keys(C.byref(v), layer, _ptr(q_recent), _ptr(lse_recent), w, scale, flags,
                                                block, _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
            "ngc_paged_score_keys")
-
-
-def ngc_probe_stream(kind: int, src, dst, nbytes: int, stream=None):
-    _check(load_library().ngc_probe_stream(kind, _ptr(src), _ptr(dst), nbytes, _stream(stream)), "ngc_probe_stream")
 
 
 def ngc_lmem(logp, rounds, reward, R: int, L: int, B: int, Hkv: int, group: int, adv_out, loss_layer, loss,

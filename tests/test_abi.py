@@ -12,8 +12,8 @@ from paper_2604_18002_amd import _build, schedule
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "ngc.h")).read()
+def _declared(header="ngc.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ngc_[a-z_]+)\s*\(", text)))
 
@@ -34,6 +34,21 @@ def test_header_and_binding_name_the_same_entry_points():
 def test_library_exports_every_declared_symbol(lib):
     for name in _declared():
         assert hasattr(lib, name), name
+
+
+def test_probe_library_exports_what_its_header_declares(lib):
+    """include/ngc_probe.h is the boundary of the second, measurement-only library."""
+    from paper_2604_18002_amd import probe
+    assert os.listdir(os.path.join(ROOT, "include")) == ["ngc.h", "ngc_probe.h"] or \
+        sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ngc.h", "ngc_probe.h"]
+    assert _declared("ngc_probe.h") == sorted(probe.EXPORTS)
+    plib = probe.load_library()
+    for name in _declared("ngc_probe.h"):
+        assert hasattr(plib, name), name
+    # host-side argument checks, no GPU needed
+    assert plib.ngc_probe_stream(1, None, None, 16, None) == -1
+    assert plib.ngc_probe_copy_shape(0x1000, 0x2000, 1 << 20, 384, 4, 8, 0, None) == -1
+    assert plib.ngc_probe_compact(0x1000, 0x2000, 0x3000, 0x4000, 1, 100, 200, 256, 4, 0, None) == -1
 
 
 def test_version_and_strerror(lib):
