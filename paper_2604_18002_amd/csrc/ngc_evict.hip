@@ -463,8 +463,10 @@ __device__ __forceinline__ void compact_pos_inplace(int32_t *pos, const int32_t 
 // Item order (for ties and for the sampled sequence) is (head, row); the noise
 // of item (head, row) is the one the per-head mode draws for it.  Up to
 // Hkv * cap = 65536 items: their key codes live in a workspace in global
-// memory (L2-resident while the workgroup works on them), the index buffers of
-// the sort stay in LDS.  Steps as in select_segment.
+// memory (read in order by the select passes), the kept items' codes and item
+// indices in two dense arrays next to them (K entries, served by the L2 cache
+// to the sort), the index buffers of the sort in LDS.  Select and sort are the
+// shared routines of ngc_select.h.
 
 constexpr int POOL_THREADS = 1024;
 constexpr int POOL_MAX_HEADS = 16;
@@ -491,7 +493,10 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
     const int lb = a.seg0 / Hkv + blockIdx.x;     // layer * B + sequence
     const int l = lb / a.g.B, b = lb - l * a.g.B;
     const int seg_first = lb * Hkv;
-    uint32_t *code = a.pool_codes + (size_t)lb * Hkv * cap;
+    // per (layer, sequence): [codes of all items][codes of the kept items][item index of the kept items]
+    uint32_t *code = a.pool_codes + (size_t)lb * Hkv * cap * 3;
+    uint32_t *kcode = code + (size_t)Hkv * cap;
+    uint16_t *items = reinterpret_cast<uint16_t *>(kcode + (size_t)Hkv * cap);
 
     // ---- 0. geometry of the pooled item space ------------------------------
     if (tid == 0) {
@@ -563,55 +568,15 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
     }
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
 
-    // ---- 2. radix select ---------------------------------------------------
-    uint32_t prefix = 0, pmask = 0;
-    int need = K;
-    {
-        const int shifts[3] = {21, 10, 0};
-        const int widths[3] = {11, 11, 10};
-#pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = shifts[pass], nb = 1 << widths[pass];
-            if (pass > 0) {
-                for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
-                __syncthreads();
-                for (int t = tid; t < N; t += THREADS) {
-                    const uint32_t u = code[t];
-                    if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
-                }
-            }
-            __syncthreads();   // pass 0: also publishes the codes written in step 1
-            const int per = (nb + THREADS - 1) / THREADS;
-            int mine = 0;
-            for (int i = 0; i < per; ++i) {
-                const int p = tid * per + i;
-                if (p < nb) mine += (int)hist[nb - 1 - p];
-            }
-            int total;
-            int above = block_excl_scan_i<THREADS>(mine, misc, &total);
-            if (above < need && need <= above + mine) {
-                for (int i = 0; i < per; ++i) {
-                    const int p = tid * per + i;
-                    const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
-                    if (need <= above + c) {
-                        misc[32] = nb - 1 - p;
-                        misc[33] = above;
-                        break;
-                    }
-                    above += c;
-                }
-            }
-            __syncthreads();
-            const uint32_t digit = (uint32_t)misc[32];
-            need -= misc[33];
-            prefix |= digit << shift;
-            pmask |= (uint32_t)(nb - 1) << shift;
-            __syncthreads();
-        }
-    }
-    const uint32_t thr = prefix;
+    // ---- 2. radix select (the first histogram was accumulated with the keys) --
+    int need;
+    __syncthreads();   // publishes the codes and the histogram of step 1
+    const uint32_t thr = radix_select_kth<THREADS>([&](int t) { return code[t]; }, N, K, hist, misc, need, true);
 
     // ---- 3. kept items, ascending in (head, row) order ----------------------
+    // Slot j of the kept list gets its item index (items[j]) and its code (kcode[j]) in two dense arrays next to
+    // the codes, so that everything after this step works on K entries read in order or from the L2 cache
+    // instead of gathering from the N codes.
     const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
     const int w_begin = wv * per_wave;
     const int w_end = (w_begin + per_wave < N) ? (w_begin + per_wave) : N;
@@ -639,7 +604,10 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
         const int eq_before = eq_base + popc_below(beq);
         const bool sel = is_gt || (is_eq && eq_before < need);
         if (sel) {
-            idxA[gt_before + (eq_before < need ? eq_before : need)] = (uint16_t)t;
+            const int slot = gt_before + (eq_before < need ? eq_before : need);
+            items[slot] = (uint16_t)t;
+            kcode[slot] = u;
+            idxA[slot] = (uint16_t)slot;
         } else if (in && want_logp) {
             const int h = head_of(t);
             float x = a.logits[(size_t)(seg_first + h) * cap + (t - misc[PM_OFF + h])];
@@ -649,91 +617,37 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
         gt_base += __popcll(bgt);
         eq_base += __popcll(beq);
     }
-    __syncthreads();
+    __syncthreads();   // items, kcode (global, this workgroup's own) and idxA are complete
     // kept slots before each head: first slot whose item lies at or beyond the head's offset
     if (tid <= Hkv) {
         const int target = misc[PM_OFF + tid];
         int lo = 0, hi = K;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if ((int)idxA[mid] < target) lo = mid + 1; else hi = mid;
+            if ((int)items[mid] < target) lo = mid + 1; else hi = mid;
         }
         misc[PM_BASE + tid] = lo;
     }
     __syncthreads();
+    auto head_of_slot = [&](int j) {
+        int h = 0;
+        while (h + 1 < Hkv && j >= misc[PM_BASE + h + 1]) ++h;
+        return h;
+    };
     for (int j = tid; j < K; j += THREADS) {
-        const int i = idxA[j];
-        const int h = head_of(i);
+        const int h = head_of_slot(j);
         const int slot = j - misc[PM_BASE + h];
-        if (slot < a.max_keep) a.kept_out[(size_t)(seg_first + h) * a.max_keep + slot] = i - misc[PM_OFF + h];
+        if (slot < a.max_keep) a.kept_out[(size_t)(seg_first + h) * a.max_keep + slot] = (int)items[j] - misc[PM_OFF + h];
     }
     if (tid < Hkv && misc[PM_BASE + tid + 1] - misc[PM_BASE + tid] > a.max_keep)
         atomicAdd(&a.status[NGC_STATUS_KEEP_CLAMPED], 1);
 
     if (want_sort) {
-        // ---- 4. sigma ------------------------------------------------------
-        const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-        const int k_begin = wv * per_wave_k;
-        const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
-        uint16_t *src = idxA, *dst = idxB;
-        volatile uint32_t *vh = hist;
-        const uint32_t range = cmax - thr;
-        const int range_bits = range ? 32 - __clz(range) : 0;
-        const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
-        __syncthreads();   // kept_out loop above still reads idxA
-#pragma unroll 1
-        for (int pass = 0; pass < passes; ++pass) {
-            const int shift = SORT_BITS * pass;
-            for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
-            __syncthreads();
-            for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-                const int j = j0 + lane;
-                if (j < k_end) {
-                    const uint32_t d = ((cmax - code[src[j]]) >> shift) & (SORT_BINS - 1);
-                    atomicAdd(&hist[wv * SORT_BINS + d], 1u);
-                }
-            }
-            __syncthreads();
-            {
-                constexpr int PER = SORT_BINS * NW / THREADS;
-                int vals[PER], sum = 0;
-#pragma unroll
-                for (int i = 0; i < PER; ++i) {
-                    const int e = tid * PER + i;
-                    vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
-                    sum += vals[i];
-                }
-                int total;
-                int run = block_excl_scan_i<THREADS>(sum, misc, &total);
-#pragma unroll
-                for (int i = 0; i < PER; ++i) {
-                    const int e = tid * PER + i;
-                    hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
-                    run += vals[i];
-                }
-            }
-            __syncthreads();
-            for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-                const int j = j0 + lane;
-                const bool in = j < k_end;
-                const uint16_t idx = in ? src[j] : (uint16_t)0;
-                const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
-                const uint64_t peers = match_digit(d, __ballot(in));
-                const int rank = popc_below(peers);
-                uint32_t base = 0;
-                if (in) base = vh[wv * SORT_BINS + d];
-                __builtin_amdgcn_wave_barrier();
-                if (in) {
-                    dst[base + rank] = idx;
-                    if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
-                }
-                __builtin_amdgcn_wave_barrier();
-            }
-            __syncthreads();
-            uint16_t *tmp = src; src = dst; dst = tmp;
-        }
-        auto logit_of_item = [&](int i) {
-            const int h = head_of(i);
+        // ---- 4. sigma: the slots sorted by descending code ---------------------
+        const uint16_t *src = sort_by_code_desc<THREADS>([&](uint16_t j) { return kcode[j]; }, K, cmax, thr, idxA, idxB,
+                                                         hist, misc);
+        auto logit_of_slot = [&](int j) {
+            const int i = items[j], h = head_of_slot(j);
             const float x = a.logits[(size_t)(seg_first + h) * cap + (i - misc[PM_OFF + h])];
             return (x != x) ? -INFINITY : x;
         };
@@ -742,9 +656,8 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
             int32_t *sig_row = a.sigma_out + (size_t)seg_first * a.max_keep;
             const int room = Hkv * a.max_keep;
             for (int j = tid; j < K && j < room; j += THREADS) {
-                const int i = src[j];
-                const int h = head_of(i);
-                sig_row[j] = h * cap + (i - misc[PM_OFF + h]);
+                const int slot = src[j], h = head_of_slot(slot);
+                sig_row[j] = h * cap + ((int)items[slot] - misc[PM_OFF + h]);
             }
         }
         if (want_logp) {
@@ -757,14 +670,14 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
             const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
             float mass = 0.f;
             if (cidx >= 0)
-                for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of_item(src[j]) - smax);
+                for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of_slot(src[j]) - smax);
             float total_mass;
             const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
             float acc = 0.f;
             if (cidx >= 0) {
                 float R = U + after;
                 for (int j = j_hi - 1; j >= j_lo; --j) {
-                    const float d = logit_of_item(src[j]) - smax;
+                    const float d = logit_of_slot(src[j]) - smax;
                     R += expf(d);
                     acc += (d == -INFINITY) ? -INFINITY : d - logf(R);
                 }
@@ -993,7 +906,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
         if (p->block != 1 || (p->flags & NGC_EVICT_UNORDERED)) return NGC_EUNSUPPORTED;
         if (c->Hkv > POOL_MAX_HEADS || (long long)c->Hkv * c->cap > 65536) return NGC_EUNSUPPORTED;
         const size_t codes_off = ngc_workspace_bytes(c, max_keep);
-        const size_t codes_bytes = (size_t)c->L * c->B * c->Hkv * c->cap * sizeof(uint32_t);
+        const size_t codes_bytes = (size_t)c->L * c->B * c->Hkv * c->cap * sizeof(uint32_t) * 3;
         if (ws_bytes < codes_off + codes_bytes) return NGC_ENOSPC;
         long long kc = (long long)c->Hkv * max_keep;
         if (kc > (long long)c->Hkv * c->cap) kc = (long long)c->Hkv * c->cap;

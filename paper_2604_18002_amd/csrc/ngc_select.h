@@ -194,6 +194,144 @@ __device__ __forceinline__ void fill_holes_inplace(unsigned char *kbase, unsigne
         for (int i = threadIdx.x; i < movers; i += THREADS) pos[hole_of(i)] = pos[kept[jstar + i]];
 }
 
+// ------------------------------------------------- shared building blocks --
+//
+// The two steps every variant of the selection shares (segments of one head in
+// LDS, pooled segments of all heads of a sequence with their codes in global
+// memory, pages as items).  `code_at(i)` returns the key code of item i.
+
+// K-th largest of the N codes by a 3-pass radix select (11 + 11 + 10 bits) over LDS histograms.  Returns that
+// code; `need` = how many of the items equal to it are taken (lowest index first).  With `have_first` the caller
+// has already accumulated the histogram of the top 11 bits in hist[0 .. SEL_BINS) (and passed a barrier).
+// Whole workgroup; ends on a barrier.  Uses misc[0 .. 34).
+template <int THREADS, class CodeAt>
+__device__ __forceinline__ uint32_t radix_select_kth(CodeAt code_at, int N, int K, uint32_t *hist, int *misc,
+                                                     int &need, bool have_first)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, pmask = 0;
+    need = K;   // how many of the items matching `prefix` are still to take
+    const int shifts[3] = {21, 10, 0};
+    const int widths[3] = {11, 11, 10};
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = shifts[pass], nb = 1 << widths[pass];
+        if (pass > 0 || !have_first) {
+            for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+            __syncthreads();
+            for (int t = tid; t < N; t += THREADS) {
+                const uint32_t u = code_at(t);
+                if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
+            }
+        }
+        __syncthreads();
+        // bins in descending digit order; each thread owns `per` of them
+        const int per = (nb + THREADS - 1) / THREADS;
+        int mine = 0;
+        for (int i = 0; i < per; ++i) {
+            const int p = tid * per + i;
+            if (p < nb) mine += (int)hist[nb - 1 - p];
+        }
+        int total;
+        int above = block_excl_scan_i<THREADS>(mine, misc, &total);
+        if (above < need && need <= above + mine) {
+            for (int i = 0; i < per; ++i) {
+                const int p = tid * per + i;
+                const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
+                if (need <= above + c) {
+                    misc[32] = nb - 1 - p;   // digit of the K-th largest
+                    misc[33] = above;        // matching items with a larger digit
+                    break;
+                }
+                above += c;
+            }
+        }
+        __syncthreads();
+        const uint32_t digit = (uint32_t)misc[32];
+        need -= misc[33];
+        prefix |= digit << shift;
+        pmask |= (uint32_t)(nb - 1) << shift;
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// Stable LSD radix sort of the K entries of idxA (u16 handles, in ascending start order) by descending code:
+// the sort key is cmax - code_of(handle), which for kept items lies in [0, cmax - thr], so only the bits of that
+// range are sorted, SORT_BITS at a time; per-wave digit counts by LDS atomics, ranks inside a wave by match-any
+// ballots -- stability plus the ascending start order is the index tie-break.  Returns the buffer (idxA or idxB)
+// that holds the sorted handles.  Whole workgroup; ends on a barrier.  hist holds SORT_BINS * waves entries.
+template <int THREADS, class CodeOf>
+__device__ __forceinline__ uint16_t *sort_by_code_desc(CodeOf code_of, int K, uint32_t cmax, uint32_t thr,
+                                                       uint16_t *idxA, uint16_t *idxB, uint32_t *hist, int *misc)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
+    const int k_begin = wv * per_wave_k;
+    const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
+    uint16_t *cur = idxA, *dst = idxB;
+    volatile uint32_t *vh = hist;
+    const uint32_t range = cmax - thr;
+    const int range_bits = range ? 32 - __clz(range) : 0;
+    const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
+#pragma unroll 1
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = SORT_BITS * pass;
+        for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
+        __syncthreads();
+        // per-wave digit counts over the wave's own contiguous range
+        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+            const int j = j0 + lane;
+            if (j < k_end) {
+                const uint32_t d = ((cmax - code_of(cur[j])) >> shift) & (SORT_BINS - 1);
+                atomicAdd(&hist[wv * SORT_BINS + d], 1u);
+            }
+        }
+        __syncthreads();
+        // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
+        {
+            constexpr int PER = SORT_BINS * NW / THREADS;
+            int vals[PER], sum = 0;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int e = tid * PER + i;
+                vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
+                sum += vals[i];
+            }
+            int total;
+            int run = block_excl_scan_i<THREADS>(sum, misc, &total);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int e = tid * PER + i;
+                hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
+                run += vals[i];
+            }
+        }
+        __syncthreads();
+        // scatter in order: rank within the batch + running offset of (wave, digit)
+        for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
+            const int j = j0 + lane;
+            const bool in = j < k_end;
+            const uint16_t idx = in ? cur[j] : (uint16_t)0;
+            const uint32_t d = in ? ((cmax - code_of(idx)) >> shift) & (SORT_BINS - 1) : 0u;
+            const uint64_t peers = match_digit(d, __ballot(in));
+            const int rank = popc_below(peers);
+            uint32_t base = 0;
+            if (in) base = vh[wv * SORT_BINS + d];
+            __builtin_amdgcn_wave_barrier();
+            if (in) {
+                dst[base + rank] = idx;
+                if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        uint16_t *tmp = cur; cur = dst; dst = tmp;
+    }
+    return cur;
+}
+
 // Slots of the small shared scratch array `misc` that outlive the selection.
 constexpr int MISC_KEPT = 35;   // items kept in this segment
 constexpr int MISC_ROWS = 36;   // rows in use after compaction
@@ -268,51 +406,8 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
     if (N > SMALL_ITEMS) {
         // ---- 2. radix select of the K-th largest code -------------------------
-        uint32_t prefix = 0, pmask = 0;
-        int need = K;   // how many of the items matching `prefix` are still to take
-        {
-            const int shifts[3] = {21, 10, 0};
-            const int widths[3] = {11, 11, 10};
-    #pragma unroll
-            for (int pass = 0; pass < 3; ++pass) {
-                const int shift = shifts[pass], nb = 1 << widths[pass];
-                for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
-                __syncthreads();
-                for (int t = tid; t < N; t += THREADS) {
-                    const uint32_t u = code[t];
-                    if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (nb - 1)], 1u);
-                }
-                __syncthreads();
-                // bins in descending digit order; each thread owns `per` of them
-                const int per = (nb + THREADS - 1) / THREADS;
-                int mine = 0;
-                for (int i = 0; i < per; ++i) {
-                    const int p = tid * per + i;
-                    if (p < nb) mine += (int)hist[nb - 1 - p];
-                }
-                int total;
-                int above = block_excl_scan_i<THREADS>(mine, misc, &total);
-                if (above < need && need <= above + mine) {
-                    for (int i = 0; i < per; ++i) {
-                        const int p = tid * per + i;
-                        const int c = (p < nb) ? (int)hist[nb - 1 - p] : 0;
-                        if (need <= above + c) {
-                            misc[32] = nb - 1 - p;   // digit of the K-th largest
-                            misc[33] = above;        // matching items with a larger digit
-                            break;
-                        }
-                        above += c;
-                    }
-                }
-                __syncthreads();
-                const uint32_t digit = (uint32_t)misc[32];
-                need -= misc[33];
-                prefix |= digit << shift;
-                pmask |= (uint32_t)(nb - 1) << shift;
-                __syncthreads();
-            }
-        }
-        const uint32_t thr = prefix;   // code of the K-th largest key; `need` items equal to it are kept
+        int need;   // items equal to the threshold that are kept
+        const uint32_t thr = radix_select_kth<THREADS>([&](int t) { return code[t]; }, N, K, hist, misc, need, false);
 
         // ---- 3. kept list, ascending ------------------------------------------
         const int per_wave = (((N + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
@@ -372,71 +467,7 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
         if (want_sort) {
 
             // ---- 4. sigma: stable sort of the kept indices by descending code ------
-            // Sort key = cmax - code (ascending), which for kept items lies in
-            // [0, cmax - thr]: only the bits of that range are sorted, SORT_BITS at a time.
-            const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
-            const int k_begin = wv * per_wave_k;
-            const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
-            uint16_t *cur = idxA, *dst = idxB;
-            volatile uint32_t *vh = hist;
-            const uint32_t range = cmax - thr;
-            const int range_bits = range ? 32 - __clz(range) : 0;
-            const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
-        #pragma unroll 1
-            for (int pass = 0; pass < passes; ++pass) {
-                const int shift = SORT_BITS * pass;
-                for (int i = tid; i < SORT_BINS * NW; i += THREADS) hist[i] = 0;
-                __syncthreads();
-                // per-wave digit counts over the wave's own contiguous range
-                for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-                    const int j = j0 + lane;
-                    if (j < k_end) {
-                        const uint32_t d = ((cmax - code[cur[j]]) >> shift) & (SORT_BINS - 1);
-                        atomicAdd(&hist[wv * SORT_BINS + d], 1u);
-                    }
-                }
-                __syncthreads();
-                // exclusive scan in (digit, wave) order; every thread owns PER consecutive entries
-                {
-                    constexpr int PER = SORT_BINS * NW / THREADS;
-                    int vals[PER], sum = 0;
-        #pragma unroll
-                    for (int i = 0; i < PER; ++i) {
-                        const int e = tid * PER + i;
-                        vals[i] = (int)hist[(e % NW) * SORT_BINS + e / NW];
-                        sum += vals[i];
-                    }
-                    int total;
-                    int run = block_excl_scan_i<THREADS>(sum, misc, &total);
-        #pragma unroll
-                    for (int i = 0; i < PER; ++i) {
-                        const int e = tid * PER + i;
-                        hist[(e % NW) * SORT_BINS + e / NW] = (uint32_t)run;
-                        run += vals[i];
-                    }
-                }
-                __syncthreads();
-                // scatter in order: rank within the batch + running offset of (wave, digit)
-                for (int j0 = k_begin; j0 < k_end; j0 += NGC_WAVE) {
-                    const int j = j0 + lane;
-                    const bool in = j < k_end;
-                    const uint16_t idx = in ? cur[j] : (uint16_t)0;
-                    const uint32_t d = in ? ((cmax - code[idx]) >> shift) & (SORT_BINS - 1) : 0u;
-                    const uint64_t peers = match_digit(d, __ballot(in));
-                    const int rank = popc_below(peers);
-                    uint32_t base = 0;
-                    if (in) base = vh[wv * SORT_BINS + d];
-                    __builtin_amdgcn_wave_barrier();
-                    if (in) {
-                        dst[base + rank] = idx;
-                        if (rank == 0) vh[wv * SORT_BINS + d] = base + (uint32_t)__popcll(peers);
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                }
-                __syncthreads();
-                uint16_t *tmp = cur; cur = dst; dst = tmp;
-            }
-            src = cur;
+            src = sort_by_code_desc<THREADS>([&](uint16_t t) { return code[t]; }, K, cmax, thr, idxA, idxB, hist, misc);
         }
     } else {
         // ---- 2'-4'. few items: rank every key by counting ---------------------
