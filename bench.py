@@ -83,6 +83,8 @@ def parse_args():
     ap.add_argument("--no-per-layer", dest="per_layer", action="store_false", help="skip the layer-by-layer timing")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout section")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming read / copy probes")
+    ap.add_argument("--only-replay", action="store_true",
+                    help="run only the replay-attention section (for counter runs of that kernel) and print its JSON")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short eviction / decode measurement of the other configurations among configs[2..4]")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -254,6 +256,64 @@ def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
     }
 
 
+def replay_case(ngc, w, g, dev, block):
+    """Replay attention (training forward under the replay mask), one layer, paper-like rounds."""
+    import torch
+    scale = 1.0 / math.sqrt(w.D)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    Bt, T = 8, 4096
+    rs = np.random.default_rng(w.data_seed + block)
+    death_h = np.full((Bt, T), T, np.int32)
+    for bb in range(Bt):
+        alive = np.zeros(0, np.int64)
+        for bnd in range(w.delta, T, w.delta):
+            alive = np.concatenate([alive, np.arange(bnd - w.delta, bnd)])
+            nb = (alive.size + block - 1) // block
+            keep_b = rs.random(nb) < (w.keep_num / w.keep_den) ** (w.delta / max(1.0, alive.size / 2))
+            keep_t = np.repeat(keep_b, block)[:alive.size]
+            death_h[bb, alive[~keep_t]] = bnd
+            alive = alive[keep_t]
+    qT = torch.randn(Bt, T, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
+    kT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    vT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
+    oT = torch.empty(Bt, T, w.Hq, w.D, dtype=torch.float32, device=dev)
+    dT = torch.from_numpy(death_h).to(dev)
+    wsT = torch.zeros(ngc.ngc_replay_workspace_bytes(Bt, T, w.Hkv), dtype=torch.uint8, device=dev)
+    ms = []
+    for rep in range(4):
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        ngc.ngc_replay_attn(qT, kT, vT, dT, Bt, T, w.Hq, w.Hkv, w.D, False, scale, oT, wsT)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    t_ms = float(np.mean(ms[1:]))
+    ii = np.arange(T)
+    visible = sum(int(((ii[:, None] >= ii[None, :]) & (ii[:, None] < death_h[bb][None, :])).sum()) for bb in range(Bt))
+    flops = 4.0 * w.D * visible * w.Hq
+    causal = 4.0 * w.D * (T * (T + 1) / 2) * w.Hq * Bt
+    # what the kernel issues: per tile of 128 queries, the keys visible to any of them, rounded up to 32,
+    # times 128 query rows, times 6 D flops per pair (QK, PV with P in two bf16 parts)
+    issued_pairs = 0
+    for bb in range(Bt):
+        for i0 in range(0, T, 128):
+            last = min(i0 + 127, T - 1)
+            n_list = int((death_h[bb][:last + 1] > i0).sum())
+            issued_pairs += ((n_list + 31) // 32) * 32 * 128
+    issued = 6.0 * w.D * issued_pairs * w.Hq
+    return {"block": block, "B": Bt, "T": T, "ms": t_ms, "visible_pairs_frac_of_causal": flops / causal,
+            "algorithmic_tflops": flops / (t_ms * 1e-3) / 1e12,
+            "mfma_frac": flops / (t_ms * 1e-3) / 1e12 / 2500.0,
+            "causal_equivalent_tflops": causal / (t_ms * 1e-3) / 1e12,
+            "issued_mfma_tflops": issued / (t_ms * 1e-3) / 1e12,
+            "issued_mfma_frac": issued / (t_ms * 1e-3) / 1e12 / 2500.0}
+
+
+
 def _cpu_segment_work(w, keep, n_after_mid, kbits, vbits, seg):
     """One segment's share of a period on the oracle: (seconds of eviction, seconds of one decode-attention step)."""
     import oracle as orc
@@ -356,6 +416,12 @@ def main():
     dev = "cuda"
     torch.cuda.set_device(0)
     w = build_workload(args)
+    if args.only_replay:
+        g = torch.Generator(device=dev)
+        g.manual_seed(w.data_seed * 2 + 3)
+        print(json.dumps({"replay_attn": {"per_token_eviction": replay_case(ngc, w, g, dev, 1),
+                                          "block32_eviction": replay_case(ngc, w, g, dev, 32)}}), flush=True)
+        return
     t_setup = time.time()
 
     if args.copy_calibration:
@@ -744,58 +810,8 @@ def main():
         del ws_p, kept_p, sigma_p
         cache.len.copy_(keep)       # back to the schedule's state
 
-    # ---- replay attention (training forward under the replay mask), one layer, paper-like rounds
-    def replay_case(block):
-        Bt, T = 8, 4096
-        rs = np.random.default_rng(w.data_seed + block)
-        death_h = np.full((Bt, T), T, np.int32)
-        for bb in range(Bt):
-            alive = np.zeros(0, np.int64)
-            for bnd in range(w.delta, T, w.delta):
-                alive = np.concatenate([alive, np.arange(bnd - w.delta, bnd)])
-                nb = (alive.size + block - 1) // block
-                keep_b = rs.random(nb) < (w.keep_num / w.keep_den) ** (w.delta / max(1.0, alive.size / 2))
-                keep_t = np.repeat(keep_b, block)[:alive.size]
-                death_h[bb, alive[~keep_t]] = bnd
-                alive = alive[keep_t]
-        qT = torch.randn(Bt, T, w.Hq, w.D, generator=g, device=dev).to(torch.bfloat16)
-        kT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
-        vT = torch.randn(Bt, T, w.Hkv, w.D, generator=g, device=dev).to(torch.bfloat16)
-        oT = torch.empty(Bt, T, w.Hq, w.D, dtype=torch.float32, device=dev)
-        dT = torch.from_numpy(death_h).to(dev)
-        wsT = torch.zeros(ngc.ngc_replay_workspace_bytes(Bt, T, w.Hkv), dtype=torch.uint8, device=dev)
-        ms = []
-        for rep in range(4):
-            torch.cuda.synchronize()
-            e0, e1 = ev(), ev()
-            e0.record()
-            ngc.ngc_replay_attn(qT, kT, vT, dT, Bt, T, w.Hq, w.Hkv, w.D, False, scale, oT, wsT)
-            e1.record()
-            torch.cuda.synchronize()
-            ms.append(e0.elapsed_time(e1))
-        t_ms = float(np.mean(ms[1:]))
-        ii = np.arange(T)
-        visible = sum(int(((ii[:, None] >= ii[None, :]) & (ii[:, None] < death_h[bb][None, :])).sum()) for bb in range(Bt))
-        flops = 4.0 * w.D * visible * w.Hq
-        causal = 4.0 * w.D * (T * (T + 1) / 2) * w.Hq * Bt
-        # what the kernel issues: per tile of 128 queries, the keys visible to any of them, rounded up to 32,
-        # times 128 query rows, times 6 D flops per pair (QK, PV with P in two bf16 parts)
-        issued_pairs = 0
-        for bb in range(Bt):
-            for i0 in range(0, T, 128):
-                last = min(i0 + 127, T - 1)
-                n_list = int((death_h[bb][:last + 1] > i0).sum())
-                issued_pairs += ((n_list + 31) // 32) * 32 * 128
-        issued = 6.0 * w.D * issued_pairs * w.Hq
-        return {"block": block, "B": Bt, "T": T, "ms": t_ms, "visible_pairs_frac_of_causal": flops / causal,
-                "algorithmic_tflops": flops / (t_ms * 1e-3) / 1e12,
-                "mfma_frac": flops / (t_ms * 1e-3) / 1e12 / 2500.0,
-                "causal_equivalent_tflops": causal / (t_ms * 1e-3) / 1e12,
-                "issued_mfma_tflops": issued / (t_ms * 1e-3) / 1e12,
-                "issued_mfma_frac": issued / (t_ms * 1e-3) / 1e12 / 2500.0}
-
     replay = {"what": "ngc_replay_attn, one layer, rounds every delta tokens, random survivors; bound: bf16 MFMA 2.5 PFLOP/s",
-              "per_token_eviction": replay_case(1), "block32_eviction": replay_case(32)}
+              "per_token_eviction": replay_case(ngc, w, g, dev, 1), "block32_eviction": replay_case(ngc, w, g, dev, 32)}
 
     # ---- the same cycle over the paged layout (pages of 32 rows = the paper's blocks): eviction edits page
     # tables, nothing moves; decode attention and append go through the table.  Runs last: the contiguous
