@@ -393,8 +393,12 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
     // so that the number of loads in flight is the same on every path and the
     // wait for the current tile's data does not also wait for the prefetch.
     if constexpr (APPEND) {
-        // The wave that owns the last tile stores the new row before it loads that tile, and waits for the store.
-        // No other wave or workgroup uses that row (prefetches past a split's end are never computed on).
+        // The wave that owns the last tile stores the new row before anything else.  No other wave or workgroup
+        // uses that row (prefetches past a split's end are never computed on).  The wave's loads of that tile
+        // come after the store in program order; they are issued at once only when the last tile is also the
+        // wave's first one -- then the wave waits for the store first.  Otherwise the loads of the last tile are
+        // issued after the wave has waited for an earlier tile's data, and memory operations of a wave complete
+        // in issue order, so the store is done by then.
         const int last_tile = tiles - 1;
         if (grew && last_tile >= t_lo && last_tile < t_hi && ((last_tile - t_lo) % ATT_WAVES) == wv) {
             if (lane < 2 * K_PIECES) {
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
                 *reinterpret_cast<u32x4 *>((is_v ? a.v_rw : a.k_rw) + dst_off) = row;
             }
             if (lane == 0 && a.pos && a.new_pos) a.pos[(size_t)seg * a.cap + (n - 1)] = a.new_pos[(seg / a.Hkv) % a.B];
-            __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (last_tile - t_lo < 2 * ATT_WAVES) __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 

@@ -256,24 +256,92 @@ __device__ __forceinline__ uint32_t radix_select_kth(CodeAt code_at, int N, int 
     return prefix;
 }
 
-// Stable LSD radix sort of the K entries of idxA (u16 handles, in ascending start order) by descending code:
-// the sort key is cmax - code_of(handle), which for kept items lies in [0, cmax - thr], so only the bits of that
-// range are sorted, SORT_BITS at a time; per-wave digit counts by LDS atomics, ranks inside a wave by match-any
-// ballots -- stability plus the ascending start order is the index tie-break.  Returns the buffer (idxA or idxB)
-// that holds the sorted handles.  Whole workgroup; ends on a barrier.  hist holds SORT_BINS * waves entries.
+// Sort of the K entries of idxA (u16 handles, ascending) by descending code, equal codes by ascending handle.
+// The sort key is cmax - code_of(handle), which for kept items lies in [0, cmax - thr].
+//
+// Fast path: one counting pass into as many buckets as the histogram area holds (the top bits of the key range),
+// a prefix sum, an unordered scatter by bucket (LDS atomics hand out the positions), and then every entry finds
+// its place inside its bucket by counting the entries of that bucket that precede it in the total order -- which
+// makes the result independent of the order in which the atomics were served.  With thousands of buckets for
+// thousands of kept items a bucket holds a few entries.  Whole workgroup; ends on a barrier.
+//
+// Fallback (a bucket above BUCKET_LIMIT entries: many equal or nearly equal keys): stable LSD radix sort, only
+// the bits of the key range, SORT_BITS at a time; per-wave digit counts by LDS atomics, ranks inside a wave by
+// match-any ballots -- stability plus the ascending start order is the index tie-break.
+// Returns the buffer (idxA or idxB) that holds the sorted handles.  hist holds max(SEL_BINS, SORT_BINS * waves)
+// entries.
+constexpr int BUCKET_LIMIT = 64;
+
 template <int THREADS, class CodeOf>
 __device__ __forceinline__ uint16_t *sort_by_code_desc(CodeOf code_of, int K, uint32_t cmax, uint32_t thr,
                                                        uint16_t *idxA, uint16_t *idxB, uint32_t *hist, int *misc)
 {
     constexpr int NW = THREADS / NGC_WAVE;
+    constexpr int NB = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;   // buckets = entries of hist
+    constexpr int NB_BITS = (NB == 2048) ? 11 : (NB == 4096) ? 12 : 13;
+    static_assert(NB == (1 << NB_BITS), "bucket count must be a power of two");
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    const uint32_t range = cmax - thr;
+    const int range_bits = range ? 32 - __clz(range) : 0;
+    if (range_bits == 0) return idxA;   // all codes equal: the ascending start order is the answer
+    {
+        const int shift = range_bits > NB_BITS ? range_bits - NB_BITS : 0;
+        for (int i = tid; i < NB; i += THREADS) hist[i] = 0;
+        __syncthreads();
+        for (int j = tid; j < K; j += THREADS) atomicAdd(&hist[(cmax - code_of(idxA[j])) >> shift], 1u);
+        __syncthreads();
+        // bucket starts (exclusive prefix sum; every thread owns PER consecutive buckets) and the largest bucket
+        constexpr int PER = NB / THREADS;
+        int vals[PER], sum = 0;
+        uint32_t biggest = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            vals[i] = (int)hist[tid * PER + i];
+            sum += vals[i];
+            biggest = (uint32_t)vals[i] > biggest ? (uint32_t)vals[i] : biggest;
+        }
+        biggest = block_max_u<THREADS>(biggest, reinterpret_cast<uint32_t *>(misc));
+        if (biggest <= (uint32_t)BUCKET_LIMIT) {
+            int total;
+            int run = block_excl_scan_i<THREADS>(sum, misc, &total);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                hist[tid * PER + i] = (uint32_t)run;
+                run += vals[i];
+            }
+            __syncthreads();
+            // unordered scatter: afterwards hist[b] is the END of bucket b (and the start of bucket b + 1)
+            for (int j = tid; j < K; j += THREADS) {
+                const uint16_t h = idxA[j];
+                const uint32_t pos = atomicAdd(&hist[(cmax - code_of(h)) >> shift], 1u);
+                idxB[pos] = h;
+            }
+            __syncthreads();
+            // place inside the bucket: count the bucket's entries that come first (larger code, or the same code
+            // and a smaller handle)
+            for (int p = tid; p < K; p += THREADS) {
+                const uint16_t h = idxB[p];
+                const uint32_t c = code_of(h);
+                const uint32_t b = (cmax - c) >> shift;
+                const int start = b ? (int)hist[b - 1] : 0, end = (int)hist[b];
+                int rank = 0;
+                for (int q = start; q < end; ++q) {
+                    const uint16_t h2 = idxB[q];
+                    const uint32_t c2 = code_of(h2);
+                    rank += (c2 > c || (c2 == c && h2 < h)) ? 1 : 0;
+                }
+                idxA[start + rank] = h;
+            }
+            __syncthreads();
+            return idxA;
+        }
+    }
+    // ---- fallback: stable LSD radix sort ---------------------------------------------------------------------
     const int per_wave_k = (((K + NW - 1) / NW) + NGC_WAVE - 1) & ~(NGC_WAVE - 1);
     const int k_begin = wv * per_wave_k;
     const int k_end = (k_begin + per_wave_k < K) ? (k_begin + per_wave_k) : K;
     uint16_t *cur = idxA, *dst = idxB;
     volatile uint32_t *vh = hist;
-    const uint32_t range = cmax - thr;
-    const int range_bits = range ? 32 - __clz(range) : 0;
     const int passes = (range_bits + SORT_BITS - 1) / SORT_BITS;
 #pragma unroll 1
     for (int pass = 0; pass < passes; ++pass) {
