@@ -92,6 +92,11 @@ __device__ __forceinline__ float perturb(float logit, float tau, uint32_t word)
 
 // Order-preserving code of an fp32 value: larger float <=> larger code,
 // -0 below +0.
+__device__ __forceinline__ float code_to_float(uint32_t c)   // inverse of ordered_code
+{
+    return __uint_as_float((c & 0x80000000u) ? (c & 0x7FFFFFFFu) : ~c);
+}
+
 __device__ __forceinline__ uint32_t ordered_code(float x)
 {
     const uint32_t b = __float_as_uint(x);

@@ -259,8 +259,7 @@ __device__ __forceinline__ uint32_t radix_select_kth(CodeAt code_at, int N, int 
 // Sort of the K entries of idxA (u16 handles, ascending) by descending code, equal codes by ascending handle.
 // The sort key is cmax - code_of(handle), which for kept items lies in [0, cmax - thr].
 //
-// Fast path: one counting pass into as many buckets as the histogram area holds (the top bits of the key range),
-// a prefix sum, an unordered scatter by bucket (LDS atomics hand out the positions), and then every entry finds
+// Fast path: one counting pass into as many buckets as the histogram area holds, a prefix sum, an unordered scatter by bucket (LDS atomics hand out the positions), and then every entry finds
 // its place inside its bucket by counting the entries of that bucket that precede it in the total order -- which
 // makes the result independent of the order in which the atomics were served.  With thousands of buckets for
 // thousands of kept items a bucket holds a few entries.  Whole workgroup; ends on a barrier.
@@ -278,17 +277,25 @@ __device__ __forceinline__ uint16_t *sort_by_code_desc(CodeOf code_of, int K, ui
 {
     constexpr int NW = THREADS / NGC_WAVE;
     constexpr int NB = (SEL_BINS > SORT_BINS * NW) ? SEL_BINS : SORT_BINS * NW;   // buckets = entries of hist
-    constexpr int NB_BITS = (NB == 2048) ? 11 : (NB == 4096) ? 12 : 13;
-    static_assert(NB == (1 << NB_BITS), "bucket count must be a power of two");
+    static_assert(NB % THREADS == 0, "every thread owns the same number of buckets");
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const uint32_t range = cmax - thr;
     const int range_bits = range ? 32 - __clz(range) : 0;
     if (range_bits == 0) return idxA;   // all codes equal: the ascending start order is the answer
-    {
-        const int shift = range_bits > NB_BITS ? range_bits - NB_BITS : 0;
+    // Buckets are equal slices of the VALUE range [key of thr, key of cmax] (not of the code range, which is
+    // logarithmic in the value and nearly empty around zero): bucket = floor((kmax - key) * NB / width), a
+    // non-increasing function of the key in IEEE arithmetic, so a larger key never lands in a later bucket.
+    const float kmax = code_to_float(cmax), kthr = code_to_float(thr);
+    const float width = kmax - kthr;
+    if (width > 0.f && width < INFINITY) {
+        const float per_value = (float)(NB - 1) / width;
+        auto bucket_of = [&](uint32_t c) -> uint32_t {
+            const float x = (kmax - code_to_float(c)) * per_value;     // >= 0; +inf for a masked key
+            return (uint32_t)fminf(x, (float)(NB - 1));
+        };
         for (int i = tid; i < NB; i += THREADS) hist[i] = 0;
         __syncthreads();
-        for (int j = tid; j < K; j += THREADS) atomicAdd(&hist[(cmax - code_of(idxA[j])) >> shift], 1u);
+        for (int j = tid; j < K; j += THREADS) atomicAdd(&hist[bucket_of(code_of(idxA[j]))], 1u);
         __syncthreads();
         // bucket starts (exclusive prefix sum; every thread owns PER consecutive buckets) and the largest bucket
         constexpr int PER = NB / THREADS;
@@ -313,7 +320,7 @@ __device__ __forceinline__ uint16_t *sort_by_code_desc(CodeOf code_of, int K, ui
             // unordered scatter: afterwards hist[b] is the END of bucket b (and the start of bucket b + 1)
             for (int j = tid; j < K; j += THREADS) {
                 const uint16_t h = idxA[j];
-                const uint32_t pos = atomicAdd(&hist[(cmax - code_of(h)) >> shift], 1u);
+                const uint32_t pos = atomicAdd(&hist[bucket_of(code_of(h))], 1u);
                 idxB[pos] = h;
             }
             __syncthreads();
@@ -322,7 +329,7 @@ __device__ __forceinline__ uint16_t *sort_by_code_desc(CodeOf code_of, int K, ui
             for (int p = tid; p < K; p += THREADS) {
                 const uint16_t h = idxB[p];
                 const uint32_t c = code_of(h);
-                const uint32_t b = (cmax - c) >> shift;
+                const uint32_t b = bucket_of(c);
                 const int start = b ? (int)hist[b - 1] : 0, end = (int)hist[b];
                 int rank = 0;
                 for (int q = start; q < end; ++q) {
