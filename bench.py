@@ -238,6 +238,23 @@ def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
                 ba_b += attn_bytes(w, int(keep_h.sum()) + (t + 1) * nseg, nseg)
             if warm and t >= offs[1]:
                 break
+    # the per-layer token-step from a HIP graph at the mid-period length (no host work between launches)
+    cache.len.copy_(keep + w.delta // 2)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for l in range(w.L):
+            ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        for l in range(w.L):
+            ngc.ngc_decode_attn(cache, l, q[l], scale, hint, out[l], ws)
+    gph.replay()
+    g_ms = timed(lambda: [gph.replay() for _ in range(10)]) / 10
+    g_bytes = attn_bytes(w, int(keep_h.sum()) + (w.delta // 2) * nseg, nseg)
+    del gph
     status = ngc.read_status(ws)
     assert all(x == 0 for x in status), f"config {w.index}: device status words not clean: {status[:8]}"
     p1_ms, st_ms = float(np.mean(p1)), float(np.mean(steady[1:]))
@@ -249,6 +266,8 @@ def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
         "decode_per_layer_ms_per_token_step": pl_ms / len(offs),
         "decode_per_layer_hbm_frac": pl_b / (pl_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "decode_per_layer_tokens_per_s": w.B * len(offs) / (pl_ms * 1e-3),
+        "decode_per_layer_hip_graph_ms_per_token_step": g_ms,
+        "decode_per_layer_hip_graph_hbm_frac": g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "decode_all_layers_per_launch_ms": ba_ms / len(offs),
         "decode_all_layers_per_launch_hbm_frac": ba_b / (ba_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "what": f"eviction: mean of {evict_reps} round-0 launches at peak cache and of 2 steady-state rounds; decode: "
@@ -782,7 +801,7 @@ def main():
     # ---- config 4, other reading: one budget per sequence pooled over its KV heads
     pooled = None
     if w.per_head_budget and w.Hkv * cap <= 65536:
-        ws_p = torch.zeros(ngc.ngc_workspace_bytes(cache, cap) + 12 * nseg * cap, dtype=torch.uint8, device=dev)
+        ws_p = torch.zeros(ngc.ngc_workspace_bytes(cache, cap) + 16 * nseg * cap, dtype=torch.uint8, device=dev)
         kept_p = torch.empty(w.L, w.B, w.Hkv, cap, dtype=torch.int32, device=dev)   # a head may keep more than its even share
         sigma_p = torch.empty_like(kept_p)
         pl_ms = []

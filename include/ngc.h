@@ -129,7 +129,7 @@ typedef struct ngc_cache {
  *                head * cap + row, in the Hkv rows of the (layer, sequence)
  *                back to back; logp_out holds its log-probability in the entry
  *                of head 0 and 0 in the others.  The workspace must be
- *                ngc_workspace_bytes() + 12 * L * B * Hkv * cap bytes.  The
+ *                ngc_workspace_bytes() + 16 * L * B * Hkv * cap bytes.  The
  *                budget of one (layer, sequence) -- a sum only the device
  *                sees -- is limited to 32000 items (the sort's index buffers
  *                live in LDS); a larger one is clamped to the limit and

@@ -463,9 +463,10 @@ __device__ __forceinline__ void compact_pos_inplace(int32_t *pos, const int32_t 
 // Item order (for ties and for the sampled sequence) is (head, row); the noise
 // of item (head, row) is the one the per-head mode draws for it.  Up to
 // Hkv * cap = 65536 items: their key codes live in a workspace in global
-// memory (read in order by the select passes), the kept items' codes and item
-// indices in two dense arrays next to them (K entries, served by the L2 cache
-// to the sort), the index buffers of the sort in LDS.  Select and sort are the
+// memory (read in order by the select passes), the kept items' codes, logits
+// and item indices in three dense arrays next to them (K entries each, served
+// by the L2 cache to the sort and to the log-probability), the index buffers
+// of the sort in LDS.  Select and sort are the
 // shared routines of ngc_select.h.
 
 constexpr int POOL_THREADS = 1024;
@@ -493,10 +494,11 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
     const int lb = a.seg0 / Hkv + blockIdx.x;     // layer * B + sequence
     const int l = lb / a.g.B, b = lb - l * a.g.B;
     const int seg_first = lb * Hkv;
-    // per (layer, sequence): [codes of all items][codes of the kept items][item index of the kept items]
-    uint32_t *code = a.pool_codes + (size_t)lb * Hkv * cap * 3;
+    // per (layer, sequence): [codes of all items][codes | logits | item indices of the kept items]
+    uint32_t *code = a.pool_codes + (size_t)lb * Hkv * cap * 4;
     uint32_t *kcode = code + (size_t)Hkv * cap;
-    uint16_t *items = reinterpret_cast<uint16_t *>(kcode + (size_t)Hkv * cap);
+    float *klogit = reinterpret_cast<float *>(kcode + (size_t)Hkv * cap);
+    uint16_t *items = reinterpret_cast<uint16_t *>(klogit + (size_t)Hkv * cap);
 
     // ---- 0. geometry of the pooled item space ------------------------------
     if (tid == 0) {
@@ -603,16 +605,22 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
         const int gt_before = gt_base + popc_below(bgt);
         const int eq_before = eq_base + popc_below(beq);
         const bool sel = is_gt || (is_eq && eq_before < need);
-        if (sel) {
-            const int slot = gt_before + (eq_before < need ? eq_before : need);
-            items[slot] = (uint16_t)t;
-            kcode[slot] = u;
-            idxA[slot] = (uint16_t)slot;
-        } else if (in && want_logp) {
-            const int h = head_of(t);
-            float x = a.logits[(size_t)(seg_first + h) * cap + (t - misc[PM_OFF + h])];
-            if (x != x) x = -INFINITY;
-            unpicked += expf(x - smax);
+        if (in && (want_logp || sel)) {
+            float x = 0.f;
+            if (want_logp) {
+                const int h = head_of(t);
+                x = a.logits[(size_t)(seg_first + h) * cap + (t - misc[PM_OFF + h])];
+                if (x != x) x = -INFINITY;
+            }
+            if (sel) {
+                const int slot = gt_before + (eq_before < need ? eq_before : need);
+                items[slot] = (uint16_t)t;
+                kcode[slot] = u;
+                klogit[slot] = x;
+                idxA[slot] = (uint16_t)slot;
+            } else {
+                unpicked += expf(x - smax);
+            }
         }
         gt_base += __popcll(bgt);
         eq_base += __popcll(beq);
@@ -646,11 +654,7 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
         // ---- 4. sigma: the slots sorted by descending code ---------------------
         const uint16_t *src = sort_by_code_desc<THREADS>([&](uint16_t j) { return kcode[j]; }, K, cmax, thr, idxA, idxB,
                                                          hist, misc);
-        auto logit_of_slot = [&](int j) {
-            const int i = items[j], h = head_of_slot(j);
-            const float x = a.logits[(size_t)(seg_first + h) * cap + (i - misc[PM_OFF + h])];
-            return (x != x) ? -INFINITY : x;
-        };
+        auto logit_of_slot = [&](int j) { return klogit[j]; };
         if (a.sigma_out) {
             // the pooled sequence occupies the Hkv rows of this (layer, sequence) back to back
             int32_t *sig_row = a.sigma_out + (size_t)seg_first * a.max_keep;
@@ -906,7 +910,7 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
         if (p->block != 1 || (p->flags & NGC_EVICT_UNORDERED)) return NGC_EUNSUPPORTED;
         if (c->Hkv > POOL_MAX_HEADS || (long long)c->Hkv * c->cap > 65536) return NGC_EUNSUPPORTED;
         const size_t codes_off = ngc_workspace_bytes(c, max_keep);
-        const size_t codes_bytes = (size_t)c->L * c->B * c->Hkv * c->cap * sizeof(uint32_t) * 3;
+        const size_t codes_bytes = (size_t)c->L * c->B * c->Hkv * c->cap * sizeof(uint32_t) * 4;
         if (ws_bytes < codes_off + codes_bytes) return NGC_ENOSPC;
         long long kc = (long long)c->Hkv * max_keep;
         if (kc > (long long)c->Hkv * c->cap) kc = (long long)c->Hkv * c->cap;

@@ -504,7 +504,7 @@ def test_pooled_heads_eviction(idx, over, sel_only):
     cache, logits, keep = upload(case, with_pos=True)
     # a head may keep far more than its even share: give the lists the full capacity
     max_keep = w.cap
-    nbytes = ngc.ngc_workspace_bytes(cache, max_keep) + 12 * w.L * w.B * w.Hkv * w.cap
+    nbytes = ngc.ngc_workspace_bytes(cache, max_keep) + 16 * w.L * w.B * w.Hkv * w.cap
     ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
     kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
     sigma = torch.full_like(kept, -1)
