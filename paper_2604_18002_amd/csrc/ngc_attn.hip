@@ -336,8 +336,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
         float tmax = x[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, x[e]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, NGC_WAVE));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NGC_WAVE));
+        tmax = quad_rows_max(tmax);
         const float m_new = fmaxf(m_run, tmax);           // finite: a tile has a valid row
         if (__ballot(m_new != m_run)) {                   // wave-uniform: the running max moved somewhere
             const float alpha = fast_exp2(m_run - m_new); // 0 on the first tile, 1 where nothing changed
@@ -443,8 +442,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
     }
 
     // ---- merge the waves of this workgroup ----------------------------------
-    l_run += __shfl_xor(l_run, 16, NGC_WAVE);
-    l_run += __shfl_xor(l_run, 32, NGC_WAVE);
+    l_run = quad_rows_sum(l_run);
     if (kg == 0) { red_m[wv][li] = m_run; red_l[wv][li] = l_run; }
     __syncthreads();   // also: every wave is done with its K staging area
     float m_all = red_m[0][li];

@@ -32,6 +32,28 @@ __device__ __forceinline__ int popc_below(uint64_t mask)
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// Reductions over the four lanes {l, l ^ 16, l ^ 32, l ^ 48} (the lane groups that share lane % 16 in the
+// attention kernels), result in all four.  gfx950's lane-swap instructions exchange the halves / the odd and even
+// rows of two registers inside the vector ALU: with both operands holding x, one comes back as [lo, lo] and the
+// other as [hi, hi] (rows [r0, r0, r2, r2] and [r1, r1, r3, r3]), so combining the pair is the xor-32 (xor-16)
+// step of a butterfly -- without the trip through LDS that a shuffle takes.
+__device__ __forceinline__ float quad_rows_max(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    u = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+    auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_rows_sum(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    u = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 __device__ __forceinline__ int wave_sum_i(int v)
 {
 #pragma unroll

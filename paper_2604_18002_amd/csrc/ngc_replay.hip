@@ -269,8 +269,7 @@ void replay_attn_kernel(ReplayArgs a)
                 float tmx = x[0];
 #pragma unroll
                 for (int e = 1; e < 8; ++e) tmx = fmaxf(tmx, x[e]);
-                tmx = fmaxf(tmx, __shfl_xor(tmx, 16, NGC_WAVE));
-                tmx = fmaxf(tmx, __shfl_xor(tmx, 32, NGC_WAVE));
+                tmx = quad_rows_max(tmx);
                 const float m_new = fmaxf(m_run[qa], tmx);
                 if (__ballot(m_new != m_run[qa])) {
                     // m_new is finite wherever it changed; exp2(-inf - finite) = 0 on a first visible tile
@@ -369,8 +368,7 @@ void replay_attn_kernel(ReplayArgs a)
 #pragma unroll
     for (int qa = 0; qa < 2; ++qa) {
         float l = l_run[qa];
-        l += __shfl_xor(l, 16, NGC_WAVE);
-        l += __shfl_xor(l, 32, NGC_WAVE);
+        l = quad_rows_sum(l);
         const float inv = l > 0.f ? 1.0f / l : 0.f;
         if (qpos[qa] < T) {
             float *orow = a.out + (((size_t)b * T + qpos[qa]) * a.Hq + head) * D;

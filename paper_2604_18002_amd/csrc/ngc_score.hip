@@ -180,8 +180,7 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
                 float tmax = x[0];
 #pragma unroll
                 for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, x[e]);
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, NGC_WAVE));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NGC_WAVE));
+                tmax = quad_rows_max(tmax);
                 const float m_new = fmaxf(m_run[qt], tmax);
                 if (m_new > -INFINITY) {
                     float psum = 0.f;
@@ -196,8 +195,7 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         float l = l_run[qt];
-        l += __shfl_xor(l, 16, NGC_WAVE);
-        l += __shfl_xor(l, 32, NGC_WAVE);
+        l = quad_rows_sum(l);
         if (kg == 0) { red_m[wv][qt * 16 + li] = m_run[qt]; red_l[wv][qt * 16 + li] = l; }
     }
     __syncthreads();
@@ -266,8 +264,7 @@ __global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
                         if (t < vis_row[qt][r])
                             acc += fast_exp2(s[r] * a.scale_log2e - m_row[qt][r]) * il_row[qt][r];
                 }
-                acc += __shfl_xor(acc, 16, NGC_WAVE);
-                acc += __shfl_xor(acc, 32, NGC_WAVE);
+                acc = quad_rows_sum(acc);
                 if (kg == 0 && t < n) psi[t] = acc * inv_rows;
             }
         }
