@@ -16,6 +16,8 @@
  *   ngc_cache_append     one new entry per token between rounds   (Sec. 4.1)
  *   ngc_decode_attn      softmax(q K^T / sqrt(d_h)) V over the surviving
  *                        entries of every sequence               (Sec. 4.1, 4.2)
+ *   ngc_decode_step      append + decode attention of a layer in one launch
+ *   ngc_decode_attn_static  ngc_decode_attn without a workspace argument
  *   ngc_replay_attn      training-time attention under the replay mask (Sec. 4.5)
  *   ngc_score_keys       attention-based importance of every cached key, the
  *                        input of the eviction policy                (Sec. 4.2)
