@@ -370,7 +370,9 @@ int ngc_score_keys(const ngc_cache *c, int32_t layer, const void *q_recent,
  *   death  int32 [B][Hkv][T] if death_per_head != 0, else [B][T] (one set of
  *          decisions per layer, shared by its KV heads)
  *   out    fp32 [B][T][Hq][D]
- * D is 64 or 128.  ws must hold ngc_replay_workspace_bytes(B, T, Hkv). */
+ *   scale  positive and finite (NGC_EINVAL otherwise)
+ * D is 64 or 128; T <= 65535 and T * Hkv * D * 2 < 2^32 (NGC_EUNSUPPORTED
+ * beyond).  ws must hold ngc_replay_workspace_bytes(B, T, Hkv). */
 size_t ngc_replay_workspace_bytes(int32_t B, int32_t T, int32_t Hkv);
 int ngc_replay_attn(const void *q, const void *k, const void *v, const int32_t *death,
                     int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,

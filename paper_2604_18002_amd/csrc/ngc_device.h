@@ -37,13 +37,20 @@ __device__ __forceinline__ int popc_below(uint64_t mask)
 // rows of two registers inside the vector ALU: with both operands holding x, one comes back as [lo, lo] and the
 // other as [hi, hi] (rows [r0, r0, r2, r2] and [r1, r1, r3, r3]), so combining the pair is the xor-32 (xor-16)
 // step of a butterfly -- without the trip through LDS that a shuffle takes.
+// max of two numbers that are known not to be NaN: the median of (a, b, +inf), one instruction, where fmaxf()
+// first spends one more on each operand whose origin the compiler cannot see (a matrix-core result, a lane swap)
+// to quiet a signalling NaN.
+__device__ __forceinline__ float max_no_nan(float a, float b)
+{
+    return __builtin_amdgcn_fmed3f(a, b, __builtin_inff());
+}
 __device__ __forceinline__ float quad_rows_max(float v)
 {
     uint32_t u = __float_as_uint(v);
     auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    u = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+    u = __float_as_uint(max_no_nan(__uint_as_float(a[0]), __uint_as_float(a[1])));
     auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    return max_no_nan(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ float quad_rows_sum(float v)
 {

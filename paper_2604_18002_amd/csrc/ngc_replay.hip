@@ -115,14 +115,25 @@ void replay_attn_kernel(ReplayArgs a)
     const int li = lane & 15, kg = lane >> 4;
     const int T = a.T;
     const int nqt = (T + RP_QT - 1) / RP_QT;
-    const int qt = nqt - 1 - blockIdx.x;                   // heaviest query tiles first
-    const int head = blockIdx.y, b = blockIdx.z;
+    // Workgroup -> (query tile, head, trajectory).  The hardware deals consecutive workgroups round-robin to the
+    // 8 XCDs, and a query tile's work grows with its position, so the tile index is the slowest coordinate,
+    // heaviest first: every XCD gets the same mix of tiles at every moment.  Within one tile index the KV group
+    // (trajectory, KV head) is the fastest coordinate: with a multiple of 8 groups an XCD always works on the
+    // same groups, whose K/V rows then stay in its own L2 for all their query heads and tiles.
     const int G = a.Hq / a.Hkv;
-    const int hkv = head / G;
+    const int nkv = a.B * a.Hkv;
+    const int per_tile = G * nkv;
+    const int qt = nqt - 1 - (int)(blockIdx.x / per_tile);
+    const int rem = (int)(blockIdx.x % per_tile);
+    const int kvp = rem % nkv;
+    const int b = kvp / a.Hkv, hkv = kvp % a.Hkv;
+    const int head = hkv * G + rem / nkv;
     const int hd = a.Hd == 1 ? 0 : hkv;
     const int i0 = qt * RP_QT;
     const int32_t *death = a.death + ((size_t)b * a.Hd + hd) * T;
-    const size_t kv_row = (size_t)a.Hkv * ROW_BYTES;       // bytes between consecutive tokens
+    // bytes between consecutive tokens; a sequence's K (or V) spans less than 2^32 bytes (checked on the host),
+    // so a row's offset from the sequence's first row fits 32 bits
+    const uint32_t kv_row = (uint32_t)a.Hkv * ROW_BYTES;
     const unsigned char *kbase = a.k + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
     const unsigned char *vbase = a.v + ((size_t)b * T * a.Hkv + hkv) * ROW_BYTES;
 
@@ -183,22 +194,32 @@ void replay_attn_kernel(ReplayArgs a)
             const int key = (int)klist[slot];
             ix.key[r] = key < T ? key : T - 1;          // whatever the list holds, stay inside k / v
         }
-        ix.mine = 0x7FFFFFFF;               // a key no query comes after
-        if (tid < RP_KT && s0 + tid < n_list) ix.mine = (int)klist[s0 + tid];
+        // every thread fetches the key of list slot s0 + tid % RP_KT (clamped; 0x7FFFFFFF = a key no query comes
+        // after, past the end): no branch around a load, so the loads in flight are the same on every path
+        int sl = s0 + (tid & (RP_KT - 1));
+        const bool inside = sl < n_list;
+        sl = inside ? sl : n_list - 1;
+        sl = sl < 0 ? 0 : sl;
+        const int mine = (int)klist[sl];
+        ix.mine = inside ? mine : 0x7FFFFFFF;
     };
     auto load_rows = [&](int t, const IdxStage &ix, Stage &st) {
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
-            const size_t off = (size_t)ix.key[r] * kv_row + (piece_id % PIECES) * 16;
+            const uint32_t off = (uint32_t)ix.key[r] * kv_row + (uint32_t)(piece_id % PIECES) * 16u;
             st.k[r] = *reinterpret_cast<const u32x4 *>(kbase + off);
             st.v[r] = *reinterpret_cast<const u32x4 *>(vbase + off);
         }
-        st.tmin = 0;
-        if (tid < RP_KT / RP_MT && (t * (RP_KT / RP_MT) + tid) * RP_MT < n_list) st.tmin = tmin[t * (RP_KT / RP_MT) + tid];
+        int ti = t * (RP_KT / RP_MT) + (tid & (RP_KT / RP_MT - 1));
+        const bool t_inside = ti * RP_MT < n_list;
+        ti = t_inside ? ti : 0;
+        const int tm = tmin[ti];
+        st.tmin = t_inside ? tm : 0;
         st.i = ix.mine;
-        st.d = 0;
-        if (ix.mine != 0x7FFFFFFF) st.d = death[ix.mine];
+        const int dkey = ix.mine < T ? ix.mine : T - 1;
+        const int dv = death[dkey];
+        st.d = ix.mine != 0x7FFFFFFF ? dv : 0;
     };
     auto store_tile = [&](int buf, const Stage &st) {
 #pragma unroll
@@ -232,45 +253,62 @@ void replay_attn_kernel(ReplayArgs a)
             // mask (wave-uniform, so the branches below do not diverge).
             const bool full = __builtin_amdgcn_readfirstlane(
                 (lkidx[RP_MT - 1] <= wave_q0 && lds_tmin[buf][half] > wave_q1) ? 1 : 0) != 0;
-            int dk[8], jk[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { dk[e] = 0x7FFFFFFF; jk[e] = 0; }
-            if (!full) {
-                const int4 d0 = *reinterpret_cast<const int4 *>(&ldeath[4 * kg]);
-                const int4 d1 = *reinterpret_cast<const int4 *>(&ldeath[16 + 4 * kg]);
-                dk[0] = d0.x; dk[1] = d0.y; dk[2] = d0.z; dk[3] = d0.w;
-                dk[4] = d1.x; dk[5] = d1.y; dk[6] = d1.z; dk[7] = d1.w;
-                const int4 j0v = *reinterpret_cast<const int4 *>(&lkidx[4 * kg]);
-                const int4 j1v = *reinterpret_cast<const int4 *>(&lkidx[16 + 4 * kg]);
-                jk[0] = j0v.x; jk[1] = j0v.y; jk[2] = j0v.z; jk[3] = j0v.w;
-                jk[4] = j1v.x; jk[5] = j1v.y; jk[6] = j1v.z; jk[7] = j1v.w;
-            }
             bf16x8 p_hi[2], p_lo[2];
+            f32x4 sc0[2], sc1[2];
 #pragma unroll
             for (int qa = 0; qa < 2; ++qa) {
-                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+                sc0[qa] = f32x4{0.f, 0.f, 0.f, 0.f};
+                sc1[qa] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
-                for (int c = 0; c < KCH; ++c) {
-                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][c], qop[qa][c], s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][c], qop[qa][c], s1, 0, 0, 0);
+            for (int c = 0; c < KCH; ++c)
+#pragma unroll
+                for (int qa = 0; qa < 2; ++qa) {
+                    sc0[qa] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][c], qop[qa][c], sc0[qa], 0, 0, 0);
+                    sc1[qa] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][c], qop[qa][c], sc1[qa], 0, 0, 0);
                 }
+            // The V rows are requested as soon as the first product has been issued (the K operand registers are
+            // free from here on) and arrive while the soft-max arithmetic runs.
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 vcur[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if constexpr (DPL == 8) {
+                    vcur[e] = *reinterpret_cast<const u32x4 *>(lv + vrow_rel[e] * LROW + li * 16);
+                } else {
+                    const u32x2 tt = *reinterpret_cast<const u32x2 *>(lv + vrow_rel[e] * LROW + li * 8);
+                    vcur[e] = u32x4{tt[0], tt[1], 0u, 0u};
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int qa = 0; qa < 2; ++qa) {
+                const f32x4 s0 = sc0[qa], s1 = sc1[qa];
+                // raw scores; the (positive) scale is applied inside the exponent's multiply-add, the running
+                // max lives in the scaled domain
                 float x[8];
                 const int qp = qpos[qa];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float sc = (e < 4) ? s0[e] : s1[e - 4];
-                    x[e] = sc * a.scale_log2e;
-                }
+                for (int e = 0; e < 8; ++e) x[e] = (e < 4) ? s0[e] : s1[e - 4];
                 if (!full) {
+                    // key indices and death positions of the rows this lane holds (rare path: fetched here, per
+                    // query tile, rather than kept in registers across the common path)
+                    const int4 d0 = *reinterpret_cast<const int4 *>(&ldeath[4 * kg]);
+                    const int4 d1 = *reinterpret_cast<const int4 *>(&ldeath[16 + 4 * kg]);
+                    const int4 j0 = *reinterpret_cast<const int4 *>(&lkidx[4 * kg]);
+                    const int4 j1 = *reinterpret_cast<const int4 *>(&lkidx[16 + 4 * kg]);
+                    const int dk[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                    const int jk[8] = {j0.x, j0.y, j0.z, j0.w, j1.x, j1.y, j1.z, j1.w};
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
                         if (!(jk[e] <= qp && qp < dk[e])) x[e] = -INFINITY;
                 }
+                // scores are finite or -inf, never NaN (finite inputs)
                 float tmx = x[0];
 #pragma unroll
-                for (int e = 1; e < 8; ++e) tmx = fmaxf(tmx, x[e]);
-                tmx = quad_rows_max(tmx);
-                const float m_new = fmaxf(m_run[qa], tmx);
+                for (int e = 1; e < 8; ++e) tmx = max_no_nan(tmx, x[e]);
+                tmx = quad_rows_max(tmx) * a.scale_log2e;
+                const float m_new = max_no_nan(m_run[qa], tmx);
                 if (__ballot(m_new != m_run[qa])) {
                     // m_new is finite wherever it changed; exp2(-inf - finite) = 0 on a first visible tile
                     const float alpha = (m_new == m_run[qa]) ? 1.0f : fast_exp2(m_run[qa] - m_new);
@@ -280,9 +318,10 @@ void replay_attn_kernel(ReplayArgs a)
                     m_run[qa] = m_new;
                 }
                 float p[8], psum = 0.f;
+                const float neg_m = -m_run[qa];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = fast_exp2(x[e] - m_run[qa]);   // x = -inf gives 0: m_run is always finite
+                    p[e] = fast_exp2(__builtin_fmaf(x[e], a.scale_log2e, neg_m));   // x = -inf gives 0: m_run is finite
                     psum += p[e];
                 }
                 l_run[qa] += psum;
@@ -297,18 +336,6 @@ void replay_attn_kernel(ReplayArgs a)
                 }
                 p_hi[qa] = __builtin_bit_cast(bf16x8, u32x4{ph[0], ph[1], ph[2], ph[3]});
                 p_lo[qa] = __builtin_bit_cast(bf16x8, u32x4{pl[0], pl[1], pl[2], pl[3]});
-            }
-            // V only now: its registers must not be live together with the K operands
-            __builtin_amdgcn_sched_barrier(0);
-            u32x4 vcur[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if constexpr (DPL == 8) {
-                    vcur[e] = *reinterpret_cast<const u32x4 *>(lv + vrow_rel[e] * LROW + li * 16);
-                } else {
-                    const u32x2 tt = *reinterpret_cast<const u32x2 *>(lv + vrow_rel[e] * LROW + li * 8);
-                    vcur[e] = u32x4{tt[0], tt[1], 0u, 0u};
-                }
             }
 #pragma unroll
             for (int c = 0; c < DPL; ++c) {
@@ -413,8 +440,9 @@ extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, cons
         return NGC_EINVAL;
     if (B <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return NGC_EINVAL;
     if (D != 64 && D != 128) return NGC_EINVAL;
-    if (!(scale == scale)) return NGC_EINVAL;
-    if (B > 65535 || Hq > 65535) return NGC_EUNSUPPORTED;
+    if (!(scale > 0.f) || scale > 3.0e38f) return NGC_EINVAL;   // positive and finite: the kernel takes maxima before scaling
+    if ((long long)((T + RP_QT - 1) / RP_QT) * Hq * B > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;   // one workgroup each
+    if ((unsigned long long)T * Hkv * D * 2 > 0xFFFFFFFFull) return NGC_EUNSUPPORTED;   // 32-bit row offsets inside a sequence
     if (T > 65535) return NGC_EUNSUPPORTED;   // 16-bit key lists
     if (ws_bytes < ngc_replay_workspace_bytes(B, T, Hkv)) return NGC_ENOSPC;
     ReplayArgs ra;
@@ -437,9 +465,9 @@ extern "C" int ngc_replay_attn(const void *q, const void *k, const void *v, cons
     hipLaunchKernelGGL(replay_lists_kernel, dim3(nqt, B * ra.Hd), dim3(RP_WAVES * 64), 0, st, ra);
     NGC_HIP_CHECK(hipGetLastError());
     if (D == 128)
-        hipLaunchKernelGGL(replay_attn_kernel<128>, dim3(nqt, Hq, B), dim3(RP_WAVES * 64), 0, st, ra);
+        hipLaunchKernelGGL(replay_attn_kernel<128>, dim3((unsigned)(nqt * Hq * B)), dim3(RP_WAVES * 64), 0, st, ra);
     else
-        hipLaunchKernelGGL(replay_attn_kernel<64>, dim3(nqt, Hq, B), dim3(RP_WAVES * 64), 0, st, ra);
+        hipLaunchKernelGGL(replay_attn_kernel<64>, dim3((unsigned)(nqt * Hq * B)), dim3(RP_WAVES * 64), 0, st, ra);
     NGC_HIP_CHECK(hipGetLastError());
     return NGC_OK;
 }
