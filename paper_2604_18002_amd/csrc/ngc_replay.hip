@@ -166,8 +166,7 @@ void replay_attn_kernel(ReplayArgs a)
 
     // keys this workgroup needs (list built by replay_lists_kernel)
     const uint16_t *klist = a.klist + (((size_t)b * a.Hd + hd) * nqt + qt) * T;
-    const int n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
-    const int t_end = (n_list + RP_KT - 1) / RP_KT;
+    int n_list = 0;   // length of the list; read after the first list entries have been requested
     const int32_t *tmin = a.tile_death + (((size_t)b * a.Hd + hd) * nqt + qt) * ((T + RP_MT - 1) / RP_MT);
     const int wave_q0 = i0 + wv * RP_QW;                               // first query position of this wave
     const int wave_q1 = (wave_q0 + RP_QW - 1 < T - 1) ? wave_q0 + RP_QW - 1 : T - 1;   // last real one
@@ -176,32 +175,31 @@ void replay_attn_kernel(ReplayArgs a)
     // inside one step: first the list entries (which keys), one step later the rows they name.
     struct IdxStage {
         int key[LOADS];   // key index of the rows this thread copies
-        int mine;         // threads < RP_KT: the key of list slot s0 + tid (0x7FFFFFFF past the end)
+        int mine;         // the entry of list slot s0 + tid % RP_KT, as stored
     };
     struct Stage {
         u32x4 k[LOADS], v[LOADS];
         int d, i;
         int tmin;   // threads < RP_KT / RP_MT only
     };
+    // List entries are fetched without looking at the list's length (slots past its end hold whatever the
+    // workspace held: any value is clamped to a valid key, and such slots are switched off when the tile is
+    // stored), so the first of these loads does not have to wait for the length to arrive.
     auto load_idx = [&](int t, IdxStage &ix) {
-        const int s0 = t * RP_KT;           // past the end every slot clamps to the last key: harmless re-reads
+        const int s0 = t * RP_KT;
 #pragma unroll
         for (int r = 0; r < LOADS; ++r) {
             const int piece_id = r * (RP_WAVES * 64) + tid;
             int slot = s0 + piece_id / PIECES;
-            slot = slot < n_list ? slot : n_list - 1;
-            slot = slot < 0 ? 0 : slot;                 // an empty list (only with death[j] <= j, not a valid input)
+            slot = slot < T ? slot : T - 1;             // a list row has T slots
             const int key = (int)klist[slot];
             ix.key[r] = key < T ? key : T - 1;          // whatever the list holds, stay inside k / v
         }
-        // every thread fetches the key of list slot s0 + tid % RP_KT (clamped; 0x7FFFFFFF = a key no query comes
-        // after, past the end): no branch around a load, so the loads in flight are the same on every path
+        // every thread fetches the key of list slot s0 + tid % RP_KT: no branch around a load, so the loads in
+        // flight are the same on every path
         int sl = s0 + (tid & (RP_KT - 1));
-        const bool inside = sl < n_list;
-        sl = inside ? sl : n_list - 1;
-        sl = sl < 0 ? 0 : sl;
-        const int mine = (int)klist[sl];
-        ix.mine = inside ? mine : 0x7FFFFFFF;
+        sl = sl < T ? sl : T - 1;
+        ix.mine = (int)klist[sl];
     };
     auto load_rows = [&](int t, const IdxStage &ix, Stage &st) {
 #pragma unroll
@@ -216,10 +214,12 @@ void replay_attn_kernel(ReplayArgs a)
         ti = t_inside ? ti : 0;
         const int tm = tmin[ti];
         st.tmin = t_inside ? tm : 0;
-        st.i = ix.mine;
+        // 0x7FFFFFFF = a key no query comes after: slots past the end of the list
+        const bool inside = t * RP_KT + (tid & (RP_KT - 1)) < n_list;
         const int dkey = ix.mine < T ? ix.mine : T - 1;
         const int dv = death[dkey];
-        st.d = ix.mine != 0x7FFFFFFF ? dv : 0;
+        st.i = inside ? ix.mine : 0x7FFFFFFF;
+        st.d = inside ? dv : 0;
     };
     auto store_tile = [&](int buf, const Stage &st) {
 #pragma unroll
@@ -366,6 +366,8 @@ void replay_attn_kernel(ReplayArgs a)
     IdxStage ix_a, ix_b;
     load_idx(0, ix_a);
     load_idx(1, ix_b);
+    n_list = a.kcount[((size_t)b * a.Hd + hd) * nqt + qt];
+    const int t_end = (n_list + RP_KT - 1) / RP_KT;
     load_rows(0, ix_a, st);
     store_tile(0, st);
     __syncthreads();

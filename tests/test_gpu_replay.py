@@ -162,3 +162,16 @@ def test_replay_sweep(c):
     scale = 1.0 / np.sqrt(D)
     got = _run(q, k, v, death.astype(np.int32), Hq, Hkv, D, c["per_head"], scale)
     _check(q, k, v, death, Hq, Hkv, D, c["per_head"], scale, got)
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.125, float("inf"), float("nan")])
+def test_replay_rejects_a_scale_that_is_not_positive_and_finite(scale):
+    """The kernel takes maxima on raw scores and scales afterwards: the scale has to be positive (ngc.h)."""
+    rng = np.random.default_rng(7)
+    T, Hq, Hkv, D = 40, 4, 2, 64
+    q, k, v = _rand_bf16(rng, (1, T, Hq, D)), _rand_bf16(rng, (1, T, Hkv, D)), _rand_bf16(rng, (1, T, Hkv, D))
+    death = np.full((1, T), T, np.int32)
+    ngc = _ngc()
+    with pytest.raises(ngc.NgcError) as e:
+        _run(q, k, v, death, Hq, Hkv, D, False, scale)
+    assert e.value.code == ngc.NGC_EINVAL
