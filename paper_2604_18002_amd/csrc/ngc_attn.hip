@@ -99,6 +99,23 @@ __device__ __forceinline__ float ld_device(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// 16-byte versions for the partial O rows (a wave's stores land as whole cache lines instead of one 4-byte
+// write-through per lane): raw buffer accesses with the device-scope bit, bounds-checked by the hardware against
+// `bytes` (a load past the end returns 0, a store past the end is dropped).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t device_span(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+constexpr int AUX_DEVICE_SCOPE = 16;   // sc1
+__device__ __forceinline__ void st_device16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, AUX_DEVICE_SCOPE);
+}
+__device__ __forceinline__ f32x4 ld_device16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX_DEVICE_SCOPE));
+}
+
 // Tiles [t_lo, t_hi) of split s when `tiles` tiles are cut into at most S
 // nearly equal runs; s_eff = number of non-empty splits.
 __device__ __forceinline__ void split_range(int tiles, int S, int s, int &t_lo, int &t_hi, int &s_eff)
@@ -210,21 +227,23 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
             if (a.lse_out) a.lse_out[((size_t)lb * a.Hkv + h) * G + qi] = (M + __log2f(den)) * 0.6931471805599453f;
         }
         __syncthreads();
-        for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
-            const int qi = i / D;
-            float num = 0.f;
+        const __amdgpu_buffer_rsrc_t po = device_span(seg_po, (uint32_t)(s_eff * G * D * sizeof(float)));
+        for (int i4 = threadIdx.x; i4 < G * D / 4; i4 += ATT_WAVES * 64) {
+            const int qi = (i4 * 4) / D;
+            f32x4 num = {0.f, 0.f, 0.f, 0.f};
             for (int sp0 = 0; sp0 < s_eff; sp0 += 4) {
-                float o[4];
+                f32x4 o[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int sp = (sp0 + u < s_eff) ? sp0 + u : s_eff - 1;
-                    o[u] = ld_device(&seg_po[(size_t)sp * G * D + i]);
+                    o[u] = ld_device16(po, (uint32_t)((sp * G * D + i4 * 4) * sizeof(float)));
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     if (sp0 + u < s_eff) num += o[u] * ml_s[((sp0 + u) * G + qi) * 2];
             }
-            out_seg[i] = num / den_s[qi];
+            const float inv = 1.0f / den_s[qi];
+            *reinterpret_cast<f32x4 *>(&out_seg[i4 * 4]) = num * inv;
         }
     };
     if (t_lo >= t_hi) {   // whole workgroup: no rows for this split
@@ -484,12 +503,13 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
         return;
     }
     float *dst_o = a.part_o + ((size_t)seg_local * a.S + split) * G * D;
-    for (int i = threadIdx.x; i < G * D; i += ATT_WAVES * 64) {
-        const int qi = i / D, d = i - qi * D;
-        float acc = 0.f;
+    const __amdgpu_buffer_rsrc_t po = device_span(dst_o, (uint32_t)(G * D * sizeof(float)));
+    for (int i4 = threadIdx.x; i4 < G * D / 4; i4 += ATT_WAVES * 64) {
+        const int qi = (i4 * 4) / D, d = i4 * 4 - qi * D;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < ATT_WAVES; ++w) acc += ost[(w * 16 + qi) * D + d];
-        st_device(&dst_o[i], acc);
+        for (int w = 0; w < ATT_WAVES; ++w) acc += *reinterpret_cast<const f32x4 *>(&ost[(w * 16 + qi) * D + d]);
+        st_device16(po, (uint32_t)(i4 * 4 * sizeof(float)), acc);
     }
     if (wv == 0 && kg == 0 && li < G) {
         float *ml = a.part_ml + (((size_t)seg_local * a.S + split) * G + li) * 2;
