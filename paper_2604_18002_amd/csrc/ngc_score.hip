@@ -38,8 +38,11 @@ struct ScoreArgs {
     int max_pages, num_pages, tpp_shift;
 };
 
+// Up to three query tiles the kernel fits 168 registers per thread without spilling, i.e. three waves per SIMD
+// (three workgroups per CU) instead of the two the compiler settles for by itself; with four tiles it does not.
 template <int D, int QT>
-__global__ __launch_bounds__(SC_WAVES * 64) void score_keys_kernel(ScoreArgs a)
+__global__ __launch_bounds__(SC_WAVES * 64) __attribute__((amdgpu_waves_per_eu(QT <= 3 ? 3 : 2)))
+void score_keys_kernel(ScoreArgs a)
 {
     constexpr int ROW_BYTES = D * 2;
     constexpr int KCH = D / 32;
