@@ -537,37 +537,41 @@ using namespace ngc;
 namespace {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 constexpr size_t STATUS_BYTES = NGC_STATUS_WORDS * sizeof(int32_t);
-// How many workgroups share a segment.  Measured on MI355X: a workgroup (4 waves, one 32-row tile in flight per
-// wave beyond the one in use) streams ~68 GB/s when nothing else limits it (one tile per wave per memory round
-// trip of ~0.9 us); the chip delivers ~6.5 TB/s to this kernel; and a split segment pays ~6 us on top for the
-// chain partial stores -> ticket -> merge loads.  The split count minimises the modelled time
-//     (S > 1 ? 6 us : 0) + max(bytes of the launch / 6.5 TB/s, rounds * bytes of the longest segment / S / 68 GB/s),
-// rounds = how often the launch refills the 512 resident workgroup slots.  Launches with many segments come out
-// unsplit; a layer's launch over few, long segments is cut up to 64 ways; a split keeps at least 128 rows.
-constexpr int RESIDENT_WORKGROUPS = 512;
+// How many workgroups share a segment.  Two measured limits (MI355X, one launch per layer, microseconds per
+// launch against S, best in brackets):
+//     segments x rows      S=1    2     3     4     6     8    12    16    24    32    64
+//         4 x  3-10K                          23.1        16.3  14.8 [14.3] 15.0  16.0  22.0
+//        16 x  3-10K                          26.3        19.7 [18.0] 18.8  23.8  25.1  36.4
+//        32 x  3-10K       80.3  46.3  35.1  29.4  25.7 [25.6] 31.7  30.8
+//        64 x  3-10K       88.7  54.8  44.9 [42.8] 51.0  46.9  50.6  52.2
+//       128 x  3-10K      101.1 [77.6] 91.6  82.1  82.6  84.6  89.2  94.0
+//       256 x  3-10K     [142.1] 149.9 145.5 148.3 151.9 156.3 166.9 178.0
+//         8 x  1.9-2.5K                       12.5       [11.2] 11.5  12.4  14.3  15.7  24.3
+//        32 x  1.9-3.5K    33.2  22.6  19.7  17.0 [16.7] 17.3  20.8  20.8
+//       128 x  1.9-3.5K    40.7 [36.2] 41.7  39.4  43.8  43.7  48.9  52.9
+//       256 x  1.9-3.5K   [60.9] 67.5  71.3  73.2  77.4  81.4  93.2 103.5
+//         8 x  1.5K                           10.5       [10.1] 10.4  11.1  13.7  13.7  20.8
+//        32 x  1.5K        18.0  14.7  13.6  12.3 [12.2] 12.5  15.0  15.4
+//        64 x  1.5K        20.5  16.0 [15.3] 15.5  18.2  17.9  20.9  22.0
+//       128 x  1.5K       [22.1] 22.2  25.6  25.0  27.8  29.5  33.9  36.7
+// (a) the launch should not have more workgroups than the chip has CUs: beyond one workgroup per CU a further cut
+// only adds workgroups, each paying its first-tile wait, its epilogue and the partial -> ticket -> merge chain;
+// (b) with few segments, a run should stay long enough that streaming it (~68 GB/s per workgroup) costs more than
+// what one more partial adds to the merge (~0.16 us): S ~ sqrt(80 x megabytes of the longest segment).
+constexpr int COMPUTE_UNITS = 256;
 constexpr int MIN_TILES_PER_SPLIT = 4;
-constexpr double CHIP_BYTES_PER_S = 6.5e12, WORKGROUP_BYTES_PER_S = 68e9, SPLIT_CHAIN_S = 6e-6;
 
 int splits_for(int nseg_launch, int max_len, int row_bytes)
 {
     const int tiles = (max_len + ATT_TILE - 1) / ATT_TILE;
-    const double seg_bytes = 2.0 * row_bytes * max_len;          // K and V
-    const double total = seg_bytes * nseg_launch;
-    int best = 1;
-    double best_t = 0.0;
-    for (int s = 1; s <= MAX_SPLITS; ++s) {
-        if (s > 1 && tiles / s < MIN_TILES_PER_SPLIT) break;
-        const long long wgs = (long long)nseg_launch * s;
-        const double rounds = (double)((wgs + RESIDENT_WORKGROUPS - 1) / RESIDENT_WORKGROUPS);
-        const double per_wg = rounds * seg_bytes / s / WORKGROUP_BYTES_PER_S;
-        const double stream = total / CHIP_BYTES_PER_S;
-        const double t = (s > 1 ? SPLIT_CHAIN_S : 0.0) + (per_wg > stream ? per_wg : stream);
-        if (s == 1 || t < best_t * 0.97) {   // a finer split has to buy at least 3 %
-            best = s;
-            best_t = t;
-        }
-    }
-    return best;
+    const double seg_mb = 2.0 * row_bytes * max_len * 1e-6;          // K and V
+    int s = COMPUTE_UNITS / (nseg_launch > 0 ? nseg_launch : 1);
+    const int by_merge = (int)sqrt(80.0 * seg_mb);
+    const int by_length = tiles / MIN_TILES_PER_SPLIT;
+    s = s < by_merge ? s : by_merge;
+    s = s < by_length ? s : by_length;
+    s = s < MAX_SPLITS ? s : MAX_SPLITS;
+    return s > 1 ? s : 1;
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
