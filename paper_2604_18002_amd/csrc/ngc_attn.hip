@@ -28,9 +28,10 @@
 // an unnormalised partial (max, sum, O) and takes a ticket of its segment; the
 // workgroup that takes the last ticket merges the partials.  One launch per
 // call.  The partials and tickets cross workgroups (and the L2 caches of
-// different XCDs) through device-scope atomic stores and loads, which go to
-// memory; the only wait is each writer's own wait for its stores before the
-// workgroup's ticket -- no cache-wide write-back or invalidate is involved.
+// different XCDs) through device-scope stores and loads, which go to memory
+// (16-byte buffer accesses for the O rows, relaxed atomics for the rest); the
+// only wait is each writer's own wait for its stores before the workgroup's
+// ticket -- no cache-wide write-back or invalidate is involved.
 //
 // The same kernel can first append the new token's K/V row (Sec. 4.1: the cache
 // grows by one entry per token): the wave that owns the last tile writes the
