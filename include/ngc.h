@@ -218,6 +218,13 @@ int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
  *   sigma    int32 [nseg][sigma_stride], first keep[s] entries used, distinct
  *   keep     int32 [nseg]
  *   logp_out fp32 [nseg]
+ * fp32 arithmetic, 1e-4 relative.  The logits may span any range: where the
+ * finite logits of a segment lie more than 80 apart (exp(x - max x) of the
+ * smallest would underflow) every running sum carries its own exponent, so a
+ * sequence that reaches those entries after everything larger has been picked
+ * still gets its finite log-probability; -inf entries are masked entries (a
+ * sequence that picks one has log-probability -inf), NaN counts as -inf.  The
+ * same holds for the log-probability ngc_evict returns.
  * ws needs NGC_STATUS_WORDS * 4 bytes (status only). */
 int ngc_subset_logprob(const float *logits, const int32_t *n_items,
                        const int32_t *sigma, const int32_t *keep, int32_t nseg,
@@ -233,6 +240,11 @@ int ngc_subset_logprob(const float *logits, const int32_t *n_items,
  *             the number of rollouts and rounds), or NULL for 1
  *   grad_out  fp32 [nseg][logit_stride]; entries past n_items are untouched
  *   max_keep  upper bound on keep[s] (<= 32768)
+ * Accuracy: 1e-4 of an entry plus ~1e-6 * gout; where the finite logits of a
+ * segment lie more than 80 apart the absolute error grows with that span (about
+ * 1e-6 * span * gout: the ratios are exponentials of differences of numbers
+ * of that size), so entries are meaningful up to spans of a few thousand.  Not
+ * defined for a sequence that picks a masked (-inf) entry.
  * Other arguments as in ngc_subset_logprob. */
 int ngc_subset_logprob_backward(const float *logits, const int32_t *n_items,
                                 const int32_t *sigma, const int32_t *keep, int32_t nseg,

@@ -171,6 +171,25 @@ __device__ __forceinline__ float block_max_f(float v, float *tmp)
     return all;
 }
 
+// Two maxima in one pass (same barriers as one).  `tmp` holds two floats per wave.
+template <int THREADS>
+__device__ __forceinline__ void block_max2_f(float &a, float &b, float *tmp)
+{
+    constexpr int NW = THREADS / NGC_WAVE;
+    a = wave_max_f(a);
+    b = wave_max_f(b);
+    if (lane_id() == 0) { tmp[2 * wave_id()] = a; tmp[2 * wave_id() + 1] = b; }
+    __syncthreads();
+    a = tmp[0];
+    b = tmp[1];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        a = fmaxf(a, tmp[2 * w]);
+        b = fmaxf(b, tmp[2 * w + 1]);
+    }
+    __syncthreads();
+}
+
 template <int THREADS>
 __device__ __forceinline__ uint32_t block_max_u(uint32_t v, uint32_t *tmp)
 {

@@ -12,6 +12,7 @@
 #include "ngc_device.h"
 #include "ngc_noise.h"
 #include "ngc_select.h"
+#include "ngc_logsum.h"
 
 namespace ngc {
 
@@ -82,21 +83,25 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
         if (atomicOr(&picked[t >> 5], bit) & bit) bad = 1;
     }
     if (bad) atomicAdd(&a.status[NGC_STATUS_BAD_SIGMA], 1);
-    float smax = -INFINITY;
+    float smax = -INFINITY, neg_smin = -INFINITY;   // over the unmasked entries
     for (int t = tid; t < N; t += THREADS) {
         float x = row[t];
         if (x == x) smax = fmaxf(smax, x);
+        if (x > -INFINITY) neg_smin = fmaxf(neg_smin, -x);
     }
-    smax = block_max_f<THREADS>(smax, fmisc);   // barriers also publish `picked`
+    block_max2_f<THREADS>(smax, neg_smin, fmisc);   // barriers also publish `picked`
+    // logits spanning more than NGC_WIDE_SPREAD: wide-range arithmetic (ngc_logsum.h); workgroup-uniform
+    const bool wide = smax > -INFINITY && smax + neg_smin > NGC_WIDE_SPREAD;
     if (smax == -INFINITY) smax = 0.f;          // every entry masked: all weights are 0
     float unpicked = 0.f;
+    LogSum unpicked_w = ls_empty();
     for (int t = tid; t < N; t += THREADS) {
         if (picked[t >> 5] & (1u << (t & 31))) continue;
         float x = row[t];
         if (x != x) x = -INFINITY;
-        unpicked += expf(x - smax);
+        if (wide) unpicked_w = ls_add_term(unpicked_w, x);   // that route works on the logits as they came
+        else unpicked += expf(x - smax);
     }
-    const float U = block_sum_f<THREADS>(unpicked, fmisc);
     const int chunk = (K + THREADS - 1) / THREADS;
     const int nchunks = (K + chunk - 1) / chunk;
     const int cidx = nchunks - 1 - tid;
@@ -111,11 +116,19 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_kernel(LogprobArgs a)
     // When they fit, the picked items' terms are gathered into LDS first (all loads in flight at once), so
     // that the serial chunk loops do not wait for one gather after another.
     const bool use_stage = K <= a.stage_cap;
+    const float shift = wide ? 0.f : smax;
     if (use_stage) {
-        for (int j = tid; j < K; j += THREADS) staged[j] = logit_of(j) - smax;
+        for (int j = tid; j < K; j += THREADS) staged[j] = logit_of(j) - shift;
         __syncthreads();
     }
-    auto term = [&](int j) { return use_stage ? staged[j] : logit_of(j) - smax; };
+    auto term = [&](int j) { return use_stage ? staged[j] : logit_of(j) - shift; };
+    if (wide) {
+        const LogSum Uw = block_sum_ls<THREADS>(unpicked_w, fmisc);
+        const float lpw = sigma_logprob_wide<THREADS>(term, K, Uw, fmisc);
+        if (tid == 0) a.logp_out[seg] = lpw;
+        return;
+    }
+    const float U = block_sum_f<THREADS>(unpicked, fmisc);
     float mass = 0.f;
     if (cidx >= 0)
         for (int j = j_lo; j < j_hi; ++j) mass += expf(term(j));
@@ -190,12 +203,73 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(Logpro
         if (atomicOr(&picked[t >> 5], bit) & bit) bad = 1;
     }
     if (bad) atomicAdd(&a.status[NGC_STATUS_BAD_SIGMA], 1);
-    float smax = -INFINITY;
+    float smax = -INFINITY, neg_smin = -INFINITY;   // over the unmasked entries
     for (int t = tid; t < N; t += THREADS) {
         const float x = row[t];
         if (x == x) smax = fmaxf(smax, x);
+        if (x > -INFINITY) neg_smin = fmaxf(neg_smin, -x);
     }
-    smax = block_max_f<THREADS>(smax, fmisc);
+    block_max2_f<THREADS>(smax, neg_smin, fmisc);
+    const int chunk = (K + THREADS - 1) / THREADS;
+    const int nchunks = (K + chunk - 1) / chunk;
+    if (smax > -INFINITY && smax + neg_smin > NGC_WIDE_SPREAD) {
+        // Logits spanning more than NGC_WIDE_SPREAD (workgroup-uniform): the same two scans in the wide-range
+        // arithmetic of ngc_logsum.h.  LDS holds, per pick, first d_j = s_j - max, then -log R_j, then log C_j;
+        // e_t C_r = exp(d_t + log C_r) is a sum of ratios e_t / R_j <= 1 and never leaves fp32's range.
+        auto d_of = [&](int t) {
+            const float x = row[t];
+            return (x != x) ? -INFINITY : x - smax;
+        };
+        LogSum uw = ls_empty();
+        for (int t = tid; t < N; t += THREADS)
+            if (!(picked[t >> 5] & (1u << (t & 31)))) uw = ls_add_term(uw, d_of(t));
+        const LogSum Uw = block_sum_ls<THREADS>(uw, fmisc);
+        for (int j = tid; j < K; j += THREADS) {
+            int t = sig[j];
+            t = t < 0 ? 0 : (t >= N ? N - 1 : t);
+            inv_r[j] = d_of(t);
+        }
+        __syncthreads();
+        {   // reverse pass: thread 0 owns the last chunk; d -> -log R in place
+            const int cidx = nchunks - 1 - tid;
+            const int j_lo = cidx * chunk;
+            const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+            LogSum mass = ls_empty();
+            if (cidx >= 0)
+                for (int j = j_lo; j < j_hi; ++j) mass = ls_add_term(mass, inv_r[j]);
+            LogSum total;
+            const LogSum after = block_excl_scan_ls<THREADS>(mass, fmisc, &total);
+            if (cidx >= 0) {
+                LogSum R = ls_add(Uw, after);
+                for (int j = j_hi - 1; j >= j_lo; --j) {
+                    R = ls_add_term(R, inv_r[j]);
+                    inv_r[j] = -ls_log(R);
+                }
+            }
+        }
+        __syncthreads();
+        LogSum c_all;
+        {   // forward pass: thread i owns chunk i; -log R -> log C in place
+            const int j_lo = tid * chunk;
+            const int j_hi = (tid < nchunks) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : j_lo;
+            LogSum part = ls_empty();
+            for (int j = j_lo; j < j_hi; ++j) part = ls_add_term(part, inv_r[j]);
+            LogSum C = block_excl_scan_ls<THREADS>(part, fmisc, &c_all);
+            for (int j = j_lo; j < j_hi; ++j) {
+                C = ls_add_term(C, inv_r[j]);
+                inv_r[j] = ls_log(C);
+            }
+        }
+        __syncthreads();
+        const float log_c_all = ls_log(c_all);
+        for (int j = tid; j < K; j += THREADS) {
+            const int t = sig[j];
+            if (t >= 0 && t < N) grow[t] = g * (1.0f - expf(d_of(t) + inv_r[j]));
+        }
+        for (int t = tid; t < N; t += THREADS)
+            if (!(picked[t >> 5] & (1u << (t & 31)))) grow[t] = -g * expf(d_of(t) + log_c_all);
+        return;
+    }
     float unpicked = 0.f;
     for (int t = tid; t < N; t += THREADS) {
         if (picked[t >> 5] & (1u << (t & 31))) continue;
@@ -210,8 +284,6 @@ __global__ __launch_bounds__(THREADS) void subset_logprob_backward_kernel(Logpro
         const float x = row[t];
         return (x != x) ? 0.f : expf(x - smax);
     };
-    const int chunk = (K + THREADS - 1) / THREADS;
-    const int nchunks = (K + chunk - 1) / chunk;
     // The masses of the picked items are gathered into LDS first, all loads in flight at once; the two
     // scans then run on LDS and never wait for a gather inside their serial chunk loops.
     for (int j = tid; j < K; j += THREADS) inv_r[j] = mass_of(j);
@@ -545,7 +617,7 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
     // ---- 1. keys (and the first histogram of the radix select) -------------
     for (int i = tid; i < SEL_BINS; i += THREADS) hist[i] = 0;
     __syncthreads();
-    float smax = -INFINITY;
+    float smax = -INFINITY, neg_smin = -INFINITY;   // over the unmasked entries
     uint32_t cmax = 0;
     for (int h = 0; h < Hkv; ++h) {
         const int n = misc[PM_N + h], off = misc[PM_OFF + h];
@@ -561,11 +633,14 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
                     atomicAdd(&hist[c >> 21], 1u);
                     cmax = c > cmax ? c : cmax;
                     smax = fmaxf(smax, s[i]);
+                    if (s[i] > -INFINITY) neg_smin = fmaxf(neg_smin, -s[i]);
                 }
         }
     }
+    bool wide = false;   // logits spanning more than NGC_WIDE_SPREAD: wide-range arithmetic for Eq. 2
     if (want_logp) {
-        smax = block_max_f<THREADS>(smax, fmisc);
+        block_max2_f<THREADS>(smax, neg_smin, fmisc);
+        wide = smax > -INFINITY && smax + neg_smin > NGC_WIDE_SPREAD;
         if (smax == -INFINITY) smax = 0.f;
     }
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
@@ -596,6 +671,7 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
     int gt_base = 0, eq_base = 0;
     for (int w = 0; w < wv; ++w) { gt_base += misc[w]; eq_base += misc[16 + w]; }
     float unpicked = 0.f;
+    LogSum unpicked_w = ls_empty();
     for (int t0 = w_begin; t0 < w_end; t0 += NGC_WAVE) {
         const int t = t0 + lane;
         const bool in = t < w_end;
@@ -618,6 +694,8 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
                 kcode[slot] = u;
                 klogit[slot] = x;
                 idxA[slot] = (uint16_t)slot;
+            } else if (wide) {
+                unpicked_w = ls_add_term(unpicked_w, x);
             } else {
                 unpicked += expf(x - smax);
             }
@@ -666,28 +744,35 @@ __global__ __launch_bounds__(POOL_THREADS) void evict_pooled_kernel(SelectArgs a
         }
         if (want_logp) {
             // ---- 5. log-probability of the pooled sequence -------------------
-            const float U = block_sum_f<THREADS>(unpicked, fmisc);
-            const int chunk = (K + THREADS - 1) / THREADS;
-            const int nchunks = (K + chunk - 1) / chunk;
-            const int cidx = nchunks - 1 - tid;
-            const int j_lo = cidx * chunk;
-            const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
-            float mass = 0.f;
-            if (cidx >= 0)
-                for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of_slot(src[j]) - smax);
-            float total_mass;
-            const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
-            float acc = 0.f;
-            if (cidx >= 0) {
-                float R = U + after;
-                for (int j = j_hi - 1; j >= j_lo; --j) {
-                    const float d = logit_of_slot(src[j]) - smax;
-                    R += expf(d);
-                    acc += (d == -INFINITY) ? -INFINITY : d - logf(R);
+            if (wide) {
+                const LogSum Uw = block_sum_ls<THREADS>(unpicked_w, fmisc);
+                const float lpw = sigma_logprob_wide<THREADS>([&](int j) { return logit_of_slot(src[j]); }, K, Uw,
+                                                              fmisc);
+                if (tid < Hkv) a.logp_out[seg_first + tid] = (tid == 0) ? lpw : 0.f;
+            } else {
+                const float U = block_sum_f<THREADS>(unpicked, fmisc);
+                const int chunk = (K + THREADS - 1) / THREADS;
+                const int nchunks = (K + chunk - 1) / chunk;
+                const int cidx = nchunks - 1 - tid;
+                const int j_lo = cidx * chunk;
+                const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
+                float mass = 0.f;
+                if (cidx >= 0)
+                    for (int j = j_lo; j < j_hi; ++j) mass += expf(logit_of_slot(src[j]) - smax);
+                float total_mass;
+                const float after = block_excl_scan_f<THREADS>(mass, fmisc, &total_mass);
+                float acc = 0.f;
+                if (cidx >= 0) {
+                    float R = U + after;
+                    for (int j = j_hi - 1; j >= j_lo; --j) {
+                        const float d = logit_of_slot(src[j]) - smax;
+                        R += expf(d);
+                        acc += (d == -INFINITY) ? -INFINITY : d - logf(R);
+                    }
                 }
+                const float lp = block_sum_f<THREADS>(acc, fmisc);
+                if (tid < Hkv) a.logp_out[seg_first + tid] = (tid == 0) ? lp : 0.f;
             }
-            const float lp = block_sum_f<THREADS>(acc, fmisc);
-            if (tid < Hkv) a.logp_out[seg_first + tid] = (tid == 0) ? lp : 0.f;
         }
     }
     if (a.k == nullptr) return;

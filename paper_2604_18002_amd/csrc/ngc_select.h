@@ -14,6 +14,7 @@
 #include "../../include/ngc.h"
 #include "ngc_device.h"
 #include "ngc_noise.h"
+#include "ngc_logsum.h"
 
 namespace ngc {
 
@@ -455,7 +456,7 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     }
 
     // ---- 1. keys ----------------------------------------------------------
-    float smax = -INFINITY;
+    float smax = -INFINITY, neg_smin = -INFINITY;   // over the unmasked entries (a NaN compares false everywhere)
     uint32_t cmax = 0;
     for (int quad = tid; 4 * quad < N; quad += THREADS) {
         float s[4], key[4];
@@ -467,10 +468,15 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
                 code[4 * quad + i] = c;
                 cmax = c > cmax ? c : cmax;
                 smax = fmaxf(smax, s[i]);
+                if (s[i] > -INFINITY) neg_smin = fmaxf(neg_smin, -s[i]);
             }
     }
+    // Logits that span more than NGC_WIDE_SPREAD take the wide-range arithmetic of ngc_logsum.h for Eq. 2
+    // (workgroup-uniform).
+    bool wide = false;
     if (want_logp) {
-        smax = block_max_f<THREADS>(smax, fmisc);   // has barriers
+        block_max2_f<THREADS>(smax, neg_smin, fmisc);   // has barriers
+        wide = smax > -INFINITY && smax + neg_smin > NGC_WIDE_SPREAD;
         if (smax == -INFINITY) smax = 0.f;          // every entry masked: all weights are 0 (log p = -inf below)
     }
     if (want_sort) cmax = block_max_u<THREADS>(cmax, reinterpret_cast<uint32_t *>(misc));
@@ -479,6 +485,7 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     // SMALL_ITEMS items (blocks or pages as items, the paper's own sizes): ranking by counting instead.
     uint16_t *src = idxA;   // the kept items in sampled order, once known
     float unpicked = 0.f;   // sum of exp(s - smax) over items not kept (for logp)
+    LogSum unpicked_w = ls_empty();   // the same sum on the wide-range route
     if (N > SMALL_ITEMS) {
         // ---- 2. radix select of the K-th largest code -------------------------
         int need;   // items equal to the threshold that are kept
@@ -520,7 +527,8 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
             } else if (in && want_logp) {
                 float x = row[t];
                 if (x != x) x = -INFINITY;
-                unpicked += expf(x - smax);
+                if (wide) unpicked_w = ls_add_term(unpicked_w, x);
+                else unpicked += expf(x - smax);
             }
             gt_base += __popcll(bgt);
             eq_base += __popcll(beq);
@@ -584,7 +592,8 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
             } else if (in && want_logp) {
                 float x = row[t];
                 if (x != x) x = -INFINITY;
-                unpicked += expf(x - smax);
+                if (wide) unpicked_w = ls_add_term(unpicked_w, x);
+                else unpicked += expf(x - smax);
             }
             kept_so_far += total;
             __syncthreads();
@@ -612,6 +621,22 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     if (!want_logp) return;
 
     // ---- 5. log-probability of sigma (Eq. 2) -------------------------------
+    // The logits of the picked items, minus the maximum, are gathered into LDS first (over the key codes,
+    // which are no longer needed), all loads in flight at once: the serial chunk loops below then never wait
+    // for a gather.
+    float *ds = reinterpret_cast<float *>(code);
+    for (int j = tid; j < K; j += THREADS) {
+        float x = row[src[j]];
+        if (x != x) x = -INFINITY;
+        ds[j] = wide ? x : x - smax;   // the wide-range route works on the logits as they came
+    }
+    __syncthreads();
+    if (wide) {
+        const LogSum Uw = block_sum_ls<THREADS>(unpicked_w, fmisc);
+        const float lpw = sigma_logprob_wide<THREADS>([&](int j) { return ds[j]; }, K, Uw, fmisc);
+        if (tid == 0) a.logp_out[seg] = lpw;
+        return;
+    }
     const float U = block_sum_f<THREADS>(unpicked, fmisc);
     const int chunk = (K + THREADS - 1) / THREADS;
     const int nchunks = (K + chunk - 1) / chunk;
@@ -620,16 +645,6 @@ __device__ __forceinline__ void select_segment(const SelectArgs &a, int seg, uns
     const int cidx = nchunks - 1 - tid;
     const int j_lo = cidx * chunk;
     const int j_hi = (cidx >= 0) ? ((j_lo + chunk < K) ? j_lo + chunk : K) : 0;
-    // The logits of the picked items, minus the maximum, are gathered into LDS first (over the key codes,
-    // which are no longer needed), all loads in flight at once: the serial chunk loops below then never wait
-    // for a gather.
-    float *ds = reinterpret_cast<float *>(code);
-    for (int j = tid; j < K; j += THREADS) {
-        float x = row[src[j]];
-        if (x != x) x = -INFINITY;
-        ds[j] = x - smax;
-    }
-    __syncthreads();
     float mass = 0.f;
     if (cidx >= 0)
         for (int j = j_lo; j < j_hi; ++j) mass += expf(ds[j]);

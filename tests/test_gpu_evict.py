@@ -806,3 +806,114 @@ def test_masked_logits(kind, tau):
     fin = ~np.isinf(got2)
     assert np.allclose(got2[fin], hlp.reshape(-1)[fin], rtol=2e-4)
     assert all(x == 0 for x in ngc.read_status(ws))
+
+
+# ------------------------------------------ logits spanning a wide range ---
+#
+# e^(s - max s) underflows in fp32 once s lies ~100 below the maximum; a sequence that reaches such entries
+# after everything larger has been picked still has a finite log-probability (every factor of Eq. 2 is a
+# softmax over what is left).  Compared against the oracle's term-by-term forms, which shift by the maximum of
+# what is left at every step.
+
+def _wide_logits(rng, n, kind):
+    if kind == "cauchy":
+        return np.clip(rng.standard_cauchy(n) * 30, -900.0, 900.0).astype(np.float32)
+    if kind == "two clusters":
+        return np.where(rng.random(n) < 0.5, rng.standard_normal(n), -500.0 + rng.standard_normal(n)).astype(np.float32)
+    if kind == "staircase":
+        return (-(np.arange(n) % 40) * 25.0 + rng.standard_normal(n)).astype(np.float32)
+    if kind == "1e30":
+        return (rng.standard_normal(n) * 1e30).astype(np.float32)
+    raise ValueError(kind)
+
+
+WIDE_KINDS = ["cauchy", "two clusters", "staircase", "1e30"]
+
+
+@pytest.mark.parametrize("kind", WIDE_KINDS)
+def test_logprob_of_logits_spanning_a_wide_range(kind):
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(31 + WIDE_KINDS.index(kind))
+    n_items = np.array([2, 40, 257, 300, 1200, 1500], np.int32)
+    keep = np.array([2, 40, 257, 150, 1200, 700], np.int32)        # K = n and K < n
+    nseg, stride, kmax = len(n_items), 1500, 1200
+    logits = np.zeros((nseg, stride), np.float32)
+    sigma = np.zeros((nseg, kmax), np.int32)
+    for s in range(nseg):
+        x = _wide_logits(rng, n_items[s], kind)
+        logits[s, :n_items[s]] = x
+        if s % 2 == 0:
+            _, sg = orc.evict_select(x, int(keep[s]), 1.0, 77, s, 0, 0, 0)
+        else:
+            sg = rng.permutation(n_items[s])[:keep[s]].astype(np.int32)   # also orders no sampler would give
+        sigma[s, :keep[s]] = sg
+    d = lambda a: torch.from_numpy(a).cuda()
+    out = torch.zeros(nseg, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(ngc.STATUS_WORDS * 4, dtype=torch.uint8, device="cuda")
+    print(f"[logprob] wide range, {kind}", flush=True)
+    ngc.ngc_subset_logprob(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, kmax, out, ws)
+    gout = rng.standard_normal(nseg).astype(np.float32)
+    grad = torch.full((nseg, stride), float("nan"), dtype=torch.float32, device="cuda")
+    ngc.ngc_subset_logprob_backward(d(logits), d(n_items), d(sigma), d(keep), nseg, stride, kmax, kmax,
+                                    d(gout), grad, ws)
+    torch.cuda.synchronize()
+    got, ggot = out.cpu().numpy(), grad.cpu().numpy()
+    for s in range(nseg):
+        n, K = n_items[s], keep[s]
+        want = orc.logprob_literal(logits[s, :n], sigma[s, :K])
+        assert np.isfinite(want)
+        assert got[s] == pytest.approx(want, rel=LOGP_RTOL, abs=1e-5), (s, got[s], want)
+        # gradient: e_t C_r is exp(d_t + log C_r) there, the sum of two fp32 numbers of the size of the span, so its
+        # absolute error grows with the span (a few 1e-7 of it per term of C_r): checked up to spans of 2000
+        span = float(logits[s, :n].max() - logits[s, :n].min())
+        if span <= 2000.0:
+            gwant = gout[s] * orc.logprob_grad(logits[s, :n], sigma[s, :K])
+            err = np.abs(ggot[s, :n] - gwant)
+            assert np.all(err <= 1e-4 * np.abs(gwant) + (2e-6 + 1e-6 * span) * abs(gout[s])), (s, span, err.max())
+            assert np.isfinite(ggot[s, :n]).all()
+    assert all(x == 0 for x in ngc.read_status(ws))
+
+
+@pytest.mark.parametrize("kind", WIDE_KINDS)
+@pytest.mark.parametrize("pooled", [False, True])
+def test_eviction_round_over_logits_spanning_a_wide_range(kind, pooled):
+    """The fused round (sample + log-prob + compaction), per head and pooled over heads, including rounds that
+    keep everything (sigma is then a full ordering and reaches the smallest entries)."""
+    import torch
+    ngc = _ngc()
+    rng = np.random.default_rng(41 + WIDE_KINDS.index(kind))
+    w = synth.workload(1, L=1, B=3, n_lo=300, n_hi=1400)
+    case = host_case(w)
+    for seg in case.segs:
+        case.logits[seg] = _wide_logits(rng, case.logits[seg].size, kind)
+    for b in range(w.B):
+        n = int(case.lens[b])
+        case.keep[0, b, :] = n if b == 0 else (n // 2 if b == 1 else max(1, n - 3))
+    if not pooled:
+        cache, kept, sigma, logp, ws = _run_evict(case, tau=1.0, rnd=2)
+        _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 2)
+        assert all(x == 0 for x in ngc.read_status(ws))
+        return
+    cache, logits, keep = upload(case)
+    max_keep = w.cap          # a head may keep far more than its even share
+    ws = torch.zeros(ngc.ngc_workspace_bytes(cache, max_keep) + 16 * w.L * w.B * w.Hkv * w.cap, dtype=torch.uint8,
+                     device="cuda")
+    kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.full((w.L, w.B, w.Hkv), float("nan"), dtype=torch.float32, device="cuda")
+    p = ngc.make_params(noise_scale=1.0, round=2, seed=w.gumbel_seed, flags=ngc.EVICT_POOL_HEADS | ngc.EVICT_SELECT_ONLY)
+    print(f"[evict] pooled, wide range, {kind}", flush=True)
+    ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+    torch.cuda.synchronize()
+    assert all(x == 0 for x in ngc.read_status(ws))
+    hsig, hlp = sigma.cpu().numpy(), logp.cpu().numpy()
+    for b in range(w.B):
+        heads = [case.logits[(0, b, h)] for h in range(w.Hkv)]
+        K_total = int(case.keep[0, b].sum())
+        okept, osig, cat, osig_idx = orc.evict_select_pooled(heads, K_total, 1.0, w.gumbel_seed, 2, 0, b)
+        got_sig = hsig[0, b].reshape(-1)[:K_total]
+        assert got_sig.tolist() == [h * w.cap + t for h, t in osig], b
+        want = orc.logprob_literal(cat, osig_idx)
+        assert np.isfinite(want)
+        assert hlp[0, b, 0] == pytest.approx(want, rel=LOGP_RTOL, abs=1e-5), (b, hlp[0, b, 0], want)
