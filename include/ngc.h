@@ -32,8 +32,9 @@
  *   - The caller owns every buffer.  The library allocates nothing, keeps no
  *     state between calls (the workspace holds, besides the status words, per-
  *     segment tickets that every launch leaves at zero: zero the workspace once
- *     before its first use and do not share it between calls that overlap in
- *     time) and never synchronises: each call only enqueues
+ *     before its first use, again before it serves a cache of another geometry
+ *     (its layout follows the geometry), and do not share it between calls that
+ *     overlap in time) and never synchronises: each call only enqueues
  *     kernels on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  Ragged lengths and keep counts are read on the device.
  *   - Return value: NGC_OK or a negative NGC_E* code; nothing is enqueued when
@@ -322,11 +323,15 @@ int ngc_decode_step(const ngc_cache *c, int32_t layer, const void *k_new, const 
  *            the anomaly counters (zeroed by the caller, only added to), or
  *            NULL to drop them.
  * Returns NGC_ENOSPC, and enqueues nothing, when the call would need more than
- * the fixed array: the partials take
- *     256 + 12 * L * B * Hkv + S * nseg * (Hq / Hkv) * (D + 2) * 4 bytes (plus
- *     alignment), nseg = segments of the launch, S = splits per segment (1 when
- *     nseg >= 512 or the rows per segment <= 1023, else up to min(ceil(512 /
- *     nseg), rows / 512, 64)).
+ * the fixed array: 4096 bytes of status words and tickets plus
+ *     S * nseg * (Hq / Hkv) * (D + 2) * 4 bytes (plus alignment) of partials,
+ *     nseg = segments of the launch, S = workgroups per segment as
+ *     ngc_decode_attn chooses them (1 for more than 128 segments, else at most
+ *     min(256 / nseg, 64)) -- i.e. only 16 query heads per KV head at D = 128
+ *     over 240 or more workgroups exceed it; ngc_decode_attn with a workspace
+ *     takes those.
+ * The layout inside the array does not depend on the cache's geometry, so caches
+ * of different shapes can be served one after the other.
  * The call itself allocates nothing and calls no allocating routine; the first
  * call on a device looks up the array's address (make that call outside graph
  * capture).  All calls on one GPU share the array: calls that overlap in time
@@ -334,7 +339,7 @@ int ngc_decode_step(const ngc_cache *c, int32_t layer, const void *k_new, const 
  * serialised by the caller.  Nothing in the array has to be cleared by anyone:
  * every partial a launch reads was written by that launch, and the per-segment
  * tickets (zero when the image is loaded) are back at zero when a launch ends. */
-#define NGC_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+#define NGC_STATIC_SCRATCH_BYTES ((size_t)2 << 20)
 int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const void *q, float scale,
                            int32_t max_len_hint, float *out, float *lse_out,
                            int32_t *status, void *stream);

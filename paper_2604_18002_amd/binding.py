@@ -39,7 +39,7 @@ EXPORTS = ("ngc_version", "ngc_strerror", "ngc_workspace_bytes", "ngc_perturbed_
            "ngc_subset_logprob_backward", "ngc_replay_attn", "ngc_replay_workspace_bytes",
            "ngc_paged_workspace_bytes", "ngc_paged_evict", "ngc_paged_append", "ngc_paged_decode_attn",
            "ngc_paged_score_keys", "ngc_lmem", "ngc_keep_counts", "ngc_decode_attn_static", "ngc_decode_step")
-STATIC_SCRATCH_BYTES = 16 << 20
+STATIC_SCRATCH_BYTES = 2 << 20
 
 
 class NgcError(RuntimeError):
@@ -265,7 +265,7 @@ def ngc_decode_attn_static(cache: Cache, layer: int, q, scale: float, max_len_hi
     v = cache.view()
     _check(load_library().ngc_decode_attn_static(C.byref(v), layer, _ptr(q), scale, max_len_hint, _ptr(out),
                                                  _ptr(lse_out), _ptr(status), _stream(stream)),
-           "ngc_decode_attn_static", "ngc_decode_step")
+           "ngc_decode_attn_static")
 
 
 def ngc_score_keys(cache: Cache, layer: int, q_recent, w: int, scale: float, flags: int, block: int,

@@ -78,7 +78,7 @@ struct AttnArgs {
     int max_pages;
     int num_pages;
     int tpp_shift;          // log2(tiles per page)
-    int32_t *ticket;        // [segments of the cache] workgroups of a segment that are done; 0 between launches
+    int32_t *ticket;        // [segments of the launch] workgroups of a segment that are done; 0 between launches
     // fused append (APPEND kernels only)
     unsigned char *k_rw;    // the cache again, writable
     unsigned char *v_rw;
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
     auto took_last_ticket = [&]() -> bool {
         __syncthreads();   // this workgroup's partial stores have been waited for by their threads
         if (threadIdx.x == 0) {
-            const int old = __hip_atomic_fetch_add(&a.ticket[seg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int old = __hip_atomic_fetch_add(&a.ticket[seg_local], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             is_last = (old == a.S - 1) ? 1 : 0;
         }
         __syncthreads();
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void decode_kernel(AttnArgs a)
     // the appended row becomes part of the segment.
     auto close_segment = [&]() {
         if (threadIdx.x == 0) {
-            if (a.S > 1) __hip_atomic_store(&a.ticket[seg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.S > 1) __hip_atomic_store(&a.ticket[seg_local], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (APPEND && grew) a.len_rw[seg] = n;
         }
     };
@@ -641,9 +641,15 @@ struct NewRows {            // fused append: the new token's rows, or all null
     const int32_t *new_pos;
 };
 
+// `fixed_layout`: the scratch is not a workspace sized for this cache but the library's own fixed array, which
+// serves caches of any geometry one after the other: tickets and partials then sit at offsets that do not depend
+// on the geometry (a ticket region that moved with the geometry would land on an earlier call's partials).
+constexpr size_t FIXED_TICKET_OFFSET = STATUS_BYTES;      // COMPUTE_UNITS tickets: only launches of at most
+constexpr size_t FIXED_PARTIAL_OFFSET = 4096;             // COMPUTE_UNITS / 2 segments are ever split
+
 int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, const NewRows *nr, const void *q,
                   float scale, int32_t max_len_hint, float *out, float *lse_out, int32_t *status, void *ws,
-                  size_t ws_bytes, void *stream)
+                  size_t ws_bytes, void *stream, bool fixed_layout = false)
 {
     if (nr && (!nr->k_new || !nr->v_new || !aligned16(nr->k_new) || !aligned16(nr->v_new) || pc)) return NGC_EINVAL;
     if (!c->k || !c->v || !c->len || !q || !out || !ws) return NGC_EINVAL;
@@ -659,9 +665,14 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     const int nseg = layer < 0 ? c->L * per_layer : per_layer;
     const int max_len = (max_len_hint > 0 && max_len_hint < c->cap) ? max_len_hint : c->cap;
     int S = splits_for(nseg, max_len, c->D * 2);
-    const size_t off = attn_offset(c);
+    if (nseg > COMPUTE_UNITS) S = 1;   // (what splits_for() returns anyway: the fixed ticket region relies on it)
+    const size_t off = fixed_layout ? FIXED_PARTIAL_OFFSET : attn_offset(c);
     if (ws_bytes < off) return NGC_ENOSPC;
-    while (S > 1 && ws_bytes < off + attn_partial_bytes(c, nseg, S)) --S;   // fewer splits: same result, less scratch
+    if (fixed_layout) {   // the fixed array either holds what the launch wants or the call is refused
+        if (ws_bytes < off + attn_partial_bytes(c, nseg, S)) return NGC_ENOSPC;
+    } else {
+        while (S > 1 && ws_bytes < off + attn_partial_bytes(c, nseg, S)) --S;   // fewer splits: same result, less scratch
+    }
     if ((long long)nseg * S > 0x7FFFFFFFLL) return NGC_EUNSUPPORTED;
 
     AttnArgs aa;
@@ -680,7 +691,8 @@ int launch_decode(const ngc_cache *c, const ngc_paged_cache *pc, int32_t layer, 
     aa.lb0 = layer < 0 ? 0 : layer * c->B;
     aa.S = S; aa.G = c->Hq / c->Hkv; aa.Hkv = c->Hkv; aa.cap = c->cap;
     aa.scale_log2e = scale * 1.4426950408889634f;
-    aa.ticket = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) + ticket_offset(c));
+    aa.ticket = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(ws) +
+                                            (fixed_layout ? FIXED_TICKET_OFFSET : ticket_offset(c)));
     aa.k_rw = reinterpret_cast<unsigned char *>(c->k);
     aa.v_rw = reinterpret_cast<unsigned char *>(c->v);
     aa.len_rw = c->len;
@@ -771,7 +783,7 @@ extern "C" int ngc_decode_attn_static(const ngc_cache *c, int32_t layer, const v
     const int rc = static_scratch(&ws);
     if (rc) return rc;
     return launch_decode(c, nullptr, layer, nullptr, q, scale, max_len_hint, out, lse_out, status, ws,
-                         STATIC_SCRATCH_BYTES, stream);
+                         STATIC_SCRATCH_BYTES, stream, true);
 }
 
 extern "C" int ngc_paged_decode_attn(const ngc_paged_cache *pc, int32_t layer, const void *q, float scale,

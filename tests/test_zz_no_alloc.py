@@ -44,6 +44,11 @@ def _both(ngc, w, cache, q, hint):
     assert rc == 0
     torch.cuda.synchronize()
     assert status.cpu().tolist() == ngc.read_status(ws)
+    # the Python binding of the same entry point (marshalling only) gives the same bits
+    again = torch.full_like(ref, -9.0)
+    ngc.ngc_decode_attn_static(cache, 0, q, scale, hint, again)
+    torch.cuda.synchronize()
+    assert torch.equal(again, got)
     return ref.cpu().numpy(), got.cpu().numpy(), ref_lse.cpu().numpy(), got_lse.cpu().numpy()
 
 
@@ -73,13 +78,30 @@ def test_static_entry_point_matches_the_workspace_one_twice_in_a_row():
 
 
 def test_static_entry_point_rejects_what_does_not_fit():
-    """A geometry whose partials exceed the fixed array is refused on the host with NGC_ENOSPC (nothing is enqueued)."""
+    """A launch whose partials exceed the fixed array is refused on the host with NGC_ENOSPC (nothing is enqueued)."""
     import torch
     from paper_2604_18002_amd import binding as ngc
     lib = ngc.load_library()
-    # 300 segments of up to 65536 rows would be cut into 2 splits each with 16 heads x 128: fine; but the segment
-    # table alone (8 bytes per segment of the whole cache) exceeds 16 MiB for L * B * Hkv = 4M segments
+    # 128 segments per layer, 2 workgroups each, 16 query heads per KV head at D = 128:
+    # 256 * 16 * 130 * 4 bytes = 2.13 MB of partials, more than the 2 MiB array
     A = 0x10000   # made-up aligned device address: the call is refused before anything is enqueued
-    c = ngc.ngc_cache(A, A, A, None, 4096, 512, 2, 12, 128, 64)
+    c = ngc.ngc_cache(A, A, A, None, 2, 32, 4, 64, 128, 2048)
+    assert 4096 + 128 * 2 * 16 * 130 * 4 > ngc.STATIC_SCRATCH_BYTES
     rc = lib.ngc_decode_attn_static(C.byref(c), 0, A, 0.1, 0, A, None, None, torch.cuda.current_stream().cuda_stream)
     assert rc == ngc.NGC_ENOSPC
+    assert "fixed scratch" in ngc.strerror(rc)
+
+
+def test_static_entry_point_serves_caches_of_different_geometry_one_after_the_other():
+    """The array's layout does not depend on the cache: a call with many segments after one with few (and back)
+    finds its tickets at zero, not on the other call's partials."""
+    from paper_2604_18002_amd import binding as ngc
+    ngc.load_library()
+    for over in (dict(B=2, n_lo=3000, n_hi=4000), dict(B=16, n_lo=900, n_hi=1100), dict(B=1, n_lo=2000, n_hi=2100),
+                 dict(B=24, n_lo=700, n_hi=1300), dict(B=3, n_lo=3000, n_hi=3100)):
+        print(f"[static] geometry {over}", flush=True)
+        w, cache, q = _case(1, **over)
+        ref, got, ref_lse, got_lse = _both(ngc, w, cache, q, 0)
+        assert np.all(np.isfinite(got))
+        assert np.array_equal(got, ref)
+        assert np.array_equal(got_lse, ref_lse)
