@@ -217,3 +217,45 @@ def test_random_workloads_through_the_other_parity_checks(ci):
                                   D=D, period=int(rng.choice([7, 16, 50, 128, 350])),
                                   keep=float(rng.choice([0.1, 0.5, 0.9])), per_head=bool(rng.integers(0, 2)),
                                   block=int(rng.choice([1, 1, 32])), B=B))
+
+
+@pytest.mark.parametrize("ci", range(24))
+def test_random_cycles_over_the_paged_layout(ci):
+    """Grow / attend / evict cycles with random page sizes, pool sizes (some too small: skipped appends are
+    counted and mirrored by the model), retention rates and single-layer rounds, against the numpy model of
+    tables, pools and free stack."""
+    import test_gpu_paged as TP
+    rng = np.random.default_rng(9_500_000 + ci)
+    ngc = TP._ngc()
+    Hkv, G, D = int(rng.integers(1, 4)), int(rng.choice([1, 2, 6, 7])), int(rng.choice([64, 128]))
+    L, B = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    P = int(rng.choice([32, 32, 64, 128]))
+    hi = int(rng.choice([40, 200, 700, 1500]))
+    lo = int(rng.integers(1, hi + 1))
+    wl = synth.workload(1, L=L, B=B, Hkv=Hkv, Hq=Hkv * G, D=D, n_lo=lo, n_hi=hi)
+    case = H.host_case(wl)
+    grow, rounds = int(rng.integers(1, 70)), int(rng.integers(1, 4))
+    max_pages = (hi + grow * rounds + P - 1) // P + int(rng.integers(0, 3))
+    nseg = L * B * Hkv
+    if rng.integers(0, 4) == 0:     # a pool that runs dry
+        num_pages = max(nseg, int(nseg * ((hi + P - 1) // P) + rng.integers(0, nseg + 1)))
+    else:
+        num_pages = nseg * max_pages
+    tau, frac = float(rng.choice([0.0, 1.0, 1.0])), float(rng.choice([0.1, 0.5, 0.9, 1.0]))
+    print(f"[random paged] L={L} B={B} Hkv={Hkv} G={G} D={D} P={P} n={lo}..{hi} grow={grow} rounds={rounds} "
+          f"max_pages={max_pages} num_pages={num_pages} tau={tau} keep={frac}", flush=True)
+    m = TP.build_model(case, P, max_pages, num_pages, seed=ci)
+    pc = TP.upload_model(m, wl)
+    ws = ngc.allocate_paged_workspace(pc)
+    step = 0
+    for rnd in range(rounds):
+        for _ in range(grow):
+            TP.append_step(pc, m, wl, ws, step)
+            step += 1
+        TP.assert_same_state(pc, m, wl, f"after growth {rnd}")
+        TP.check_attention(pc, m, wl, ws, -1, 20 + rnd, lse=bool(rng.integers(0, 2)))
+        layer = -1 if rng.integers(0, 2) else int(rng.integers(0, L))
+        TP.run_round(pc, m, wl, ws, rnd, lambda N: max(0 if frac < 0.2 else 1, int(np.ceil(N * frac))), tau=tau,
+                     layer=layer, share_heads=int(rng.integers(0, 2)))
+        TP.assert_same_state(pc, m, wl, f"after round {rnd}")
+    TP.check_attention(pc, m, wl, ws, -1, 99)
