@@ -76,7 +76,7 @@ def parse_args():
                          "own runs (latency-bound, see --per-layer)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (0 = the workload's)")
-    ap.add_argument("--evict-reps", type=int, default=5, help="timed repetitions of the round-0 eviction")
+    ap.add_argument("--evict-reps", type=int, default=10, help="timed repetitions of the round-0 eviction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", default=True,
                     help="also time decode attention launched layer by layer, eagerly and from a HIP graph (default)")
