@@ -66,7 +66,9 @@ extern "C" {
 
 /* Status words: int32 counters at the start of the workspace, one per kind of
  * device-detected anomaly.  The caller zeroes the workspace once; kernels only
- * add to them.  NGC_STATUS_WORDS words are reserved. */
+ * add to them.  NGC_STATUS_WORDS words are reserved; the last two are the
+ * library's own (the work counter of the eviction kernel and a count of its
+ * finished workgroups: both zero again when a launch has ended). */
 #define NGC_STATUS_WORDS        64
 #define NGC_STATUS_KEEP_CLAMPED  0  /* keep[seg] > items (or < 0): clamped                  */
 #define NGC_STATUS_LEN_CLAMPED   1  /* len[seg] > cap (or < 0): clamped                     */

@@ -114,6 +114,7 @@ struct SelectArgs {
     int32_t *len_out;
     int unordered;       // 1: fill the holes below K with the kept rows beyond K (block == 1 only)
     int seg0;
+    int nseg;            // segments of the launch (the persistent eviction kernel hands them out one by one)
     int max_keep;
     int items_cap;       // ceil(cap / block): size of the code array in LDS
     int keep_cap;        // size of each index buffer in LDS
@@ -122,6 +123,11 @@ struct SelectArgs {
     SegGeom g;
     NoiseArgs na;
 };
+
+// The last two status words of the workspace are the library's own: a work counter and a count of finished
+// workgroups of the eviction kernel, both zero between launches.
+constexpr int WS_QUEUE_NEXT = NGC_STATUS_WORDS - 2;
+constexpr int WS_QUEUE_DONE = NGC_STATUS_WORDS - 1;
 
 constexpr int SMALL_ITEMS = 256;             // at most this many items: selection by ranking
 constexpr int SORT_BITS = 9;                 // digit width of the sigma sort

@@ -195,6 +195,50 @@ def test_select_only_moves_nothing():
     assert (cache.len.cpu().numpy() == case.lens[None, :, None]).all()
 
 
+def test_more_large_segments_than_resident_workgroups():
+    # Segments of more than 4096 items go to workgroups that fill a compute unit and fetch one segment after
+    # another from a counter in the workspace: 640 segments on 256 compute units, so most workgroups take
+    # several.  Two calls on the same workspace (the counters must be back at zero in between): selection
+    # only, then the full round; the same noise, so both must give the oracle's lists.
+    import torch
+    ngc = _ngc()
+    w = synth.workload(1, L=2, B=160, Hkv=2, Hq=4, D=64, n_lo=4097, n_hi=4400)
+    segs = sorted({(0, 0, 0), (w.L - 1, w.B - 1, w.Hkv - 1), (0, 128, 0), (1, 0, 1), (1, 77, 0), (0, 159, 1),
+                   (1, 130, 1), (0, 64, 1)})
+    case = host_case(w, segs)
+    max_keep = int(case.keep.max())
+    cache = ngc.Cache.allocate(w.L, w.B, w.Hkv, w.Hq, w.D, w.cap, with_pos=True)
+    synth.fill_normal_bf16_(cache.k, 11)
+    synth.fill_normal_bf16_(cache.v, 12)
+    cache.pos.copy_(torch.arange(w.cap, dtype=torch.int32).expand(w.L, w.B, w.Hkv, w.cap))
+    logits = torch.empty(w.L, w.B, w.Hkv, w.cap, dtype=torch.float32, device="cuda")
+    synth.fill_logits_(logits, w, 13)
+    cache.len.copy_(torch.from_numpy(np.broadcast_to(case.lens[None, :, None], (w.L, w.B, w.Hkv)).copy()))
+    for seg in segs:
+        l, b, h = seg
+        n = case.k[seg].shape[0]
+        cache.k[l, b, h, :n] = to_bf16_tensor(case.k[seg], "cuda")
+        cache.v[l, b, h, :n] = to_bf16_tensor(case.v[seg], "cuda")
+        logits[l, b, h, :n] = torch.from_numpy(case.logits[seg]).cuda()
+    keep = torch.from_numpy(case.keep).cuda()
+    ws = ngc.allocate_workspace(cache, max_keep)
+    for select_only in (True, False):
+        kept = torch.full((w.L, w.B, w.Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+        sigma = torch.full_like(kept, -1)
+        logp = torch.full((w.L, w.B, w.Hkv), float("nan"), dtype=torch.float32, device="cuda")
+        p = ngc.make_params(noise_scale=1.0, round=2, seed=w.gumbel_seed,
+                            flags=ngc.EVICT_SELECT_ONLY if select_only else 0)
+        print(f"[evict] {w.L * w.B * w.Hkv} segments of up to {w.cap} rows, select_only={select_only}", flush=True)
+        ngc.ngc_evict(cache, -1, logits, keep, p, max_keep, kept, sigma, logp, ws)
+        torch.cuda.synchronize()
+        assert all(x == 0 for x in ngc.read_status(ws))   # includes the two queue words
+        _check_against_oracle(case, cache, kept, sigma, logp, 1.0, 2, segs=segs, moved=not select_only)
+        # every segment was served exactly once: all lists filled, all log-probabilities written
+        valid = torch.arange(max_keep, device="cuda") < keep.unsqueeze(-1)
+        assert bool(((kept >= 0) | ~valid).all()) and bool(torch.isfinite(logp).all())
+    assert torch.equal(cache.len.cpu(), torch.from_numpy(case.keep))
+
+
 def test_no_sigma_no_logp_fast_path():
     w = synth.workload(1, B=3)
     case = host_case(w)
