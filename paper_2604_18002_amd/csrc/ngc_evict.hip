@@ -1121,8 +1121,10 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     keep_cap = (keep_cap + 7) & ~7;
     const int items_cap_al = (items_cap + 3) & ~3;
     // workgroup size and rows in flight per thread, measured on configs 2-4 (selection wants few large workgroups
-    // for large segments; the copy wants as many bytes in flight per compute unit as registers allow)
-    const int threads = items_cap > 4096 ? 1024 : (items_cap > 2048 ? 512 : 256);
+    // for large segments; the copy wants as many bytes in flight per compute unit as registers allow).  The size
+    // follows the rows of a segment, not its items: with blocks of rows as items the selection is small and the
+    // copy is all there is
+    const int threads = c->cap > 4096 ? 1024 : (c->cap > 2048 ? 512 : 256);
     const size_t lds = select_lds_bytes(threads, items_cap_al, keep_cap);
     if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
 
