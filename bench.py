@@ -159,7 +159,7 @@ def layer_step_calls(ngc, cache, k_new, v_new, q, scale, hint, out, ws):
     return run
 
 
-def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
+def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3, with_ceiling=False):
     """Round-0 and steady-state eviction, and decode steps at `samples` lengths spread over a period (one launch
     per layer, and all layers in one launch), of one workload; a few seconds."""
     import torch
@@ -258,7 +258,14 @@ def quick_config(ngc, synth, w, dev, samples=32, evict_reps=3):
     status = ngc.read_status(ws)
     assert all(x == 0 for x in status), f"config {w.index}: device status words not clean: {status[:8]}"
     p1_ms, st_ms = float(np.mean(p1)), float(np.mean(steady[1:]))
+    read_at = None
+    if with_ceiling:
+        from paper_2604_18002_amd import probe
+        read_at = probe.read_ceiling_at(int(pl_b / len(offs) / w.L), w.L)
     return {
+        "decode_per_layer_frac_of_read_probe_at_launch_size":
+            (pl_b / (pl_ms * 1e-3) / 1e9 / read_at["GBs"]) if read_at else None,
+        "read_probe_at_decode_launch_size": read_at,
         "workload": f"configs[{w.index}] {w.name}: L={w.L} B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} peak cache "
                     f"{w.n_lo}..{w.n_hi}, keep {w.keep_num}/{w.keep_den}, delta={w.delta}",
         "eviction_step_us": 1e3 * p1_ms, "eviction_hbm_frac": p1_bytes / (p1_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -570,6 +577,9 @@ def main():
     tokens = w.B * w.delta * args.steps
     value = tokens / elapsed
     attn_gbs = attn_b / (attn_ms * 1e-3) / 1e9
+    # what the plainest read kernel reaches when it is launched the same way: one launch of a layer's bytes after
+    # the other, every launch over memory no earlier launch has touched
+    read_at = probe.read_ceiling_at(int(attn_b / n_attn / w.L), w.L) if ceilings is not None else None
     p1_gbs = p1_bytes / (p1_us * 1e-6) / 1e9
 
     # ---- secondary: the same decode steps with all layers in ONE launch (what the kernel does when the launch is
@@ -955,7 +965,7 @@ def main():
         for idx in (2, 3, 4):
             if idx == w.index:
                 continue
-            other[str(idx)] = quick_config(ngc, synth, synth.workload(idx), dev)
+            other[str(idx)] = quick_config(ngc, synth, synth.workload(idx), dev, with_ceiling=ceilings is not None)
             torch.cuda.empty_cache()
 
     line = {
@@ -996,6 +1006,8 @@ def main():
                               "stream) divided by L: includes the gaps between launches",
             "frac_of_measured_read_ceiling": (attn_gbs / max(ceilings["read_GBs"], ceilings["read_nontemporal_GBs"])
                                               if ceilings else None),
+            "frac_of_read_probe_at_launch_size": (attn_gbs / read_at["GBs"]) if read_at else None,
+            "read_probe_at_launch_size": read_at,
         },
         "roofline_decode_all_layers_per_launch": {
             "what": "the same decode steps with all layers in one launch (a model cannot issue this; it shows the kernel "

@@ -120,6 +120,38 @@ def streaming_ceilings(nbytes: int = 8 << 30) -> dict:
     return out
 
 
+def read_ceiling_at(nbytes: int, launches: int, span: int = 8 << 30, trains: int = 6) -> dict:
+    """Rate of the plain nontemporal read probe when it runs the way a per-layer kernel does: trains of `launches`
+    back-to-back launches of `nbytes` bytes each, every launch over the next region of a `span`-byte buffer (so no
+    launch finds its bytes in a cache), HIP events around each train.  A launch of a few hundred MB does not reach
+    the rate of one long stream; this is the figure a kernel of that launch size can be held against."""
+    import torch
+    nbytes = max(4096, int(nbytes) & ~4095)
+    src = torch.empty(span, dtype=torch.uint8, device="cuda")
+    sink = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    regions = max(1, span // nbytes)
+    nxt = 0
+    ms = []
+    for t in range(trains + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            ngc_probe_stream(READ_NT, src[nxt * nbytes:], sink, nbytes)
+            nxt = (nxt + 1) % regions
+        e1.record()
+        torch.cuda.synchronize()
+        if t:   # the first train is the warm-up
+            ms.append(e0.elapsed_time(e1) / launches)
+    del src, sink
+    torch.cuda.empty_cache()
+    mean = sum(ms) / len(ms)
+    return {"bytes_per_launch": nbytes, "launches_per_train": launches, "trains": trains,
+            "us_per_launch": 1e3 * mean, "GBs": nbytes / (mean * 1e-3) / 1e9,
+            "what": "plain nontemporal read probe, trains of back-to-back launches of this size over successive regions "
+                    "of a %d GiB buffer, events around each train" % (span >> 30)}
+
+
 def compaction_case(nseg: int, cap: int, n_lo: int, n_hi: int, num: int, den: int, seed: int = 12345):
     """Synthetic kept lists of the shape of a benchmark configuration: segment lengths uniform in [n_lo, n_hi],
     ceil(n num / den) rows kept, uniformly at random, ascending.  Returns (kept int32 [nseg, max_keep],

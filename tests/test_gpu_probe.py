@@ -34,6 +34,17 @@ def test_probe_kinds(nbytes):
         probe.ngc_probe_stream(9, src, src, 16)
 
 
+def test_read_ceiling_at_a_launch_size():
+    # trains of small launches over successive regions of a small buffer: sizes are rounded down to 4 KB, the
+    # regions stay inside the buffer, and the figure is a positive rate below the vendor's peak
+    from paper_2604_18002_amd import probe
+    r = probe.read_ceiling_at((3 << 20) + 1234, launches=5, span=16 << 20, trains=2)
+    assert r["bytes_per_launch"] == (3 << 20) and r["launches_per_train"] == 5
+    assert 0 < r["GBs"] < 8000 and r["us_per_launch"] > 0
+    r = probe.read_ceiling_at(100, launches=2, span=1 << 20, trains=1)       # below one page: 4 KB
+    assert r["bytes_per_launch"] == 4096
+
+
 @pytest.mark.parametrize("threads,unroll,pipelined", [(256, 4, False), (256, 16, False), (512, 8, True), (1024, 4, True),
                                                       (1024, 8, False), (1024, 16, False)])
 def test_copy_shapes_copy(threads, unroll, pipelined):
