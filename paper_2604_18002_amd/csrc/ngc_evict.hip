@@ -1120,16 +1120,21 @@ extern "C" int ngc_evict(const ngc_cache *c, int32_t layer, const float *logits,
     int keep_cap = max_keep < items_cap ? max_keep : items_cap;
     keep_cap = (keep_cap + 7) & ~7;
     const int items_cap_al = (items_cap + 3) & ~3;
-    // workgroup size and rows in flight per thread, measured on configs 2-4 (selection wants few large workgroups
-    // for large segments; the copy wants as many bytes in flight per compute unit as registers allow).  The size
-    // follows the rows of a segment, not its items: with blocks of rows as items the selection is small and the
-    // copy is all there is
-    const int threads = c->cap > 4096 ? 1024 : (c->cap > 2048 ? 512 : 256);
+    // Workgroup size and rows in flight per thread, measured on configs 2-4.  A round that moves rows in order
+    // is a copy with a selection in front: the copy wants as many bytes in flight per compute unit as registers
+    // allow, which is one 1024-thread workgroup per CU from 4097 rows per segment up (the size follows the rows
+    // of a segment, not its items: with blocks of rows as items the selection is small and the copy is all there
+    // is).  A round that only selects, or fills holes (few rows move), is bound by the selection's ~45 workgroup
+    // barriers; two 512-thread workgroups per CU then cover each other's waits, up to the 8192 rows at which two
+    // of them still fit in LDS (config 3, selection only: 1.79 -> 1.14 ms, steady-state 1.46 -> 0.84 ms;
+    // unordered: 4.54 -> 4.18 and 2.17 -> 1.53 ms).
+    const bool move_rows = !(p->flags & NGC_EVICT_SELECT_ONLY);
+    const bool copy_bound = move_rows && !(p->flags & NGC_EVICT_UNORDERED);
+    const int threads = c->cap > (copy_bound ? 4096 : 8192) ? 1024 : (c->cap > 2048 ? 512 : 256);
     const size_t lds = select_lds_bytes(threads, items_cap_al, keep_cap);
     if (lds > 160 * 1024) return NGC_EUNSUPPORTED;
 
     int32_t *status = reinterpret_cast<int32_t *>(ws);
-    const bool move_rows = !(p->flags & NGC_EVICT_SELECT_ONLY);
 
     SelectArgs sa;
     sa.logits = logits; sa.len = c->len; sa.keep = keep;
