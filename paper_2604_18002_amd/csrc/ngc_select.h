@@ -80,7 +80,7 @@ __device__ __forceinline__ void keys_of_quad(const float *row, int n_items, int 
 
 // ------------------------------------------------------------- select -----
 //
-// One workgroup per segment.  LDS holds the order-preserving code of every
+// One workgroup works on one segment at a time.  LDS holds the order-preserving code of every
 // perturbed key (4 B per item), two index buffers for the sort of the kept
 // items (2 B per kept item each) and a histogram area.
 //
