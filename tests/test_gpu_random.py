@@ -110,6 +110,106 @@ def _values(rng, shape, kind):
 VALUE_KINDS = ["normal", "sharp", "constant", "zeros", "big", "tiny", "one hot"]
 
 
+@pytest.mark.parametrize("ci", range(16))
+def test_random_rounds_with_more_large_segments_than_workgroups(ci):
+    # Segments of more than 4096 rows, several hundred of them: the workgroups of the round take one segment after
+    # another from a counter.  Lengths include 0, 1 and the full capacity, keep counts 0 and everything; a sample
+    # of segments is generated on the host and compared with the oracle, every segment is held to what must be
+    # true of any round (kept ascending and in range, sigma a permutation of kept, a log-probability written).
+    import torch
+    from paper_2604_18002_amd import binding as ngc
+    ngc.load_library()
+    rng = np.random.default_rng(9_000_000 + ci)
+    L, Hkv = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    B = int(rng.integers(257, 700)) // (L * Hkv) + 1
+    G, D = int(rng.choice([1, 2, 7])), int(rng.choice([64, 128]))
+    cap = int(rng.choice([4097, 5000, 8192, 12000, 16384]))
+    block = int(rng.choice([1, 1, 32]))
+    mode = str(rng.choice(["ordered", "ordered", "select_only", "unordered"])) if block == 1 else "ordered"
+    tau = float(rng.choice([0.0, 1.0, 1.0]))
+    kind = LOGIT_KINDS[ci % len(LOGIT_KINDS)]
+    w = synth.workload(0, L=L, B=B, Hq=Hkv * G, Hkv=Hkv, D=D, n_lo=cap, n_hi=cap, fixed_keep=None)
+    lens = np.array([int(rng.choice([0, 1, cap, cap - 1, int(rng.integers(0, cap + 1)),
+                                     int(rng.integers(cap // 2, cap + 1))])) for _ in range(B)])
+    segs = [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)]
+    pick = sorted({segs[0], segs[-1], *[segs[int(i)] for i in rng.integers(0, len(segs), 5)]})
+    items_b = (lens + block - 1) // block
+    keep = np.zeros((L, B, Hkv), np.int32)
+    for (l, b, h) in segs:
+        it = int(items_b[b])
+        keep[l, b, h] = min(16000, it, int(rng.choice([0, 1, it, max(it - 1, 0), it // 2, (2 * it) // 5,
+                                                         int(rng.integers(0, it + 1))])))
+    k, v, lg = {}, {}, {}
+    for seg in pick:
+        l, b, h = seg
+        k[seg], v[seg] = synth.segment_kv(w, l, b, h, int(lens[b]))
+        lg[seg] = _logits(rng, int(items_b[b]), kind)
+        if lg[seg].size * int(keep[seg]) > 6_000_000:      # the oracle's term-by-term Eq. 2 costs n * K
+            keep[seg] = min(int(keep[seg]), max(1, 6_000_000 // lg[seg].size))
+    case = H.HostCase(w, lens, keep, pick, k, v, lg)
+    max_keep = max(int(keep.max()), 1)
+    print(f"[random] L={L} B={B} Hkv={Hkv} D={D} cap={cap} block={block} mode={mode} tau={tau} kind={kind}", flush=True)
+    cache = ngc.Cache.allocate(L, B, Hkv, Hkv * G, D, cap)
+    synth.fill_normal_bf16_(cache.k, 11 + ci)
+    synth.fill_normal_bf16_(cache.v, 12 + ci)
+    logits = torch.randn(L, B, Hkv, cap, device="cuda")
+    cache.len.copy_(torch.from_numpy(np.broadcast_to(lens[None, :, None], (L, B, Hkv)).astype(np.int32).copy()))
+    for seg in pick:
+        l, b, h = seg
+        n = k[seg].shape[0]
+        if n:
+            cache.k[l, b, h, :n] = H.to_bf16_tensor(k[seg], "cuda")
+            cache.v[l, b, h, :n] = H.to_bf16_tensor(v[seg], "cuda")
+        logits[l, b, h, :lg[seg].size] = torch.from_numpy(lg[seg]).cuda()
+    keep_t = torch.from_numpy(keep).cuda()
+    ws = ngc.allocate_workspace(cache, max_keep)
+    kept = torch.full((L, B, Hkv, max_keep), -1, dtype=torch.int32, device="cuda")
+    sigma = torch.full_like(kept, -1)
+    logp = torch.full((L, B, Hkv), float("nan"), dtype=torch.float32, device="cuda")
+    flags = {"ordered": 0, "select_only": ngc.EVICT_SELECT_ONLY, "unordered": ngc.EVICT_UNORDERED}[mode]
+    rnd = int(rng.integers(0, 1000))
+    p = ngc.make_params(block=block, noise_scale=tau, round=rnd, seed=w.gumbel_seed, flags=flags)
+    for _ in range(2 if mode == "select_only" else 1):     # twice on one workspace where nothing moves
+        ngc.ngc_evict(cache, -1, logits, keep_t, p, max_keep, kept, sigma, logp, ws)
+        torch.cuda.synchronize()
+        assert all(x == 0 for x in ngc.read_status(ws))
+
+    def rows(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    hkept, hsig, hlp, hlen = kept.cpu().numpy(), sigma.cpu().numpy(), logp.cpu().numpy(), cache.len.cpu().numpy()
+    for seg in pick:
+        l, b, h = seg
+        if lens[b] == 0:
+            assert hlen[l, b, h] == 0
+            continue
+        okept, osig, olp, ok_, ov_ = H.oracle_evict_segment(case, seg, tau, w.gumbel_seed, rnd, block, False)
+        K = okept.size
+        assert hkept[l, b, h, :K].tolist() == okept.tolist(), seg
+        assert hsig[l, b, h, :K].tolist() == osig.tolist(), seg
+        if np.isfinite(olp):
+            assert hlp[l, b, h] == pytest.approx(olp, rel=TE.LOGP_RTOL, abs=1e-5), seg
+        if mode == "ordered":
+            n_new = ok_.shape[0]
+            assert hlen[l, b, h] == n_new, seg
+            assert rows(cache.k[l, b, h, :n_new]).tobytes() == ok_.tobytes(), seg
+            assert rows(cache.v[l, b, h, :n_new]).tobytes() == ov_.tobytes(), seg
+        elif mode == "unordered":
+            assert hlen[l, b, h] == K
+            got = rows(cache.k[l, b, h, :K])
+            assert {got[j].tobytes() for j in range(K)} == {k[seg][int(t)].tobytes() for t in okept}, seg
+        else:
+            assert hlen[l, b, h] == lens[b]
+    slot = torch.arange(max_keep, device="cuda")
+    n0 = torch.from_numpy(np.broadcast_to(items_b[None, :, None], keep.shape).astype(np.int32).copy()).cuda()
+    valid = slot < keep_t.unsqueeze(-1)
+    assert bool(((kept[..., 1:] > kept[..., :-1]) | ~valid[..., 1:]).all())
+    assert bool((((kept >= 0) & (kept < n0.unsqueeze(-1))) | ~valid).all())
+    ssort = torch.where(valid, sigma, torch.full_like(sigma, 2 ** 30)).sort(dim=-1).values
+    assert torch.equal(ssort, torch.where(valid, kept, torch.full_like(kept, 2 ** 30)))
+    assert not bool(torch.isnan(logp).any())
+
+
 @pytest.mark.parametrize("ci", range(48))
 def test_random_decode_attention(ci):
     """ngc_decode_attn (all layers / per layer), ngc_decode_attn_static and ngc_decode_step in turn, caches of
