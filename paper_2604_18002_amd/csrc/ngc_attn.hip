@@ -601,7 +601,7 @@ size_t attn_partial_bytes(const ngc_cache *c, int nseg_launch, int S)
 }
 }  // namespace
 
-extern "C" int ngc_version(void) { return 210; }
+extern "C" int ngc_version(void) { return 220; }
 
 extern "C" const char *ngc_strerror(int code)
 {
