@@ -833,7 +833,7 @@ __device__ __forceinline__ void evict_segment(const SelectArgs &a, int seg, unsi
     if (threadIdx.x == 0) a.len_out[seg] = rows_new;
 }
 
-// The 1024-thread kernel (segments of more than 4096 items) is persistent: one workgroup fills a CU, the grid
+// The 1024-thread kernel (the host picks it for large segments, see ngc_evict) is persistent: one workgroup fills a CU, the grid
 // holds as many workgroups as the chip keeps resident, and each takes the next segment from a counter in the
 // workspace until none is left.  (With one workgroup per segment, a CU waited 7 us on average -- 20 us in one
 // case out of ten -- between the end of one 1024-thread workgroup and the start of the next, with nothing else
